@@ -1,0 +1,240 @@
+"""CPU checker ("oracle") for the TableCache online path.
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product package imports this; it is
+used by ``tests/``, by ``__graft_entry__.smoke()`` and by the ``cpu_baseline``
+leg of ``bench.py``.  It shares no code with the HIP library: the fp64
+arithmetic lives in ``tc_oracle.c`` (gcc, OpenMP), the integer models
+(block allocation, cache replacement) are the plain Python below.
+
+Pieces and the passages they follow:
+
+* ``stitch``            Sec. 4.1.2 (matched tables' KV concatenated in match order)
+* ``prefill_attn``      App. E.4 (the uncached part attends to all preceding table
+                        content) with the suffix causal to itself
+* ``SeqBlockModel``     the paged-pool bookkeeping the library documents: lowest
+                        free block first, queries in batch order
+* ``LRUModel`` / ``FIFOModel`` / ``LFUModel``   App. A, the three replacement rules
+
+Parity status: every function here is pinned by ``tests/test_oracle_*.py``
+(library causal attention, closed forms, brute-force masks, position-coded
+gathers, hand-worked replacement traces under ``tests/golden/``).  What is
+not pinned, because it needs the paper's datasets, weights and engines: any
+statement about end-to-end accuracy or TTFT ("parity unpinned").
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tc_oracle.c")
+_LIB = os.path.join(_HERE, "liborc.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile tc_oracle.c with the host compiler (never hipcc)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".%d.tmp" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        lib.orc_num_threads.restype = ctypes.c_int
+        lib.orc_concat_tokens.restype = ctypes.c_int64
+        lib.orc_concat_tokens.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p,
+                                          ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p]
+        lib.orc_prefill_attn.restype = ctypes.c_int
+        lib.orc_prefill_attn.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_int32] * 5 + \
+            [ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().orc_num_threads())
+
+
+# ----------------------------------------------------------------------------- O1: gather
+
+def stitch(tables: Dict[int, np.ndarray], ids: Sequence[int]) -> np.ndarray:
+    """Stitched sequence of one query.
+
+    ``tables[t]`` is table t's K (or V) as [L][n_t][Hkv][D] in any storage type;
+    the result is [L][P][Hkv][D] with P = sum of the selected tables' lengths,
+    segments in the order of ``ids`` (a table listed twice is copied twice).
+    Byte copy, token by token, layer by layer.
+    """
+    lib = _load()
+    first = tables[int(ids[0])] if len(ids) else next(iter(tables.values()))
+    L = first.shape[0]
+    row_shape = first.shape[2:]
+    row_bytes = int(np.prod(row_shape)) * first.dtype.itemsize
+    n_tok = np.array([tables[int(t)].shape[1] for t in ids], dtype=np.int32)
+    P = int(n_tok.sum())
+    out = np.empty((L, P) + tuple(row_shape), dtype=first.dtype)
+    segs = [np.ascontiguousarray(tables[int(t)]) for t in ids]
+    for l in range(L):
+        ptrs = (ctypes.c_void_p * max(len(ids), 1))()
+        for j, s in enumerate(segs):
+            ptrs[j] = s[l].ctypes.data
+        n = lib.orc_concat_tokens(ptrs, n_tok.ctypes.data, len(ids), row_bytes,
+                                  out[l].ctypes.data if P else None)
+        assert n == P
+    return out
+
+
+# ----------------------------------------------------------------------------- O3: attention
+
+def prefill_attn(q: np.ndarray, k_seq: np.ndarray, v_seq: np.ndarray,
+                 k_new: np.ndarray, v_new: np.ndarray, sm_scale: float,
+                 return_weights: bool = False):
+    """One query, one layer, fp64.  q [S][Hq][D]; k_seq/v_seq [P][Hkv][D];
+    k_new/v_new [S][Hkv][D].  Returns out [S][Hq][D] (and the softmax weights
+    [S][Hq][P+S] when asked)."""
+    lib = _load()
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    k_seq = np.ascontiguousarray(k_seq, dtype=np.float64)
+    v_seq = np.ascontiguousarray(v_seq, dtype=np.float64)
+    k_new = np.ascontiguousarray(k_new, dtype=np.float64)
+    v_new = np.ascontiguousarray(v_new, dtype=np.float64)
+    S, Hq, D = q.shape
+    P, Hkv, _ = k_seq.shape
+    assert k_new.shape == (S, Hkv, D) and v_new.shape == (S, Hkv, D) and v_seq.shape == k_seq.shape
+    out = np.zeros((S, Hq, D), dtype=np.float64)
+    w = np.zeros((S, Hq, P + S), dtype=np.float64) if return_weights else None
+    rc = lib.orc_prefill_attn(q.ctypes.data, k_seq.ctypes.data, v_seq.ctypes.data,
+                              k_new.ctypes.data, v_new.ctypes.data, P, S, Hq, Hkv, D,
+                              float(sm_scale), out.ctypes.data,
+                              w.ctypes.data if w is not None else None)
+    if rc != 0:
+        raise RuntimeError("orc_prefill_attn failed: %d" % rc)
+    return (out, w) if return_weights else out
+
+
+def attn_row(q_row: np.ndarray, keys: np.ndarray, values: np.ndarray, sm_scale: float) -> np.ndarray:
+    """One output row from its visible keys/values ([n][D] each), fp64: the same
+    definition for spot checks at sizes where whole layers are too slow."""
+    q_row = np.asarray(q_row, dtype=np.float64)
+    s = sm_scale * (np.asarray(keys, dtype=np.float64) @ q_row)
+    w = np.exp(s - s.max())
+    return (w / w.sum()) @ np.asarray(values, dtype=np.float64)
+
+
+# ----------------------------------------------------------------------------- O2: block tables
+
+class SeqBlockModel:
+    """Bookkeeping model of the sequence region of the paged pool.
+
+    Physical blocks ``first .. first+n-1``; an allocation always takes the
+    lowest-numbered free block; queries are served in batch order and each
+    query's logical blocks in ascending order; a failed batch allocates nothing.
+    """
+
+    def __init__(self, first_block: int, n_blocks: int, block_size: int = 16):
+        self.free = sorted(range(first_block, first_block + n_blocks))
+        self.bs = block_size
+
+    def stitch(self, prefix_len: Sequence[int], suffix_len: Sequence[int], max_blocks: int):
+        need = [-(-(int(p) + int(s)) // self.bs) for p, s in zip(prefix_len, suffix_len)]
+        if sum(need) > len(self.free) or any(n > max_blocks for n in need):
+            return None
+        bt = np.full((len(need), max_blocks), -1, dtype=np.int32)
+        for i, n in enumerate(need):
+            for j in range(n):
+                bt[i, j] = self.free.pop(0)
+        return bt
+
+    def release(self, block_table: np.ndarray):
+        for b in block_table.reshape(-1):
+            if b >= 0:
+                self.free.append(int(b))
+        self.free.sort()
+
+
+def prefix_lengths(table_len: Sequence[int], table_ids: Sequence[int], cu_tables: Sequence[int]):
+    """P_i = sum of the lengths of query i's tables (Sec. 4.1.2 concatenation)."""
+    return np.array([sum(int(table_len[int(t)]) for t in table_ids[cu_tables[i]:cu_tables[i + 1]])
+                     for i in range(len(cu_tables) - 1)], dtype=np.int32)
+
+
+# ----------------------------------------------------------------------------- O4: replacement
+
+class LRUModel:
+    """App. A, LRU: hit -> move to the front; miss -> evict the end if |cache| >= C,
+    insert at the front.  ``access`` returns (hit, evicted or None)."""
+
+    def __init__(self, capacity: int):
+        self.C = capacity
+        self.items: List[int] = []          # index 0 = front
+
+    def access(self, t: int) -> Tuple[bool, Optional[int]]:
+        if t in self.items:
+            self.items.remove(t)
+            self.items.insert(0, t)
+            return True, None
+        ev = None
+        if len(self.items) >= self.C:
+            ev = self.items.pop()
+        self.items.insert(0, t)
+        return False, ev
+
+
+class FIFOModel:
+    """App. A, FIFO: miss -> evict the head if full, enqueue at the tail; hit -> nothing."""
+
+    def __init__(self, capacity: int):
+        self.C = capacity
+        self.items: List[int] = []          # index 0 = head
+
+    def access(self, t: int) -> Tuple[bool, Optional[int]]:
+        if t in self.items:
+            return True, None
+        ev = None
+        if len(self.items) >= self.C:
+            ev = self.items.pop(0)
+        self.items.append(t)
+        return False, ev
+
+
+class LFUModel:
+    """App. A, LFU: hit -> frequency+1, timestamp=now; miss -> evict the smallest
+    frequency (ties: smallest timestamp) if full, insert (1, now).  The timestamp
+    is the running access counter."""
+
+    def __init__(self, capacity: int):
+        self.C = capacity
+        self.items: Dict[int, Tuple[int, int]] = {}
+        self.now = 0
+
+    def access(self, t: int) -> Tuple[bool, Optional[int]]:
+        self.now += 1
+        if t in self.items:
+            f, _ = self.items[t]
+            self.items[t] = (f + 1, self.now)
+            return True, None
+        ev = None
+        if len(self.items) >= self.C:
+            ev = min(self.items, key=lambda x: self.items[x])
+            del self.items[ev]
+        self.items[t] = (1, self.now)
+        return False, ev
+
+
+def replay(model, accesses: Sequence[int]) -> List[Tuple[int, int, int]]:
+    """Trace of (table, hit as 0/1, evicted or -1) for an access stream."""
+    out = []
+    for t in accesses:
+        hit, ev = model.access(int(t))
+        out.append((int(t), int(hit), -1 if ev is None else int(ev)))
+    return out
