@@ -1,0 +1,205 @@
+/*
+ * libtablecache - the online hot path of TableCache on one MI355X (gfx950).
+ *
+ * The paper precomputes one KV cache per database table offline and keeps them
+ * in CPU memory (Sec. 1, Sec. 4.1).  Online, per prompt, the KV caches of the
+ * matched tables are brought to the GPU if they are not there (Sec. 4.2, App. A),
+ * concatenated in match order (Sec. 4.1.2) and the model then computes only the
+ * uncached rest of the prompt - question and instructions - which attends to all
+ * of the table content before it (App. E.4).  This library is that path:
+ *
+ *   tc_register_table_kv   a table's precomputed KV in pinned host memory      (Sec. 1, 4.1)
+ *   tc_load_async          make tables device-resident under a replacement rule (Sec. 4.2, 4.2.2, App. A)
+ *   tc_stitch_kv           concatenate the selected tables' KV into paged blocks (Sec. 4.1.2)
+ *   tc_prefill_attn        GQA attention of the suffix over stitched KV + itself (App. E.4)
+ *
+ * Conventions
+ *   - Plain C ABI.  Every pointer argument says HOST or DEVICE.  No call throws or
+ *     aborts; every call returns a tc_status (0 = ok, negative = error) and, on an
+ *     argument or state error, has no side effect (a failed tc_stitch_kv allocates
+ *     nothing).  tc_last_error() gives a text for the most recent failure.
+ *   - Streams are hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued and the call returns; errors of asynchronous work surface as
+ *     TC_ERR_HIP from a later call.
+ *   - One host thread per context at a time.
+ *   - Element type: TC_F32 (fp32 storage and arithmetic) or TC_BF16 (bf16 storage,
+ *     fp32 accumulation on the matrix cores).  bf16 needs head_dim == 128.
+ *
+ * The device KV pool
+ *   The caller allocates one device buffer of tc_pool_bytes(cfg) bytes and hands it
+ *   to tc_create.  It is carved into n_pool_blocks blocks of block_size (16) tokens,
+ *   layer-major: the bytes of (layer l, block b) start at (l * n_pool_blocks + b) *
+ *   tc_block_bytes(cfg).  Blocks [0, table_capacity * slot_blocks) are TABLE slots,
+ *   slot_blocks = ceil(max_table_tokens / block_size): slot s holds one resident
+ *   table, per layer its K rows [n_tokens][Hkv][D] as registered, then its V rows at
+ *   half the slot.  The remaining blocks are SEQUENCE blocks handed out by
+ *   tc_stitch_kv, lowest-numbered free block first; their in-block layout is private
+ *   to the library (read them back with tc_read_seq_kv).
+ */
+#ifndef TABLECACHE_H
+#define TABLECACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tc_ctx tc_ctx;
+typedef int32_t tc_status;
+
+enum {
+    TC_OK = 0,
+    TC_ERR_INVALID = -1,       /* bad argument (null, out of range, unsupported shape)        */
+    TC_ERR_UNKNOWN_TABLE = -2, /* table id was never registered                               */
+    TC_ERR_OOM_POOL = -3,      /* not enough free sequence blocks (or max_blocks too small)   */
+    TC_ERR_NOT_RESIDENT = -4,  /* a table needed by the call is not on the device             */
+    TC_ERR_CAPACITY = -5,      /* table does not fit a slot / nothing can be evicted          */
+    TC_ERR_HIP = -6            /* the HIP runtime reported an error                           */
+};
+
+enum { TC_F32 = 0, TC_BF16 = 1 };
+enum { TC_POLICY_LRU = 0, TC_POLICY_FIFO = 1, TC_POLICY_LFU = 2 };
+
+typedef struct {
+    int32_t n_layers;          /* L                                                          */
+    int32_t n_q_heads;         /* Hq, a multiple of n_kv_heads                               */
+    int32_t n_kv_heads;        /* Hkv                                                        */
+    int32_t head_dim;          /* D: 64 or 128 (bf16: 128)                                   */
+    int32_t block_size;        /* tokens per block; must be 16                               */
+    int32_t dtype;             /* TC_F32 | TC_BF16                                           */
+    int64_t n_pool_blocks;     /* total blocks, table slots included                         */
+    int32_t table_capacity;    /* C of App. A: how many tables the device cache holds        */
+    int32_t max_table_tokens;  /* longest table that may be registered (sizes a slot)        */
+    int32_t policy;            /* TC_POLICY_*                                                */
+    int32_t reserved;          /* 0                                                          */
+} tc_config;
+
+/* Bytes of one block in one layer: 2 (K and V) * Hkv * block_size * D * sizeof(element). */
+size_t tc_block_bytes(const tc_config *cfg);
+/* Bytes the caller must allocate for the pool: n_layers * n_pool_blocks * tc_block_bytes.  0 if cfg is invalid. */
+size_t tc_pool_bytes(const tc_config *cfg);
+/* First sequence block = table_capacity * ceil(max_table_tokens / block_size).  -1 if cfg is invalid. */
+int64_t tc_first_seq_block(const tc_config *cfg);
+
+/*
+ * Create a context over a caller-owned pool.
+ *   cfg          HOST, copied.
+ *   kv_pool_dev  DEVICE, 256-byte aligned, at least tc_pool_bytes(cfg) bytes, owned by the
+ *                caller, must outlive the context.  Contents need not be initialised.
+ *   out          HOST, receives the context.
+ * The library allocates only small metadata buffers of its own (work lists, split-KV partials).
+ */
+tc_status tc_create(const tc_config *cfg, void *kv_pool_dev, size_t pool_bytes, tc_ctx **out);
+tc_status tc_destroy(tc_ctx *ctx);
+
+/*
+ * Register a table's precomputed KV (Sec. 1: table KV computed offline and stored in CPU
+ * memory; Sec. 4.1.2: a trie leaf names the table id and where its KV is kept).
+ *   table_id  >= 0, unique.
+ *   n_tokens  1 .. max_table_tokens.
+ *   host_k, host_v  HOST, pinned (hipHostMalloc or torch pin_memory), layout
+ *             [L][n_tokens][Hkv][D] in the context's element type, owned by the caller,
+ *             must stay valid and unchanged until the context is destroyed.
+ * Nothing is copied here.
+ */
+tc_status tc_register_table_kv(tc_ctx *ctx, int32_t table_id, int32_t n_tokens,
+                               const void *host_k, const void *host_v);
+
+/*
+ * Request tables, in order, from the device table cache (Sec. 4.2: an update happens
+ * only when a request targets a non-cached table and then swaps it in, the victim
+ * chosen by the replacement rule; App. A gives the rules; Sec. 4.2.2: the copies run
+ * concurrently with computation).  For each id, the rule's Update(request) is applied
+ * exactly as listed in App. A; on a miss the table takes the lowest free slot, or the
+ * victim's slot, and host->device copies of its K and V for layers [l0, l1) are
+ * enqueued on `stream`.  A later call with another layer range for a table that is
+ * already in the cache (a hit) copies the layers not copied yet.
+ *   table_ids  HOST, n entries.
+ *   stream     the side stream the copies run on.
+ * Ordering against other streams is the library's job: a stitch that reads a slot
+ * waits for that slot's copies; a copy into a reused slot waits for the last stitch
+ * that read it.  The (table, hit, evicted) trace is kept for tc_load_trace.
+ * Errors: TC_ERR_UNKNOWN_TABLE, TC_ERR_INVALID (layer range), TC_ERR_HIP.
+ */
+tc_status tc_load_async(tc_ctx *ctx, const int32_t *table_ids, int32_t n,
+                        int32_t l0, int32_t l1, void *stream);
+
+/* Copy out up to `cap` entries of the access trace since the last call: triples
+ * (table, hit 0/1, evicted table or -1).  HOST out[3*cap].  Returns the count (>= 0). */
+int32_t tc_load_trace(tc_ctx *ctx, int32_t *out, int32_t cap);
+/* 1 if the table is in the device cache with layers [l0,l1) copied (or enqueued), else 0. */
+int32_t tc_is_resident(const tc_ctx *ctx, int32_t table_id, int32_t l0, int32_t l1);
+
+/*
+ * Stitch (Sec. 4.1.2: the KV caches of the tables found in the prompt are concatenated,
+ * in the order they were found, and fed to the model).  For query i the tables
+ * table_ids[cu_tables[i] .. cu_tables[i+1]) give P_i = sum of their lengths schema
+ * tokens; ceil((P_i + suffix_len[i]) / 16) sequence blocks are taken (lowest free
+ * first, queries in order), and a gather kernel copies, for every layer and KV head,
+ * logical token p of the concatenation into slot p % 16 of block block_table[i][p / 16].
+ * Slots past P_i in the touched blocks are zero-filled.  A table may appear twice.
+ *   table_ids, cu_tables, suffix_len   HOST in  (cu_tables has B+1 entries)
+ *   block_table                        HOST out [B][max_blocks], unused entries -1
+ *   prefix_len                         HOST out [B]
+ *   stream                             the compute stream; the gather is enqueued on it
+ * The batch becomes the context's current batch (its integer plan is uploaded once and
+ * reused by tc_prefill_attn for every layer).
+ * Errors: TC_ERR_UNKNOWN_TABLE, TC_ERR_NOT_RESIDENT (all layers must be resident or
+ * enqueued), TC_ERR_OOM_POOL, TC_ERR_INVALID.
+ */
+tc_status tc_stitch_kv(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_tables, int32_t B,
+                       const int32_t *suffix_len, int32_t *block_table, int32_t max_blocks,
+                       int32_t *prefix_len, void *stream);
+
+/*
+ * Suffix prefill attention, one layer (App. E.4: only the uncached part of the prompt
+ * is computed, and it attends to all preceding table content; it is causal to itself).
+ * First the suffix keys/values are appended to the sequence blocks at logical positions
+ * [P_i, P_i + S_i); then for query i, head h (KV head h / (Hq/Hkv)), suffix row r:
+ *   out = softmax_j( sm_scale * q . k_j ) v_j   over j in [0, P_i) U [P_i, P_i + r].
+ *   q, out            DEVICE [sum S][Hq][D]      (16-byte aligned)
+ *   k_new, v_new      DEVICE [sum S][Hkv][D]     (16-byte aligned)
+ *   cu_seqlens        HOST [B+1], cu_seqlens[i+1]-cu_seqlens[i] == suffix_len[i]
+ *   block_table       HOST [B][max_blocks]
+ *   prefix_len, suffix_len   HOST [B]
+ * The integer arguments normally are the ones tc_stitch_kv returned for the current
+ * batch, in which case nothing is uploaded; if they differ, the call re-plans from them
+ * (every block id must be a sequence block in range).
+ * Errors: TC_ERR_INVALID, TC_ERR_HIP.
+ */
+tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void *k_new,
+                          const void *v_new, void *out, const int32_t *cu_seqlens,
+                          const int32_t *block_table, int32_t max_blocks,
+                          const int32_t *prefix_len, const int32_t *suffix_len, int32_t B,
+                          float sm_scale, void *stream);
+
+/* Return the sequence blocks named in block_table (HOST [B][max_blocks], -1 ignored) to
+ * the free set.  The caller must have ordered this after the kernels that use them.
+ * Errors: TC_ERR_INVALID if an entry is not an allocated sequence block (nothing freed). */
+tc_status tc_release_seqs(tc_ctx *ctx, const int32_t *block_table, int32_t max_blocks, int32_t B);
+
+/*
+ * Read logical tokens [0, n_tokens) of one sequence in one layer back in token-major
+ * order, undoing the private in-block layout: out_k, out_v HOST [n_tokens][Hkv][D].
+ * blocks: HOST, ceil(n_tokens/16) sequence block ids.  Synchronises `stream`.
+ * For checking the gather and the append bit for bit.
+ */
+tc_status tc_read_seq_kv(tc_ctx *ctx, int32_t layer, const int32_t *blocks, int32_t n_tokens,
+                         void *out_k, void *out_v, void *stream);
+
+/* Number of split-KV partitions tc_prefill_attn uses for the longest query of the
+ * current batch (1 = no split); tc_set_kv_splits forces a value (0 = automatic). */
+int32_t tc_kv_splits(const tc_ctx *ctx);
+tc_status tc_set_kv_splits(tc_ctx *ctx, int32_t n_splits);
+
+/* Text for the most recent error on this context; library-owned, valid until the next call. */
+const char *tc_last_error(const tc_ctx *ctx);
+/* Library version string. */
+const char *tc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TABLECACHE_H */

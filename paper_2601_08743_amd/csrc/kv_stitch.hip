@@ -1,0 +1,223 @@
+// KV stitch (gather of table segments into sequence blocks), suffix append and
+// read-back kernels.  All three are pure byte movement: HBM-bound, 128-bit accesses.
+//
+// Sequence-block layout in one layer (private to the library):
+//   K half: [Hkv][16 tokens][D]                        (token rows, as the QK^T operand wants them)
+//   V half: fp32: [Hkv][16 tokens][D]
+//           bf16: [Hkv][D][16 tokens], token t stored at position vperm(t) so that the two
+//                 8-token groups a PV matrix-core operand needs are 16 contiguous bytes.
+#include "tc_internal.h"
+
+namespace tc {
+
+__device__ __forceinline__ int vperm(int t) { return (t & 3) | ((t & 4) << 1) | ((t & 8) >> 1); }
+
+// ------------------------------------------------------------------------------------ stitch
+// Paper Sec. 4.1.2: the matched tables' KV caches are concatenated in match order.
+// One work-group per (destination block, layer).
+template <bool kTransposeV>
+__global__ __launch_bounds__(256) void stitch_kernel(Geom g, BatchDev b, int l0)
+{
+    extern __shared__ uint4 lds[];                 // transposing path: [16][row_bytes/16]
+    __shared__ int64_t src_off[kBlockTokens];
+    const StitchBlk blk = b.stitch_blk[blockIdx.x];
+    const int layer = l0 + blockIdx.y;
+    const int tid = threadIdx.x;
+    if (tid < kBlockTokens) {
+        const int p = blk.p0 + tid;
+        int64_t off = -1;
+        if (p < b.prefix_len[blk.q]) {
+            int s = blk.seg;
+            while (p >= b.seg_start[s] + b.seg_len[s]) ++s;
+            off = (int64_t)b.seg_slot[s] * g.slot_bytes + (int64_t)(p - b.seg_start[s]) * g.row_bytes;
+        }
+        src_off[tid] = off;
+    }
+    __syncthreads();
+    const char *layer_base = g.pool + (int64_t)layer * g.layer_stride;
+    char *dst = g.pool + (int64_t)layer * g.layer_stride + (int64_t)blk.phys * g.block_bytes;
+    const int cpr = g.row_bytes >> 4;              // 16-byte chunks per token row
+    const int cph = g.head_bytes >> 4;             // ... per head
+    const int n_chunks = kBlockTokens * cpr;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    // K: [t][h][d] -> [h][t][d]
+    for (int c = tid; c < n_chunks; c += 256) {
+        const int t = c / cpr, w = c - t * cpr;
+        const int h = w / cph, dc = w - h * cph;
+        const int64_t so = src_off[t];
+        const uint4 v = so >= 0 ? *(const uint4 *)(layer_base + so + ((int64_t)w << 4)) : zero;
+        *(uint4 *)(dst + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = v;
+    }
+    const char *vsrc_base = layer_base + (g.slot_bytes >> 1);
+    char *vdst = dst + (g.block_bytes >> 1);
+    if (!kTransposeV) {
+        for (int c = tid; c < n_chunks; c += 256) {
+            const int t = c / cpr, w = c - t * cpr;
+            const int h = w / cph, dc = w - h * cph;
+            const int64_t so = src_off[t];
+            const uint4 v = so >= 0 ? *(const uint4 *)(vsrc_base + so + ((int64_t)w << 4)) : zero;
+            *(uint4 *)(vdst + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = v;
+        }
+    } else {
+        for (int c = tid; c < n_chunks; c += 256) {
+            const int t = c / cpr, w = c - t * cpr;
+            const int64_t so = src_off[t];
+            lds[c] = so >= 0 ? *(const uint4 *)(vsrc_base + so + ((int64_t)w << 4)) : zero;
+        }
+        __syncthreads();
+        // out chunk oc = (h, d, half): 8 tokens of one (h, d), 2-byte elements
+        const unsigned short *l16 = (const unsigned short *)lds;
+        const int row_elems = g.row_bytes >> 1;
+        const int n_out = g.Hkv * g.D * 2;
+        for (int oc = tid; oc < n_out; oc += 256) {
+            const int half = oc & 1;
+            const int hd = oc >> 1;                // h * D + d
+            unsigned short e[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int t = (k & 3) | ((k & 4) << 1) | (half << 2);
+                e[k] = l16[t * row_elems + hd];
+            }
+            uint4 v;
+            v.x = e[0] | ((unsigned)e[1] << 16);
+            v.y = e[2] | ((unsigned)e[3] << 16);
+            v.z = e[4] | ((unsigned)e[5] << 16);
+            v.w = e[6] | ((unsigned)e[7] << 16);
+            *(uint4 *)(vdst + ((int64_t)oc << 4)) = v;
+        }
+    }
+}
+
+hipError_t launch_stitch(const Geom &g, const BatchDev &b, int l0, int l1, hipStream_t s)
+{
+    if (b.n_stitch_blk == 0 || l1 <= l0) return hipSuccess;
+    dim3 grid(b.n_stitch_blk, l1 - l0);
+    if (g.esize == 2)
+        stitch_kernel<true><<<grid, 256, kBlockTokens * g.row_bytes, s>>>(g, b, l0);
+    else
+        stitch_kernel<false><<<grid, 256, 0, s>>>(g, b, l0);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------ append
+// The suffix tokens' own K/V go to logical positions [P_i, P_i + S_i) of the sequence, so the
+// attention kernel reads one uniform paged sequence.  Work-group n < total_S handles suffix
+// token n; work-group total_S + i zero-fills the unused tail of query i's last block.
+template <bool kTransposeV>
+__global__ __launch_bounds__(256) void append_kernel(Geom g, BatchDev b, int layer,
+                                                     const char *k_new, const char *v_new)
+{
+    const int tid = threadIdx.x;
+    const int n = blockIdx.x;
+    char *layer_base = g.pool + (int64_t)layer * g.layer_stride;
+    const int cpr = g.row_bytes >> 4, cph = g.head_bytes >> 4;
+    if (n < b.total_S) {
+        const int i = b.tok_q[n];
+        const int p = b.prefix_len[i] + (n - b.cu_seqlens[i]);
+        const int phys = b.block_table[(int64_t)i * b.max_blocks + (p >> 4)];
+        const int t = p & 15;
+        char *kd = layer_base + (int64_t)phys * g.block_bytes;
+        char *vd = kd + (g.block_bytes >> 1);
+        for (int w = tid; w < cpr; w += 256) {
+            const int h = w / cph, dc = w - h * cph;
+            const uint4 kv = *(const uint4 *)(k_new + (int64_t)n * g.row_bytes + (w << 4));
+            *(uint4 *)(kd + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = kv;
+            const uint4 vv = *(const uint4 *)(v_new + (int64_t)n * g.row_bytes + (w << 4));
+            if (!kTransposeV) {
+                *(uint4 *)(vd + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = vv;
+            } else {
+                const unsigned u[4] = {vv.x, vv.y, vv.z, vv.w};
+                unsigned short *v16 = (unsigned short *)vd;
+                const int d0 = dc << 3;            // 8 bf16 per chunk
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const unsigned short e = (unsigned short)(u[k >> 1] >> ((k & 1) * 16));
+                    v16[((int64_t)(h * g.D + d0 + k) << 4) + vperm(t)] = e;
+                }
+            }
+        }
+    } else {
+        const int i = n - b.total_S;
+        const int end = b.prefix_len[i] + b.suffix_len[i];
+        const int t0 = end & 15;
+        if (t0 == 0) return;
+        const int phys = b.block_table[(int64_t)i * b.max_blocks + (end >> 4)];
+        char *kd = layer_base + (int64_t)phys * g.block_bytes;
+        char *vd = kd + (g.block_bytes >> 1);
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+        const int n_tail = kBlockTokens - t0;
+        for (int c = tid; c < n_tail * cpr; c += 256) {
+            const int t = t0 + c / cpr, w = c % cpr;
+            const int h = w / cph, dc = w - h * cph;
+            *(uint4 *)(kd + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = zero;
+            if (!kTransposeV) {
+                *(uint4 *)(vd + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = zero;
+            } else {
+                unsigned short *v16 = (unsigned short *)vd;
+                const int d0 = dc << 3;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v16[((int64_t)(h * g.D + d0 + k) << 4) + vperm(t)] = 0;
+            }
+        }
+    }
+}
+
+hipError_t launch_append(const Geom &g, const BatchDev &b, int layer, const void *k_new,
+                         const void *v_new, hipStream_t s)
+{
+    const int n = b.total_S + b.B;
+    if (n == 0) return hipSuccess;
+    if (g.esize == 2)
+        append_kernel<true><<<n, 256, 0, s>>>(g, b, layer, (const char *)k_new, (const char *)v_new);
+    else
+        append_kernel<false><<<n, 256, 0, s>>>(g, b, layer, (const char *)k_new, (const char *)v_new);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------ read-back
+// Undo the block layout: token-major [n_tokens][Hkv][D] for K and V.  One work-group per block.
+template <bool kTransposeV>
+__global__ __launch_bounds__(256) void readback_kernel(Geom g, int layer, const int32_t *blocks,
+                                                       int n_tokens, char *k_out, char *v_out)
+{
+    const int tid = threadIdx.x;
+    const int jb = blockIdx.x;
+    const int phys = blocks[jb];
+    const char *kd = g.pool + (int64_t)layer * g.layer_stride + (int64_t)phys * g.block_bytes;
+    const char *vd = kd + (g.block_bytes >> 1);
+    const int cpr = g.row_bytes >> 4, cph = g.head_bytes >> 4;
+    for (int c = tid; c < kBlockTokens * cpr; c += 256) {
+        const int t = c / cpr, w = c - t * cpr;
+        const int p = jb * kBlockTokens + t;
+        if (p >= n_tokens) continue;
+        const int h = w / cph, dc = w - h * cph;
+        *(uint4 *)(k_out + (int64_t)p * g.row_bytes + (w << 4)) =
+            *(const uint4 *)(kd + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4));
+        if (!kTransposeV) {
+            *(uint4 *)(v_out + (int64_t)p * g.row_bytes + (w << 4)) =
+                *(const uint4 *)(vd + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4));
+        } else {
+            const unsigned short *v16 = (const unsigned short *)vd;
+            unsigned short *o16 = (unsigned short *)(v_out + (int64_t)p * g.row_bytes + (w << 4));
+            const int d0 = dc << 3;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) o16[k] = v16[((int64_t)(h * g.D + d0 + k) << 4) + vperm(t)];
+        }
+    }
+}
+
+hipError_t launch_readback(const Geom &g, int layer, const int32_t *blocks_dev, int n_tokens,
+                           void *k_out_dev, void *v_out_dev, hipStream_t s)
+{
+    if (n_tokens <= 0) return hipSuccess;
+    const int nb = (n_tokens + kBlockTokens - 1) / kBlockTokens;
+    if (g.esize == 2)
+        readback_kernel<true><<<nb, 256, 0, s>>>(g, layer, blocks_dev, n_tokens, (char *)k_out_dev,
+                                                 (char *)v_out_dev);
+    else
+        readback_kernel<false><<<nb, 256, 0, s>>>(g, layer, blocks_dev, n_tokens, (char *)k_out_dev,
+                                                  (char *)v_out_dev);
+    return hipGetLastError();
+}
+
+}  // namespace tc

@@ -1,0 +1,723 @@
+// Host side of libtablecache: the C ABI of include/tablecache.h, the table registry, the
+// device table cache with its replacement rules (paper App. A), the sequence-block allocator,
+// per-batch planning (stitch descriptors, attention work list, split-KV) and kernel launches.
+#include "../../include/tablecache.h"
+#include "tc_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <list>
+#include <map>
+#include <memory>
+#include <set>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+using namespace tc;
+
+namespace {
+
+// ------------------------------------------------------------------ replacement rules (App. A)
+// Each rule answers three questions about the set of cached tables: is the request cached,
+// what happens on a hit, and who goes when a miss finds the cache full.
+class Replacement {
+public:
+    virtual ~Replacement() {}
+    virtual bool cached(int32_t id) const = 0;
+    virtual void on_hit(int32_t id) = 0;
+    virtual int32_t pick_victim() const = 0;       // cache is non-empty
+    virtual void remove(int32_t id) = 0;
+    virtual void insert(int32_t id) = 0;
+    virtual size_t size() const = 0;
+    virtual void tick() {}                         // called once per request, before anything else
+};
+
+// LRU: recency list, most recent at the front; the end is evicted.
+class LruRule : public Replacement {
+    std::list<int32_t> order_;
+    std::unordered_map<int32_t, std::list<int32_t>::iterator> pos_;
+public:
+    bool cached(int32_t id) const override { return pos_.count(id) != 0; }
+    void on_hit(int32_t id) override { order_.splice(order_.begin(), order_, pos_[id]); }
+    int32_t pick_victim() const override { return order_.back(); }
+    void remove(int32_t id) override { order_.erase(pos_[id]); pos_.erase(id); }
+    void insert(int32_t id) override { order_.push_front(id); pos_[id] = order_.begin(); }
+    size_t size() const override { return pos_.size(); }
+};
+
+// FIFO: a queue; hits leave it alone; the head is evicted, arrivals join the tail.
+class FifoRule : public Replacement {
+    std::list<int32_t> queue_;
+    std::unordered_map<int32_t, std::list<int32_t>::iterator> pos_;
+public:
+    bool cached(int32_t id) const override { return pos_.count(id) != 0; }
+    void on_hit(int32_t) override {}
+    int32_t pick_victim() const override { return queue_.front(); }
+    void remove(int32_t id) override { queue_.erase(pos_[id]); pos_.erase(id); }
+    void insert(int32_t id) override { queue_.push_back(id); pos_[id] = std::prev(queue_.end()); }
+    size_t size() const override { return pos_.size(); }
+};
+
+// LFU: (frequency, timestamp) per table; smallest frequency goes, ties by smallest timestamp.
+class LfuRule : public Replacement {
+    struct Stat { int64_t freq, stamp; };
+    std::unordered_map<int32_t, Stat> stat_;
+    int64_t clock_ = 0;
+public:
+    void tick() override { ++clock_; }
+    bool cached(int32_t id) const override { return stat_.count(id) != 0; }
+    void on_hit(int32_t id) override { Stat &s = stat_[id]; s.freq += 1; s.stamp = clock_; }
+    int32_t pick_victim() const override {
+        int32_t best = -1; Stat bs{0, 0};
+        for (const auto &kv : stat_)
+            if (best < 0 || kv.second.freq < bs.freq ||
+                (kv.second.freq == bs.freq && kv.second.stamp < bs.stamp)) { best = kv.first; bs = kv.second; }
+        return best;
+    }
+    void remove(int32_t id) override { stat_.erase(id); }
+    void insert(int32_t id) override { stat_[id] = Stat{1, clock_}; }
+    size_t size() const override { return stat_.size(); }
+};
+
+struct Table {
+    int32_t n_tokens = 0;
+    const char *host_k = nullptr, *host_v = nullptr;
+    int32_t slot = -1;
+    std::vector<uint8_t> layer_loaded;
+};
+
+struct Slot {
+    int32_t table = -1;
+    hipEvent_t ready = nullptr;        // recorded on the load stream after the latest copies
+    hipStream_t ready_stream = nullptr;
+    bool ready_pending = false;        // a record exists that other streams may have to wait for
+    int32_t read_ev = -1;              // index into the read-event ring, -1 = never read
+};
+
+// The integer plan of one batch, host copy and layout of the device copy.
+struct Plan {
+    bool valid = false;
+    int32_t B = 0, max_blocks = 0, total_S = 0, n_stitch_blk = 0, n_items = 0, max_splits = 1;
+    std::vector<int32_t> block_table, cu_seqlens, prefix_len, suffix_len;
+    BatchDev dev{};
+    const AttnItem *items_dev = nullptr;
+};
+
+inline size_t align8(size_t n) { return (n + 7) & ~size_t(7); }
+
+}  // namespace
+
+struct tc_ctx {
+    tc_config cfg{};
+    Geom geom{};
+    int32_t slot_blocks = 0;
+    int64_t first_seq = 0;
+    std::unordered_map<int32_t, Table> tables;
+    std::unique_ptr<Replacement> rule;
+    std::vector<Slot> slots;
+    std::set<int32_t> free_slots;
+    std::set<int32_t> free_seq;            // free sequence blocks, ordered
+    std::vector<uint8_t> seq_used;         // by block id - first_seq
+    std::vector<int32_t> trace;            // (table, hit, evicted) triples
+    std::vector<hipEvent_t> read_ring;     // events recorded after stitch kernels
+    int32_t read_next = 0;
+    Plan plan;
+    int32_t *h_stage = nullptr; size_t h_stage_ints = 0;
+    int32_t *d_plan = nullptr; size_t d_plan_ints = 0;
+    hipEvent_t stage_ev = nullptr; bool stage_pending = false;
+    float *d_part = nullptr; size_t d_part_floats = 0;
+    int32_t forced_splits = 0;
+    std::string err;
+};
+
+namespace {
+
+tc_status fail(tc_ctx *ctx, tc_status code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx) ctx->err = buf;
+    return code;
+}
+
+#define TC_HIP(ctx, call)                                                                       \
+    do {                                                                                        \
+        hipError_t e_ = (call);                                                                 \
+        if (e_ != hipSuccess)                                                                   \
+            return fail(ctx, TC_ERR_HIP, "%s: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+
+bool config_ok(const tc_config *c)
+{
+    if (!c) return false;
+    if (c->n_layers <= 0 || c->n_kv_heads <= 0 || c->n_q_heads <= 0) return false;
+    if (c->n_q_heads % c->n_kv_heads != 0) return false;
+    if (c->block_size != kBlockTokens) return false;
+    if (c->dtype != TC_F32 && c->dtype != TC_BF16) return false;
+    if (c->head_dim != 64 && c->head_dim != 128) return false;
+    if (c->dtype == TC_BF16 && c->head_dim != 128) return false;
+    if (c->table_capacity < 0 || c->max_table_tokens <= 0) return false;
+    if (c->policy < TC_POLICY_LRU || c->policy > TC_POLICY_LFU) return false;
+    if (c->n_pool_blocks <= 0 || c->n_pool_blocks > INT32_MAX) return false;
+    const int64_t sb = (c->max_table_tokens + kBlockTokens - 1) / kBlockTokens;
+    if ((int64_t)c->table_capacity * sb > c->n_pool_blocks) return false;
+    return true;
+}
+
+int esize_of(const tc_config &c) { return c.dtype == TC_F32 ? 4 : 2; }
+
+tc_status ensure_stage(tc_ctx *ctx, size_t ints)
+{
+    if (ctx->stage_pending) {                       // the previous upload still reads the staging buffer
+        TC_HIP(ctx, hipEventSynchronize(ctx->stage_ev));
+        ctx->stage_pending = false;
+    }
+    if (ints > ctx->h_stage_ints) {
+        if (ctx->h_stage) TC_HIP(ctx, hipHostFree(ctx->h_stage));
+        ctx->h_stage = nullptr; ctx->h_stage_ints = 0;
+        const size_t cap = std::max(ints * 2, size_t(1) << 16);
+        TC_HIP(ctx, hipHostMalloc((void **)&ctx->h_stage, cap * sizeof(int32_t), hipHostMallocDefault));
+        ctx->h_stage_ints = cap;
+    }
+    if (ints > ctx->d_plan_ints) {
+        if (ctx->d_plan) TC_HIP(ctx, hipFree(ctx->d_plan));   // hipFree waits for work that may use it
+        ctx->d_plan = nullptr; ctx->d_plan_ints = 0;
+        const size_t cap = std::max(ints * 2, size_t(1) << 16);
+        TC_HIP(ctx, hipMalloc((void **)&ctx->d_plan, cap * sizeof(int32_t)));
+        ctx->d_plan_ints = cap;
+    }
+    return TC_OK;
+}
+
+struct SegInfo { int32_t start, len, slot; };
+
+// Attention work list for the batch in `p` (host arrays filled in).  Items of one
+// (query, KV head, split) read the same K/V; they are given work-group ids that are congruent
+// modulo 8 so that they land on the same XCD and share its L2 (work-groups go to the 8 XCDs
+// round-robin by id).  Holes are padded with no-op items (q = -1).
+void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
+                    std::vector<int32_t> &splits_of_q)
+{
+    const tc_config &c = ctx->cfg;
+    const int G = c.n_q_heads / c.n_kv_heads;
+    const bool bf16 = c.dtype == TC_BF16;
+    const int RT = bf16 ? kAttnRows : kF32Rows;
+    const int KT = bf16 ? kAttnKeys : kF32Keys;
+    int64_t base = 0;
+    for (int i = 0; i < p.B; ++i)
+        if (p.suffix_len[i] > 0) base += (int64_t)c.n_kv_heads * ((p.suffix_len[i] * G + RT - 1) / RT);
+    int want = 1;
+    if (ctx->forced_splits > 0) want = ctx->forced_splits;
+    else if (base > 0) {
+        const int64_t target = bf16 ? 256 : 512;       // work-groups that fill the chip once
+        want = (int)std::max<int64_t>(1, target / base);
+    }
+    splits_of_q.assign(p.B, 1);
+    p.max_splits = 1;
+    std::vector<std::vector<AttnItem>> per_xcd(8);
+    int group = 0;
+    for (int i = 0; i < p.B; ++i) {
+        const int S = p.suffix_len[i], P = p.prefix_len[i];
+        if (S <= 0) continue;
+        const int n_tiles = (P + S + KT - 1) / KT;
+        int ns = std::min(want, ctx->forced_splits > 0 ? n_tiles : std::max(1, n_tiles / 4));
+        ns = std::max(1, std::min(ns, n_tiles));
+        splits_of_q[i] = ns;
+        p.max_splits = std::max(p.max_splits, ns);
+        const int n_mt = (S * G + RT - 1) / RT;
+        for (int h = 0; h < c.n_kv_heads; ++h)
+            for (int s = 0; s < ns; ++s) {
+                const int t0 = (int)((int64_t)n_tiles * s / ns), t1 = (int)((int64_t)n_tiles * (s + 1) / ns);
+                for (int mt = 0; mt < n_mt; ++mt)
+                    per_xcd[group & 7].push_back(AttnItem{i, h, mt * RT, t0, t1, s, ns, 0});
+                ++group;
+            }
+    }
+    size_t longest = 0;
+    for (auto &v : per_xcd) longest = std::max(longest, v.size());
+    items.clear();
+    for (size_t k = 0; k < longest; ++k)
+        for (int x = 0; x < 8; ++x)
+            items.push_back(k < per_xcd[x].size() ? per_xcd[x][k] : AttnItem{-1, 0, 0, 0, 0, 0, 1, 0});
+    while (!items.empty() && items.back().q < 0) items.pop_back();
+    p.n_items = (int32_t)items.size();
+}
+
+// Serialise the plan into the staging buffer and enqueue its upload on `stream`.
+tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
+                      const std::vector<int32_t> &seg_end_of_q, const std::vector<StitchBlk> &sblk,
+                      hipStream_t stream)
+{
+    std::vector<AttnItem> items;
+    std::vector<int32_t> splits_of_q;
+    plan_attention(ctx, p, items, splits_of_q);
+
+    const size_t B = p.B, nseg = segs.size();
+    size_t off = 0;
+    auto take = [&](size_t n) { size_t o = off; off += align8(n); return o; };
+    const size_t o_bt = take(B * p.max_blocks), o_cu = take(B + 1), o_pl = take(B), o_sl = take(B);
+    const size_t o_ss = take(nseg), o_sn = take(nseg), o_st = take(nseg), o_se = take(B);
+    const size_t o_sb = take(sblk.size() * 4), o_sp = take(B), o_tq = take(p.total_S);
+    const size_t o_it = take(items.size() * 8);
+    const size_t total = std::max(off, size_t(8));
+    tc_status st = ensure_stage(ctx, total);
+    if (st != TC_OK) return st;
+    int32_t *h = ctx->h_stage;
+    std::memset(h, 0, total * sizeof(int32_t));
+    if (B) {
+        std::memcpy(h + o_bt, p.block_table.data(), B * p.max_blocks * 4);
+        std::memcpy(h + o_cu, p.cu_seqlens.data(), (B + 1) * 4);
+        std::memcpy(h + o_pl, p.prefix_len.data(), B * 4);
+        std::memcpy(h + o_sl, p.suffix_len.data(), B * 4);
+        std::memcpy(h + o_sp, splits_of_q.data(), B * 4);
+        if (!seg_end_of_q.empty()) std::memcpy(h + o_se, seg_end_of_q.data(), B * 4);
+    }
+    for (size_t k = 0; k < nseg; ++k) {
+        h[o_ss + k] = segs[k].start; h[o_sn + k] = segs[k].len; h[o_st + k] = segs[k].slot;
+    }
+    if (!sblk.empty()) std::memcpy(h + o_sb, sblk.data(), sblk.size() * sizeof(StitchBlk));
+    for (int i = 0; i < p.B; ++i)
+        for (int n = p.cu_seqlens[i]; n < p.cu_seqlens[i + 1]; ++n) h[o_tq + n] = i;
+    if (!items.empty()) std::memcpy(h + o_it, items.data(), items.size() * sizeof(AttnItem));
+
+    TC_HIP(ctx, hipMemcpyAsync(ctx->d_plan, h, total * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+    TC_HIP(ctx, hipEventRecord(ctx->stage_ev, stream));
+    ctx->stage_pending = true;
+
+    const int32_t *d = ctx->d_plan;
+    p.dev.block_table = d + o_bt; p.dev.cu_seqlens = d + o_cu; p.dev.prefix_len = d + o_pl;
+    p.dev.suffix_len = d + o_sl; p.dev.seg_start = d + o_ss; p.dev.seg_len = d + o_sn;
+    p.dev.seg_slot = d + o_st; p.dev.seg_end_of_q = d + o_se;
+    p.dev.stitch_blk = (const StitchBlk *)(d + o_sb); p.dev.splits_of_q = d + o_sp;
+    p.dev.tok_q = d + o_tq;
+    p.dev.B = p.B; p.dev.max_blocks = p.max_blocks; p.dev.total_S = p.total_S;
+    p.dev.n_stitch_blk = (int32_t)sblk.size();
+    p.n_stitch_blk = (int32_t)sblk.size();
+    p.items_dev = (const AttnItem *)(d + o_it);
+
+    if (p.max_splits > 1) {
+        const size_t need = (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * (ctx->cfg.head_dim + 2);
+        if (need > ctx->d_part_floats) {
+            if (ctx->d_part) TC_HIP(ctx, hipFree(ctx->d_part));
+            ctx->d_part = nullptr; ctx->d_part_floats = 0;
+            TC_HIP(ctx, hipMalloc((void **)&ctx->d_part, need * sizeof(float)));
+            ctx->d_part_floats = need;
+        }
+    }
+    p.valid = true;
+    return TC_OK;
+}
+
+}  // namespace
+
+// =========================================================================== C ABI
+
+extern "C" {
+
+size_t tc_block_bytes(const tc_config *c)
+{
+    if (!c || c->n_kv_heads <= 0 || c->head_dim <= 0 || c->block_size <= 0) return 0;
+    return (size_t)2 * c->n_kv_heads * c->block_size * c->head_dim * (c->dtype == TC_F32 ? 4 : 2);
+}
+
+size_t tc_pool_bytes(const tc_config *c)
+{
+    if (!config_ok(c)) return 0;
+    return (size_t)c->n_layers * (size_t)c->n_pool_blocks * tc_block_bytes(c);
+}
+
+int64_t tc_first_seq_block(const tc_config *c)
+{
+    if (!config_ok(c)) return -1;
+    return (int64_t)c->table_capacity * ((c->max_table_tokens + kBlockTokens - 1) / kBlockTokens);
+}
+
+const char *tc_version(void) { return "libtablecache 0.1 (gfx950)"; }
+
+const char *tc_last_error(const tc_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+tc_status tc_create(const tc_config *cfg, void *kv_pool_dev, size_t pool_bytes, tc_ctx **out)
+{
+    if (!out) return TC_ERR_INVALID;
+    *out = nullptr;
+    if (!config_ok(cfg) || !kv_pool_dev) return TC_ERR_INVALID;
+    if (pool_bytes < tc_pool_bytes(cfg) || ((uintptr_t)kv_pool_dev & 255)) return TC_ERR_INVALID;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev <= 0) return TC_ERR_HIP;   // no CPU fallback exists
+
+    std::unique_ptr<tc_ctx> ctx(new tc_ctx);
+    ctx->cfg = *cfg;
+    ctx->slot_blocks = (cfg->max_table_tokens + kBlockTokens - 1) / kBlockTokens;
+    ctx->first_seq = tc_first_seq_block(cfg);
+    Geom &g = ctx->geom;
+    g.pool = (char *)kv_pool_dev;
+    g.block_bytes = (int64_t)tc_block_bytes(cfg);
+    g.layer_stride = g.block_bytes * cfg->n_pool_blocks;
+    g.slot_bytes = g.block_bytes * ctx->slot_blocks;
+    g.first_seq = (int32_t)ctx->first_seq;
+    g.n_blocks = (int32_t)cfg->n_pool_blocks;
+    g.Hq = cfg->n_q_heads; g.Hkv = cfg->n_kv_heads; g.D = cfg->head_dim; g.G = g.Hq / g.Hkv;
+    g.esize = esize_of(*cfg);
+    g.row_bytes = g.Hkv * g.D * g.esize;
+    g.head_bytes = g.D * g.esize;
+
+    if (cfg->policy == TC_POLICY_LRU) ctx->rule.reset(new LruRule);
+    else if (cfg->policy == TC_POLICY_FIFO) ctx->rule.reset(new FifoRule);
+    else ctx->rule.reset(new LfuRule);
+
+    ctx->slots.resize(cfg->table_capacity);
+    for (int s = 0; s < cfg->table_capacity; ++s) {
+        if (hipEventCreateWithFlags(&ctx->slots[s].ready, hipEventDisableTiming) != hipSuccess) return TC_ERR_HIP;
+        ctx->free_slots.insert(s);
+    }
+    ctx->read_ring.resize(64);
+    for (auto &e : ctx->read_ring)
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return TC_ERR_HIP;
+    if (hipEventCreateWithFlags(&ctx->stage_ev, hipEventDisableTiming) != hipSuccess) return TC_ERR_HIP;
+    for (int64_t b = ctx->first_seq; b < cfg->n_pool_blocks; ++b) ctx->free_seq.insert((int32_t)b);
+    ctx->seq_used.assign((size_t)(cfg->n_pool_blocks - ctx->first_seq), 0);
+    *out = ctx.release();
+    return TC_OK;
+}
+
+tc_status tc_destroy(tc_ctx *ctx)
+{
+    if (!ctx) return TC_ERR_INVALID;
+    (void)hipDeviceSynchronize();
+    for (auto &s : ctx->slots) if (s.ready) (void)hipEventDestroy(s.ready);
+    for (auto &e : ctx->read_ring) if (e) (void)hipEventDestroy(e);
+    if (ctx->stage_ev) (void)hipEventDestroy(ctx->stage_ev);
+    if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
+    if (ctx->d_plan) (void)hipFree(ctx->d_plan);
+    if (ctx->d_part) (void)hipFree(ctx->d_part);
+    delete ctx;
+    return TC_OK;
+}
+
+tc_status tc_register_table_kv(tc_ctx *ctx, int32_t table_id, int32_t n_tokens, const void *host_k,
+                               const void *host_v)
+{
+    if (!ctx) return TC_ERR_INVALID;
+    if (table_id < 0 || !host_k || !host_v) return fail(ctx, TC_ERR_INVALID, "register: bad id or null KV");
+    if (n_tokens <= 0 || n_tokens > ctx->cfg.max_table_tokens)
+        return fail(ctx, TC_ERR_CAPACITY, "register: table %d has %d tokens, slot holds %d", table_id,
+                    n_tokens, ctx->cfg.max_table_tokens);
+    if (ctx->tables.count(table_id)) return fail(ctx, TC_ERR_INVALID, "register: table %d already registered", table_id);
+    Table t;
+    t.n_tokens = n_tokens;
+    t.host_k = (const char *)host_k; t.host_v = (const char *)host_v;
+    t.layer_loaded.assign(ctx->cfg.n_layers, 0);
+    ctx->tables.emplace(table_id, std::move(t));
+    return TC_OK;
+}
+
+tc_status tc_load_async(tc_ctx *ctx, const int32_t *table_ids, int32_t n, int32_t l0, int32_t l1, void *stream_)
+{
+    if (!ctx) return TC_ERR_INVALID;
+    if (n < 0 || (n > 0 && !table_ids)) return fail(ctx, TC_ERR_INVALID, "load: bad id list");
+    if (l0 < 0 || l1 > ctx->cfg.n_layers || l0 > l1) return fail(ctx, TC_ERR_INVALID, "load: bad layer range [%d,%d)", l0, l1);
+    if (ctx->cfg.table_capacity == 0 && n > 0) return fail(ctx, TC_ERR_CAPACITY, "load: table cache has no slots");
+    for (int k = 0; k < n; ++k)
+        if (!ctx->tables.count(table_ids[k])) return fail(ctx, TC_ERR_UNKNOWN_TABLE, "load: table %d not registered", table_ids[k]);
+    hipStream_t stream = (hipStream_t)stream_;
+    const Geom &g = ctx->geom;
+    std::set<int32_t> touched;
+    for (int k = 0; k < n; ++k) {
+        const int32_t id = table_ids[k];
+        Table &t = ctx->tables[id];
+        ctx->rule->tick();
+        int32_t evicted = -1;
+        const bool hit = ctx->rule->cached(id);
+        if (hit) {
+            ctx->rule->on_hit(id);
+        } else {
+            if ((int64_t)ctx->rule->size() >= ctx->cfg.table_capacity) {
+                evicted = ctx->rule->pick_victim();
+                ctx->rule->remove(evicted);
+                Table &v = ctx->tables[evicted];
+                ctx->free_slots.insert(v.slot);
+                ctx->slots[v.slot].table = -1;
+                v.slot = -1;
+                std::fill(v.layer_loaded.begin(), v.layer_loaded.end(), 0);
+            }
+            ctx->rule->insert(id);
+            t.slot = *ctx->free_slots.begin();
+            ctx->free_slots.erase(ctx->free_slots.begin());
+            Slot &s = ctx->slots[t.slot];
+            s.table = id;
+            if (s.read_ev >= 0) {       // a stitch may still be reading the previous occupant
+                TC_HIP(ctx, hipStreamWaitEvent(stream, ctx->read_ring[s.read_ev], 0));
+                s.read_ev = -1;
+            }
+            if (s.ready_pending && s.ready_stream != stream)   // earlier copies into this slot on another stream
+                TC_HIP(ctx, hipStreamWaitEvent(stream, s.ready, 0));
+        }
+        ctx->trace.push_back(id); ctx->trace.push_back(hit ? 1 : 0); ctx->trace.push_back(evicted);
+        // copy the layers of the range that are not on the device yet: per layer, the table's K rows
+        // and V rows are each one contiguous transfer
+        const size_t width = (size_t)t.n_tokens * g.row_bytes;
+        for (int l = l0; l < l1; ++l) {
+            if (t.layer_loaded[l]) continue;
+            char *dst = g.pool + (int64_t)l * g.layer_stride + (int64_t)t.slot * g.slot_bytes;
+            TC_HIP(ctx, hipMemcpyAsync(dst, t.host_k + (size_t)l * width, width, hipMemcpyHostToDevice, stream));
+            TC_HIP(ctx, hipMemcpyAsync(dst + (g.slot_bytes >> 1), t.host_v + (size_t)l * width, width,
+                                       hipMemcpyHostToDevice, stream));
+            t.layer_loaded[l] = 1;
+            touched.insert(t.slot);
+        }
+    }
+    for (int32_t s : touched) {
+        Slot &sl = ctx->slots[s];
+        TC_HIP(ctx, hipEventRecord(sl.ready, stream));
+        sl.ready_stream = stream;
+        sl.ready_pending = true;
+    }
+    return TC_OK;
+}
+
+int32_t tc_load_trace(tc_ctx *ctx, int32_t *out, int32_t cap)
+{
+    if (!ctx || cap < 0 || (cap > 0 && !out)) return TC_ERR_INVALID;
+    const int32_t have = (int32_t)(ctx->trace.size() / 3);
+    const int32_t n = std::min(have, cap);
+    std::memcpy(out, ctx->trace.data(), (size_t)n * 3 * sizeof(int32_t));
+    ctx->trace.erase(ctx->trace.begin(), ctx->trace.begin() + (size_t)n * 3);
+    return n;
+}
+
+int32_t tc_is_resident(const tc_ctx *ctx, int32_t table_id, int32_t l0, int32_t l1)
+{
+    if (!ctx) return 0;
+    auto it = ctx->tables.find(table_id);
+    if (it == ctx->tables.end() || it->second.slot < 0) return 0;
+    if (l0 < 0 || l1 > ctx->cfg.n_layers || l0 > l1) return 0;
+    for (int l = l0; l < l1; ++l) if (!it->second.layer_loaded[l]) return 0;
+    return 1;
+}
+
+tc_status tc_stitch_kv(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_tables, int32_t B,
+                       const int32_t *suffix_len, int32_t *block_table, int32_t max_blocks,
+                       int32_t *prefix_len, void *stream_)
+{
+    if (!ctx) return TC_ERR_INVALID;
+    if (B < 0 || max_blocks < 0) return fail(ctx, TC_ERR_INVALID, "stitch: negative size");
+    if (B > 0 && (!cu_tables || !suffix_len || !block_table || !prefix_len))
+        return fail(ctx, TC_ERR_INVALID, "stitch: null argument");
+    if (B > 0 && (cu_tables[0] != 0)) return fail(ctx, TC_ERR_INVALID, "stitch: cu_tables[0] != 0");
+    hipStream_t stream = (hipStream_t)stream_;
+    const int L = ctx->cfg.n_layers;
+
+    // ---- validate and size everything before touching any state
+    std::vector<SegInfo> segs;
+    std::vector<int32_t> seg_end_of_q(B), P(B), need(B);
+    int64_t need_total = 0, total_S = 0;
+    for (int i = 0; i < B; ++i) {
+        if (cu_tables[i + 1] < cu_tables[i]) return fail(ctx, TC_ERR_INVALID, "stitch: cu_tables not monotone");
+        if (cu_tables[i + 1] > cu_tables[i] && !table_ids) return fail(ctx, TC_ERR_INVALID, "stitch: null table_ids");
+        if (suffix_len[i] < 0) return fail(ctx, TC_ERR_INVALID, "stitch: negative suffix_len");
+        int64_t p = 0;
+        for (int k = cu_tables[i]; k < cu_tables[i + 1]; ++k) {
+            auto it = ctx->tables.find(table_ids[k]);
+            if (it == ctx->tables.end()) return fail(ctx, TC_ERR_UNKNOWN_TABLE, "stitch: table %d not registered", table_ids[k]);
+            const Table &t = it->second;
+            bool all = t.slot >= 0;
+            for (int l = 0; all && l < L; ++l) all = t.layer_loaded[l] != 0;
+            if (!all) return fail(ctx, TC_ERR_NOT_RESIDENT, "stitch: table %d is not device-resident", table_ids[k]);
+            segs.push_back(SegInfo{(int32_t)p, t.n_tokens, t.slot});
+            p += t.n_tokens;
+            if (p + suffix_len[i] > INT32_MAX / 2) return fail(ctx, TC_ERR_INVALID, "stitch: sequence too long");
+        }
+        seg_end_of_q[i] = (int32_t)segs.size();
+        P[i] = (int32_t)p;
+        need[i] = (int32_t)((p + suffix_len[i] + kBlockTokens - 1) / kBlockTokens);
+        if (need[i] > max_blocks) return fail(ctx, TC_ERR_OOM_POOL, "stitch: query %d needs %d blocks, max_blocks is %d", i, need[i], max_blocks);
+        need_total += need[i];
+        total_S += suffix_len[i];
+    }
+    if (need_total > (int64_t)ctx->free_seq.size())
+        return fail(ctx, TC_ERR_OOM_POOL, "stitch: need %lld sequence blocks, %zu free", (long long)need_total, ctx->free_seq.size());
+    if (total_S > INT32_MAX / 2) return fail(ctx, TC_ERR_INVALID, "stitch: batch too long");
+
+    // ---- build the plan (host side), then allocate
+    Plan p;
+    p.B = B; p.max_blocks = max_blocks; p.total_S = (int32_t)total_S;
+    p.block_table.assign((size_t)B * max_blocks, -1);
+    p.cu_seqlens.assign(B + 1, 0);
+    p.prefix_len = P;
+    p.suffix_len.assign(suffix_len, suffix_len + B);
+    for (int i = 0; i < B; ++i) p.cu_seqlens[i + 1] = p.cu_seqlens[i] + suffix_len[i];
+    auto next_free = ctx->free_seq.begin();
+    std::vector<StitchBlk> sblk;
+    for (int i = 0; i < B; ++i) {
+        int seg = i ? seg_end_of_q[i - 1] : 0;
+        for (int j = 0; j < need[i]; ++j, ++next_free) {
+            const int32_t phys = *next_free;
+            p.block_table[(size_t)i * max_blocks + j] = phys;
+            const int p0 = j * kBlockTokens;
+            if (p0 < P[i]) {
+                while (p0 >= segs[seg].start + segs[seg].len) ++seg;
+                sblk.push_back(StitchBlk{phys, seg, p0, i});
+            }
+        }
+    }
+    tc_status st = upload_plan(ctx, p, segs, seg_end_of_q, sblk, stream);
+    if (st != TC_OK) return st;               // nothing allocated yet
+
+    // ---- commit: take the blocks, order the gather after the loads it reads, launch
+    for (int i = 0; i < B; ++i)
+        for (int j = 0; j < need[i]; ++j) {
+            const int32_t phys = p.block_table[(size_t)i * max_blocks + j];
+            ctx->free_seq.erase(phys);
+            ctx->seq_used[phys - ctx->first_seq] = 1;
+        }
+    std::set<int32_t> used_slots;
+    for (const SegInfo &s : segs) used_slots.insert(s.slot);
+    for (int32_t s : used_slots) {
+        Slot &sl = ctx->slots[s];
+        if (sl.ready_pending && sl.ready_stream != stream)
+            TC_HIP(ctx, hipStreamWaitEvent(stream, sl.ready, 0));
+    }
+    ctx->plan = std::move(p);
+    TC_HIP(ctx, launch_stitch(ctx->geom, ctx->plan.dev, 0, L, stream));
+    if (!used_slots.empty()) {
+        const int32_t ev = ctx->read_next;
+        ctx->read_next = (ctx->read_next + 1) % (int32_t)ctx->read_ring.size();
+        TC_HIP(ctx, hipEventRecord(ctx->read_ring[ev], stream));
+        for (int32_t s : used_slots) ctx->slots[s].read_ev = ev;
+    }
+    if (B > 0) {
+        std::memcpy(block_table, ctx->plan.block_table.data(), (size_t)B * max_blocks * sizeof(int32_t));
+        std::memcpy(prefix_len, ctx->plan.prefix_len.data(), (size_t)B * sizeof(int32_t));
+    }
+    return TC_OK;
+}
+
+tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,
+                          void *out, const int32_t *cu_seqlens, const int32_t *block_table,
+                          int32_t max_blocks, const int32_t *prefix_len, const int32_t *suffix_len,
+                          int32_t B, float sm_scale, void *stream_)
+{
+    if (!ctx) return TC_ERR_INVALID;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, TC_ERR_INVALID, "attn: layer %d out of range", layer);
+    if (B < 0 || max_blocks < 0) return fail(ctx, TC_ERR_INVALID, "attn: negative size");
+    if (!(sm_scale > 0.f) || !std::isfinite(sm_scale)) return fail(ctx, TC_ERR_INVALID, "attn: sm_scale must be positive and finite");
+    if (B == 0) return TC_OK;
+    if (!cu_seqlens || !block_table || !prefix_len || !suffix_len) return fail(ctx, TC_ERR_INVALID, "attn: null integer argument");
+    hipStream_t stream = (hipStream_t)stream_;
+    Plan &cur = ctx->plan;
+    const bool same = cur.valid && cur.B == B && cur.max_blocks == max_blocks &&
+                      !std::memcmp(cur.cu_seqlens.data(), cu_seqlens, (size_t)(B + 1) * 4) &&
+                      !std::memcmp(cur.prefix_len.data(), prefix_len, (size_t)B * 4) &&
+                      !std::memcmp(cur.suffix_len.data(), suffix_len, (size_t)B * 4) &&
+                      !std::memcmp(cur.block_table.data(), block_table, (size_t)B * max_blocks * 4);
+    if (!same) {
+        // a caller-made batch: check every integer the kernels will index with, then plan it
+        if (cu_seqlens[0] != 0) return fail(ctx, TC_ERR_INVALID, "attn: cu_seqlens[0] != 0");
+        Plan p;
+        p.B = B; p.max_blocks = max_blocks;
+        for (int i = 0; i < B; ++i) {
+            if (prefix_len[i] < 0 || suffix_len[i] < 0 || cu_seqlens[i + 1] - cu_seqlens[i] != suffix_len[i])
+                return fail(ctx, TC_ERR_INVALID, "attn: lengths of query %d are inconsistent", i);
+            const int64_t nb = ((int64_t)prefix_len[i] + suffix_len[i] + kBlockTokens - 1) / kBlockTokens;
+            if (nb > max_blocks) return fail(ctx, TC_ERR_INVALID, "attn: query %d needs %lld blocks > max_blocks", i, (long long)nb);
+            for (int j = 0; j < nb; ++j) {
+                const int32_t b = block_table[(size_t)i * max_blocks + j];
+                if (b < ctx->first_seq || b >= ctx->cfg.n_pool_blocks)
+                    return fail(ctx, TC_ERR_INVALID, "attn: block_table[%d][%d] = %d is not a sequence block", i, j, b);
+            }
+        }
+        p.total_S = cu_seqlens[B];
+        p.block_table.assign(block_table, block_table + (size_t)B * max_blocks);
+        p.cu_seqlens.assign(cu_seqlens, cu_seqlens + B + 1);
+        p.prefix_len.assign(prefix_len, prefix_len + B);
+        p.suffix_len.assign(suffix_len, suffix_len + B);
+        tc_status st = upload_plan(ctx, p, {}, {}, {}, stream);
+        if (st != TC_OK) return st;
+        ctx->plan = std::move(p);
+    }
+    Plan &p = ctx->plan;
+    if (p.total_S == 0) return TC_OK;
+    if (!q || !k_new || !v_new || !out) return fail(ctx, TC_ERR_INVALID, "attn: null tensor");
+    if (((uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)out) & 15)
+        return fail(ctx, TC_ERR_INVALID, "attn: tensors must be 16-byte aligned");
+
+    TC_HIP(ctx, launch_append(ctx->geom, p.dev, layer, k_new, v_new, stream));
+    AttnArgs a{};
+    a.q = q; a.out = out; a.items = p.items_dev; a.n_items = p.n_items; a.layer = layer;
+    a.scale_log2 = sm_scale * 1.4426950408889634f;
+    a.part_o = ctx->d_part;
+    a.part_ml = ctx->d_part ? ctx->d_part + (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * ctx->cfg.head_dim : nullptr;
+    if (ctx->cfg.dtype == TC_BF16) TC_HIP(ctx, launch_attn_bf16(ctx->geom, p.dev, a, stream));
+    else TC_HIP(ctx, launch_attn_f32(ctx->geom, p.dev, a, stream));
+    if (p.max_splits > 1) TC_HIP(ctx, launch_merge(ctx->geom, p.dev, a, stream));
+    return TC_OK;
+}
+
+tc_status tc_release_seqs(tc_ctx *ctx, const int32_t *block_table, int32_t max_blocks, int32_t B)
+{
+    if (!ctx) return TC_ERR_INVALID;
+    if (B < 0 || max_blocks < 0 || ((int64_t)B * max_blocks > 0 && !block_table))
+        return fail(ctx, TC_ERR_INVALID, "release: bad arguments");
+    const size_t n = (size_t)B * max_blocks;
+    std::set<int32_t> seen;
+    for (size_t k = 0; k < n; ++k) {
+        const int32_t b = block_table[k];
+        if (b < 0) continue;
+        if (b < ctx->first_seq || b >= ctx->cfg.n_pool_blocks || !ctx->seq_used[b - ctx->first_seq] || !seen.insert(b).second)
+            return fail(ctx, TC_ERR_INVALID, "release: %d is not an allocated sequence block", b);
+    }
+    for (int32_t b : seen) {
+        ctx->seq_used[b - ctx->first_seq] = 0;
+        ctx->free_seq.insert(b);
+    }
+    if (ctx->plan.valid && !seen.empty()) ctx->plan.valid = false;   // its blocks may be handed out again
+    return TC_OK;
+}
+
+tc_status tc_read_seq_kv(tc_ctx *ctx, int32_t layer, const int32_t *blocks, int32_t n_tokens, void *out_k,
+                         void *out_v, void *stream_)
+{
+    if (!ctx) return TC_ERR_INVALID;
+    if (layer < 0 || layer >= ctx->cfg.n_layers || n_tokens < 0) return fail(ctx, TC_ERR_INVALID, "read: bad layer or length");
+    if (n_tokens == 0) return TC_OK;
+    if (!blocks || !out_k || !out_v) return fail(ctx, TC_ERR_INVALID, "read: null argument");
+    const int nb = (n_tokens + kBlockTokens - 1) / kBlockTokens;
+    for (int j = 0; j < nb; ++j)
+        if (blocks[j] < ctx->first_seq || blocks[j] >= ctx->cfg.n_pool_blocks)
+            return fail(ctx, TC_ERR_INVALID, "read: block %d is not a sequence block", blocks[j]);
+    hipStream_t stream = (hipStream_t)stream_;
+    const size_t bytes = (size_t)n_tokens * ctx->geom.row_bytes;
+    char *d_k = nullptr, *d_v = nullptr; int32_t *d_b = nullptr;
+    TC_HIP(ctx, hipMalloc((void **)&d_k, bytes));
+    TC_HIP(ctx, hipMalloc((void **)&d_v, bytes));
+    TC_HIP(ctx, hipMalloc((void **)&d_b, nb * sizeof(int32_t)));
+    tc_status st = TC_OK;
+    hipError_t e = hipMemcpyAsync(d_b, blocks, nb * sizeof(int32_t), hipMemcpyHostToDevice, stream);
+    if (e == hipSuccess) e = launch_readback(ctx->geom, layer, d_b, n_tokens, d_k, d_v, stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(out_k, d_k, bytes, hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(out_v, d_v, bytes, hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) st = fail(ctx, TC_ERR_HIP, "read: %s", hipGetErrorString(e));
+    (void)hipFree(d_k); (void)hipFree(d_v); (void)hipFree(d_b);
+    return st;
+}
+
+int32_t tc_kv_splits(const tc_ctx *ctx) { return (ctx && ctx->plan.valid) ? ctx->plan.max_splits : 1; }
+
+tc_status tc_set_kv_splits(tc_ctx *ctx, int32_t n_splits)
+{
+    if (!ctx || n_splits < 0) return TC_ERR_INVALID;
+    ctx->forced_splits = n_splits;
+    ctx->plan.valid = false;
+    return TC_OK;
+}
+
+}  // extern "C"

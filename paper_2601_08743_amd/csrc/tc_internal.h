@@ -1,0 +1,87 @@
+// Internal declarations shared by the host side of libtablecache and its kernel files.
+// Nothing here is part of the public ABI (see include/tablecache.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tc {
+
+constexpr int kBlockTokens = 16;     // tokens per pool block
+constexpr int kAttnRows = 128;       // bf16 kernel: rows (suffix token x group head) per work-group
+constexpr int kAttnKeys = 64;        // bf16 kernel: keys per tile (4 pool blocks)
+constexpr int kF32Rows = 4;          // fp32 kernel: rows per work-group (one per wave)
+constexpr int kF32Keys = 64;         // fp32 kernel: keys per tile
+
+// Pool geometry, passed by value to kernels.
+struct Geom {
+    char *pool;              // device base of the pool
+    int64_t layer_stride;    // bytes between the same block in consecutive layers
+    int64_t block_bytes;     // bytes of one block in one layer (K half then V half)
+    int64_t slot_bytes;      // bytes of one table slot in one layer (slot_blocks * block_bytes)
+    int32_t first_seq;       // first sequence block
+    int32_t n_blocks;        // total blocks
+    int32_t Hq, Hkv, D, G;
+    int32_t esize;           // bytes per element
+    int32_t row_bytes;       // Hkv * D * esize: one token's K (or V) row as registered
+    int32_t head_bytes;      // D * esize
+};
+
+// One destination block of a stitch: 16 logical positions p0 .. p0+15 of query q.
+struct StitchBlk {
+    int32_t phys;      // destination block id
+    int32_t seg;       // index (into the flattened segment arrays) of the segment holding p0
+    int32_t p0;        // logical position of slot 0
+    int32_t q;         // query index in the batch
+};
+
+// Device-side view of the current batch (all arrays int32, one upload per batch).
+struct BatchDev {
+    const int32_t *block_table;   // [B][max_blocks]
+    const int32_t *cu_seqlens;    // [B+1]
+    const int32_t *prefix_len;    // [B]
+    const int32_t *suffix_len;    // [B]
+    const int32_t *seg_start;     // [n_seg] logical start of segment within its query
+    const int32_t *seg_len;       // [n_seg]
+    const int32_t *seg_slot;      // [n_seg] table slot holding the segment's table
+    const int32_t *seg_end_of_q;  // [B] one past the last segment index of query q
+    const StitchBlk *stitch_blk;  // [n_stitch_blk]
+    const int32_t *splits_of_q;   // [B] split-KV partitions used for query q
+    const int32_t *tok_q;         // [sum S] query index of each suffix token
+    int32_t B, max_blocks, total_S, n_stitch_blk;
+};
+
+// One unit of attention work: a tile of rows of one (query, KV head) against a range of key tiles.
+struct AttnItem {
+    int32_t q;
+    int32_t kvh;
+    int32_t m0;          // first row (row = suffix_token * G + head_in_group)
+    int32_t tile_begin;  // first key tile
+    int32_t tile_end;    // one past the last key tile
+    int32_t split;       // which partition this is (0 when n_splits == 1)
+    int32_t n_splits;    // partitions of this query
+    int32_t pad;
+};
+
+struct AttnArgs {
+    const void *q;
+    void *out;
+    const AttnItem *items;
+    float *part_o;       // [max_splits][total_S][Hq][D] unnormalised partial outputs
+    float *part_ml;      // [max_splits][total_S][Hq][2] (reference max in log2 units, sum)
+    float scale_log2;    // sm_scale * log2(e)
+    int32_t layer;
+    int32_t n_items;
+};
+
+// kv_stitch.hip
+hipError_t launch_stitch(const Geom &g, const BatchDev &b, int l0, int l1, hipStream_t s);
+hipError_t launch_append(const Geom &g, const BatchDev &b, int layer, const void *k_new,
+                         const void *v_new, hipStream_t s);
+hipError_t launch_readback(const Geom &g, int layer, const int32_t *blocks_dev, int n_tokens,
+                           void *k_out_dev, void *v_out_dev, hipStream_t s);
+// prefill_attn_bf16.hip / prefill_attn_f32.hip
+hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, hipStream_t s);
+hipError_t launch_attn_f32(const Geom &g, const BatchDev &b, const AttnArgs &a, hipStream_t s);
+hipError_t launch_merge(const Geom &g, const BatchDev &b, const AttnArgs &a, hipStream_t s);
+
+}  // namespace tc
