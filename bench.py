@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the TableCache hot path on one MI355X.
+
+A step is one pass of the whole path over one batch: tc_stitch_kv (gather of the selected
+tables' KV into sequence blocks, all layers) followed by tc_prefill_attn for every layer
+(suffix K/V append, GQA prefill attention, split-KV merge), then the host-side release of
+the sequence blocks.  Inputs (table KV in the device table cache, per-layer q/k/v) are
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0          # MI355X dense bf16 matrix peak
+PEAK_FP32_TFLOPS = 157.3           # MI355X fp32 vector peak
+PEAK_HBM_GBPS = 8000.0
+
+
+def attn_flops_per_layer(cfg, P, S):
+    """4*Hq*D per unmasked (row, key) pair: QK^T and PV, 2 flops per multiply-add."""
+    return sum(4 * cfg.n_q_heads * cfg.head_dim * (int(s) * int(p) + int(s) * (int(s) + 1) // 2)
+               for p, s in zip(P, S))
+
+
+def read_traffic(workload):
+    """HBM bytes per attention launch from the committed counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "prefill_attn_bf16_%s_pmc.txt" % workload)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--splits", type=int, default=0, help="force split-KV partitions (0 = automatic)")
+    ap.add_argument("--row-blocks", type=int, default=0, help="force 128 (1) or 256 (2) rows per work-group")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true", help="also time the layer loop replayed as a HIP graph")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2601_08743_amd import binding as B          # raises if the HIP library is not built
+    from paper_2601_08743_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    wl = W.get(args.workload)
+    c = wl.cfg
+    t_setup = time.time()
+    P = np.array([int(wl.table_len[q].sum()) for q in wl.queries])
+    S = wl.suffix_len.astype(int)
+    need = [-(-(int(p) + int(s)) // 16) for p, s in zip(P, S)]
+    max_blocks = max(need) + 1
+    max_tok = int(wl.table_len.max())
+    cap = c.capacity
+    n_blocks = cap * (-(-max_tok // 16)) + sum(need) + 8
+    cfg = B.make_config(c.n_layers, c.n_q_heads, c.n_kv_heads, c.head_dim,
+                        B.TC_F32 if c.dtype == "f32" else B.TC_BF16, n_blocks, cap, max_tok)
+    pool = torch.empty(B.tc_pool_bytes(cfg), dtype=torch.uint8, device="cuda")
+    ctx = B.Context(cfg, pool)
+    stream = torch.cuda.Stream()
+
+    # offline part: register every table of the database, make the cache warm
+    resident = list(range(c.n_tables))[:cap]
+    tables_np = {}
+    for t in range(c.n_tables):
+        k, v = wl.table_kv(t)
+        hk, hv = torch.from_numpy(k).pin_memory(), torch.from_numpy(v).pin_memory()
+        ctx.tc_register_table_kv(t, int(wl.table_len[t]), hk, hv)
+        if t in set(wl.table_ids.tolist()):
+            tables_np[t] = (k, v)
+    ctx.tc_load_async(resident, 0, c.n_layers, stream)
+    missing = [int(t) for t in wl.table_ids if t not in set(resident)]
+    if missing:
+        raise SystemExit("workload %s needs the loading pipeline (tables %s not resident)" % (c.name, missing[:5]))
+    tdt = torch.float32 if c.dtype == "f32" else torch.bfloat16
+
+    def dev(a):
+        t = torch.from_numpy(np.ascontiguousarray(a))
+        return (t if c.dtype == "f32" else t.view(torch.bfloat16)).cuda()
+
+    qkv_np = [wl.suffix_qkv(l) for l in range(c.n_layers)]
+    qkv = [tuple(dev(x) for x in qkv_np[l]) for l in range(c.n_layers)]
+    outs = [torch.empty_like(qkv[l][0]) for l in range(c.n_layers)]
+    torch.cuda.synchronize()
+    setup_s = time.time() - t_setup
+    if args.splits:
+        ctx.tc_set_kv_splits(args.splits)
+    if args.row_blocks:
+        ctx.tc_set_row_blocks(args.row_blocks)
+
+    ids, cu_t, cu_s, sl = wl.table_ids, wl.cu_tables, wl.cu_seqlens, wl.suffix_len
+    scale = wl.sm_scale
+
+    def layers(bt, pl):
+        for l in range(c.n_layers):
+            q, k, v = qkv[l]
+            ctx.tc_prefill_attn(l, q, k, v, outs[l], cu_s, bt, pl, sl, scale, stream)
+
+    def step():
+        bt, pl = ctx.tc_stitch_kv(ids, cu_t, sl, max_blocks, stream)
+        layers(bt, pl)
+        return bt
+
+    def run(n):
+        """n steps; the blocks of a step are released once the next step has been enqueued on the
+        same stream (stream order makes that safe for the kernels of the earlier step)."""
+        for _ in range(n):
+            bt = step()
+            ctx.tc_release_seqs(bt)
+
+    for _ in range(args.warmup):
+        run(1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-kernel durations: HIP events around every launch, on the launch stream
+    ctx.tc_profile_enable(True)
+    run(args.steps)
+    torch.cuda.synchronize()
+    prof = ctx.tc_profile_read()
+    ctx.tc_profile_enable(False)
+    n_splits = None
+    bt, pl = ctx.tc_stitch_kv(ids, cu_t, sl, max_blocks, stream)
+    n_splits = ctx.tc_kv_splits()
+
+    flops_layer = attn_flops_per_layer(c, P, S)
+    flops_step = flops_layer * c.n_layers
+    kappa = 2 * c.n_kv_heads * c.head_dim * c.elem_bytes
+    stitch_bytes = 2 * kappa * c.n_layers * int(P.sum())
+    attn_us = prof["attn"][0] * 1e3 / max(prof["attn"][1], 1)
+    merge_us = prof["merge"][0] * 1e3 / max(prof["merge"][1], 1)
+    append_us = prof["append"][0] * 1e3 / max(prof["append"][1], 1)
+    stitch_us = prof["stitch"][0] * 1e3 / max(prof["stitch"][1], 1)
+    attn_tflops_kernel = flops_layer / (attn_us * 1e-6) / 1e12
+    peak = PEAK_BF16_TFLOPS if c.dtype == "bf16" else PEAK_FP32_TFLOPS
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    extra = {}
+    if args.graph:
+        g = torch.cuda.CUDAGraph()
+        layers(bt, pl)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=stream):
+            layers(bt, pl)
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        extra["graph_layers_ms"] = round(g_ms, 4)
+        extra["graph_layers_tflops"] = round(flops_step / (g_ms * 1e-3) / 1e12, 2)
+
+    # CPU baseline: the checker as it stands, on the same workload (also a parity spot check)
+    cpu = None
+    parity = None
+    if not args.no_cpu_baseline:
+        import oracle
+        layers(bt, pl)
+        torch.cuda.synchronize()
+        n_layers_cpu = c.n_layers
+        est = flops_step / 10e9
+        if est > 40:                        # bound the sample to roughly 10-30 s of CPU work
+            n_layers_cpu = max(1, int(c.n_layers * 25 / est))
+        t_cpu, worst = 0.0, 0.0
+        qs = list(range(c.batch))
+        for l in range(n_layers_cpu):
+            q_np, k_np, v_np = qkv_np[l]
+            got = outs[l].float().cpu().numpy().astype(np.float64)
+            for i in qs:
+                tk = {int(t): tables_np[int(t)][0][l:l + 1] for t in wl.queries[i]}
+                tv = {int(t): tables_np[int(t)][1][l:l + 1] for t in wl.queries[i]}
+                ks, vs = oracle.stitch(tk, wl.queries[i])[0], oracle.stitch(tv, wl.queries[i])[0]
+                s_ = slice(int(cu_s[i]), int(cu_s[i + 1]))
+                a = [W.storage_to_f64(x, c.dtype) for x in (q_np[s_], ks, vs, k_np[s_], v_np[s_])]
+                t1 = time.perf_counter()
+                ref = oracle.prefill_attn(*a, scale)
+                t_cpu += time.perf_counter() - t1
+                worst = max(worst, float(np.abs(got[s_] - ref).max()))
+        cpu = {"value": round(flops_layer * n_layers_cpu / t_cpu / 1e12, 6), "unit": "TFLOP/s",
+               "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "%s, all queries and heads, layers 0..%d of %d (%.1f s of fp64 naive attention)" %
+                         (c.name, n_layers_cpu - 1, c.n_layers, t_cpu)}
+        parity = worst
+    ctx.tc_release_seqs(bt)
+
+    res = {
+        "metric": "suffix prefill attn TFLOP/s (whole step: KV stitch + per-layer append, attention, split-KV merge)",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": c.dtype, "data": "synthetic",
+        "config": {"workload": "%s: L=%d Hq=%d Hkv=%d D=%d, %d tables U[%d,%d] tok, B=%d, P=%s, S=%s, block 16" % (
+            c.name, c.n_layers, c.n_q_heads, c.n_kv_heads, c.head_dim, c.n_tables, c.table_len[0],
+            c.table_len[1], c.batch, P.tolist() if c.batch <= 4 else "sum %d" % P.sum(),
+            S.tolist() if c.batch <= 4 else "sum %d" % S.sum()), "kv_splits": n_splits},
+        "prefill_ms_per_query": round(ms_per_step / c.batch, 4),
+        "attn_kernel_us": round(attn_us, 2), "merge_kernel_us": round(merge_us, 2),
+        "append_kernel_us": round(append_us, 2), "stitch_kernel_us": round(stitch_us, 2),
+        "attn_tflops_kernel_time": round(attn_tflops_kernel, 2),
+        "stitch_gbps": round(stitch_bytes / (stitch_us * 1e-6) / 1e9, 1),
+        "stitch_frac_hbm": round(stitch_bytes / (stitch_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4),
+        "roofline": {"bound": "mfma" if c.dtype == "bf16" else "alu", "achieved": round(attn_tflops_kernel, 2),
+                     "peak": peak, "unit": "TFLOP/s", "frac": round(attn_tflops_kernel / peak, 4),
+                     "traffic": read_traffic(c.name), "kernel": "attn_%s_kernel" % c.dtype},
+        "cpu_baseline": cpu, "parity_max_abs_vs_oracle": parity, "setup_s": round(setup_s, 1),
+    }
+    res.update(extra)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

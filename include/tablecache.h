@@ -193,6 +193,20 @@ tc_status tc_read_seq_kv(tc_ctx *ctx, int32_t layer, const int32_t *blocks, int3
  * current batch (1 = no split); tc_set_kv_splits forces a value (0 = automatic). */
 int32_t tc_kv_splits(const tc_ctx *ctx);
 tc_status tc_set_kv_splits(tc_ctx *ctx, int32_t n_splits);
+/* Rows per attention work-group of the bf16 kernel: 1 = 128 rows, 2 = 256 rows (each wave holds two
+ * blocks of 32 rows and reuses every K/V fragment twice), 0 = automatic (256 when the batch still
+ * yields enough work-groups to fill the chip).  Results do not depend on it beyond rounding. */
+tc_status tc_set_row_blocks(tc_ctx *ctx, int32_t row_blocks);
+
+/*
+ * Measurement support.  With profiling on, every kernel the library launches is bracketed by
+ * two HIP timing events on the stream it is launched on.  tc_profile_read waits for them and
+ * returns, per kernel kind (0 stitch, 1 append, 2 attention, 3 split-KV merge), the summed
+ * elapsed milliseconds and the number of launches since the previous read.
+ *   ms_out HOST double[4], count_out HOST int64_t[4].
+ */
+tc_status tc_profile_enable(tc_ctx *ctx, int32_t on);
+tc_status tc_profile_read(tc_ctx *ctx, double *ms_out, int64_t *count_out);
 
 /* Text for the most recent error on this context; library-owned, valid until the next call. */
 const char *tc_last_error(const tc_ctx *ctx);

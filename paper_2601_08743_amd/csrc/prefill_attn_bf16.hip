@@ -6,12 +6,24 @@
 // rows are packed into one M dimension (row = token * G + head_in_group): a K/V tile is
 // fetched once per KV head and shared by G*S rows, which is what makes the op compute-bound.
 //
-// Work-group: 4 waves, 128 rows, key tiles of 64 (= 4 pool blocks).  Each wave owns 32 rows and
-// computes the TRANSPOSED score tile S^T[key][row] = K . Q^T with v_mfma_f32_32x32x16_bf16, so
+// Work-group: 4 waves, key tiles of 64 (= 4 pool blocks).  Each wave owns one or two blocks of 32
+// rows (128 or 256 rows per work-group) and, per row block, computes the TRANSPOSED score tile S^T[key][row] = K . Q^T with v_mfma_f32_32x32x16_bf16, so
 // that every lane holds scores of ONE row (column l%32 of the accumulator): row max, row sum and
 // the output rescale need no cross-lane traffic except one exchange between lanes l and l^32.
 // The exponentials, packed to bf16, are directly the B operand of O^T[d][row] += V^T . P^T; the
 // pool stores V transposed inside a block with the token order the operand wants (kv_stitch.hip).
+//
+// Memory pipeline: the work item carries the block ids of its first two tiles, the rest are
+// fetched into LDS once; each iteration handles two key tiles, whose K/V travel global ->
+// registers (issued a whole iteration ahead) -> two LDS buffers.  At batch 1 the kernel is
+// latency-bound, so the depth of this pipeline and the length of the dependent-load chain at
+// start-up are what matter.
+//
+// Split-KV: when a query is cut into key partitions, every work-group stores its unnormalised
+// partial (O, max, sum) in accumulator-fragment order (1 KB contiguous per wave and fragment) and
+// a second kernel combines the partitions.  (Combining inside this kernel - last work-group to
+// arrive folds the others in - was measured 3x slower: device-scope release/acquire on this chip
+// writes back and invalidates the XCD's whole L2, which every work-group would do.)
 #include "tc_internal.h"
 
 namespace tc {
@@ -20,146 +32,251 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kKRow = 272;            // LDS bytes per K row: 256 + 16 pad (conflict-free b128 reads)
-constexpr int kHeadBlk = 4096;        // bytes of one head's K (or V) in one block: 16 * 128 * 2
-constexpr float kRescaleThresh = 8.f; // log2 units: rescale O only when the max grew by more
+constexpr int kKRow = 272;                       // LDS bytes per K row: 256 + 16 pad (conflict-free b128 reads)
+constexpr int kHeadBlk = 4096;                   // bytes of one head's K (or V) in one block: 16 * 128 * 2
+constexpr int kKTile = kAttnKeys * kKRow;        // 17408
+constexpr int kVTile = 4 * kHeadBlk;             // 16384
+constexpr int kStage = kKTile + kVTile;          // one LDS buffer
+constexpr int kBidBytes = kAttnMaxTiles * 4 * 4; // block ids of the item's key range
+constexpr int kLdsBytes = 2 * kStage + kBidBytes;
+constexpr float kRescaleThresh = 8.f;            // log2 units: rescale O only when the max grew by more
 
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(Geom g, BatchDev b, AttnArgs a)
+// Per-lane state of RB row blocks (each row block = 32 rows of the wave, one row per lane pair).
+template <int RB>
+struct RowState {
+    f32x16 o[RB][4];
+    float m_run[RB], l_lane[RB];
+};
+
+// One key tile for RB row blocks: scores, online softmax, PV.  k_ld / v_ld already point at this
+// lane's operands.  Every K and V fragment read from LDS feeds RB matrix instructions: with
+// RB = 2 the LDS traffic per flop is half that of RB = 1, which is what the LDS (about 100 B per
+// clock and CU, measured) can sustain next to the matrix cores.
+template <int RB>
+__device__ __forceinline__ void tile_math(RowState<RB> &st, const bf16x8 (&qf)[RB][8], const char *k_ld,
+                                          const char *v_ld, int key0, const int (&limit)[RB],
+                                          bool need_mask, int hh, float c)
 {
-    __shared__ __attribute__((aligned(16))) char lds_k[kAttnKeys * kKRow];
-    __shared__ __attribute__((aligned(16))) char lds_v[4 * kHeadBlk];
-
-    const AttnItem it = a.items[blockIdx.x];
-    if (it.q < 0) return;                              // padding item (uniform for the work-group)
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, hh = lane >> 5;
-    const int i = it.q, G = g.G;
-    const int P = b.prefix_len[i], S = b.suffix_len[i], cu = b.cu_seqlens[i];
-    const int n_blk = (P + S + kBlockTokens - 1) >> 4;
-    const int m_rows = S * G;
-    const int row_m = it.m0 + w * 32 + r32;
-    const bool valid = row_m < m_rows;
-    const int rm = valid ? row_m : m_rows - 1;
-    const int s_tok = rm / G;
-    const int head = it.kvh * G + (rm - s_tok * G);
-    const int limit = P + s_tok;                                    // last visible key of this row
-    const int wave_limit_min = P + min(it.m0 + w * 32, m_rows - 1) / G;
-    const int32_t *bt = b.block_table + (int64_t)i * b.max_blocks;
-    const char *layer_base = g.pool + (int64_t)a.layer * g.layer_stride + (int64_t)it.kvh * kHeadBlk + tid * 16;
-    const int64_t v_half = g.block_bytes >> 1;
-
-    // Q^T fragments (B operand): lane (row r32, half hh) holds q[row][16*ks + 8*hh .. +8]
-    bf16x8 qf[8];
-    {
-        const char *qp = (const char *)a.q + ((int64_t)(cu + s_tok) * g.Hq + head) * 256 + hh * 16;
+    f32x16 sacc[RB][2];
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8 *)(qp + ks * 32);
-    }
-
-    f32x16 o[4];
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[db][e] = 0.f;
-    float m_run = -INFINITY, l_lane = 0.f;
-    const float c = a.scale_log2;
-
-    // next tile's K/V chunks, prefetched into registers (named scalars: arrays here end up in scratch)
-    uint4 k0, k1, k2, k3, v0, v1, v2, v3;
-#define TC_LOAD_BLK(t_, j_, kx_, vx_)                                                             \
-    {                                                                                             \
-        int jb = (t_) * 4 + (j_);                                                                 \
-        jb = jb < n_blk ? jb : n_blk - 1; /* past the end: a valid block, masked below */         \
-        const char *src = layer_base + (int64_t)bt[jb] * g.block_bytes;                           \
-        kx_ = *(const uint4 *)src;                                                                \
-        vx_ = *(const uint4 *)(src + v_half);                                                     \
-    }
-#define TC_LOAD_TILE(t_) TC_LOAD_BLK(t_, 0, k0, v0) TC_LOAD_BLK(t_, 1, k1, v1) TC_LOAD_BLK(t_, 2, k2, v2) TC_LOAD_BLK(t_, 3, k3, v3)
-    char *k_st = lds_k + (tid >> 4) * kKRow + (tid & 15) * 16;
-    char *v_st = lds_v + tid * 16;
-    const char *k_ld = lds_k + r32 * kKRow + hh * 16;
-    const char *v_ld = lds_v + r32 * 32 + hh * 16;
-
-    TC_LOAD_TILE(it.tile_begin)
-    for (int t = it.tile_begin; t < it.tile_end; ++t) {
-        __syncthreads();                               // previous tile fully consumed
-        *(uint4 *)(k_st) = k0;                  *(uint4 *)(v_st) = v0;
-        *(uint4 *)(k_st + 16 * kKRow) = k1;     *(uint4 *)(v_st + kHeadBlk) = v1;
-        *(uint4 *)(k_st + 32 * kKRow) = k2;     *(uint4 *)(v_st + 2 * kHeadBlk) = v2;
-        *(uint4 *)(k_st + 48 * kKRow) = k3;     *(uint4 *)(v_st + 3 * kHeadBlk) = v3;
-        __syncthreads();
-        if (t + 1 < it.tile_end) { TC_LOAD_TILE(t + 1) }   // in flight during the math below
-
-        // S^T[key][row]: two 32-key blocks, contraction over D = 8 steps of 16
-        f32x16 sacc[2];
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) sacc[mb][e] = 0.f;
+            for (int e = 0; e < 16; ++e) sacc[rb][mb][e] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
+    for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
-                const bf16x8 ka = *(const bf16x8 *)(k_ld + mb * 32 * kKRow + ks * 32);
-                sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], sacc[mb], 0, 0, 0);
-            }
-
-        const int key0 = t * kAttnKeys;
-        if (key0 + kAttnKeys - 1 > wave_limit_min) {   // causal edge or ragged tail in this tile
+        for (int mb = 0; mb < 2; ++mb) {
+            const bf16x8 ka = *(const bf16x8 *)(k_ld + mb * 32 * kKRow + ks * 32);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                sacc[rb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[rb][ks], sacc[rb][mb], 0, 0, 0);
+        }
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        if (need_mask) {                               // causal edge or ragged tail in this tile
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int key = key0 + 32 * mb + 8 * (e >> 2) + 4 * hh + (e & 3);
-                    if (key > limit) sacc[mb][e] = -INFINITY;
+                    if (key > limit[rb]) sacc[rb][mb][e] = -INFINITY;
                 }
         }
-        float mx = sacc[0][0];
+        float mx = sacc[rb][0][0];
 #pragma unroll
-        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sacc[0][e]);
+        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sacc[rb][0][e]);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[1][e]);
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[rb][1][e]);
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float mxs = mx * c;
-        if (__any(mxs > m_run + kRescaleThresh)) {     // also taken while m_run is still -inf
-            const float m_new = fmaxf(m_run, mxs);
-            const float alpha = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run - m_new);
-            l_lane *= alpha;
+        if (__any(mxs > st.m_run[rb] + kRescaleThresh)) {   // also taken while m_run is still -inf
+            const float m_new = fmaxf(st.m_run[rb], mxs);
+            const float alpha = (st.m_run[rb] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m_run[rb] - m_new);
+            st.l_lane[rb] *= alpha;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
-            m_run = m_new;
+                for (int e = 0; e < 16; ++e) st.o[rb][db][e] *= alpha;
+            st.m_run[rb] = m_new;
         }
-        const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
+        const float neg_m = (st.m_run[rb] == -INFINITY) ? 0.f : -st.m_run[rb];
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][e], c, neg_m));
-                sacc[mb][e] = p;
-                l_lane += p;
+                const float p = __builtin_amdgcn_exp2f(fmaf(sacc[rb][mb][e], c, neg_m));
+                sacc[rb][mb][e] = p;
+                st.l_lane[rb] += p;
             }
-
-        // O^T[d][row] += V^T[d][key] P^T[key][row]: four 16-key groups (one pool block each)
+    }
+    // O^T[d][row] += V^T[d][key] P^T[key][row]: four 16-key groups (one pool block each)
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 pf;
+    for (int kk = 0; kk < 4; ++kk) {
+        bf16x8 pf[RB];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) pf[e] = (__bf16)sacc[kk >> 1][8 * (kk & 1) + e];
+        for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                const bf16x8 va = *(const bf16x8 *)(v_ld + kk * kHeadBlk + db * 32 * 32);
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf, o[db], 0, 0, 0);
-            }
+            for (int e = 0; e < 8; ++e) pf[rb][e] = (__bf16)sacc[rb][kk >> 1][8 * (kk & 1) + e];
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            const bf16x8 va = *(const bf16x8 *)(v_ld + kk * kHeadBlk + db * 32 * 32);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                st.o[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[rb], st.o[rb][db], 0, 0, 0);
         }
     }
+}
 
-#undef TC_LOAD_TILE
-#undef TC_LOAD_BLK
-    const float l = l_lane + __shfl_xor(l_lane, 32);
-    if (!valid) return;
-    const int64_t row = (int64_t)(cu + s_tok) * g.Hq + head;
-    if (it.n_splits == 1) {
+// RB = row blocks per wave: the work-group covers 128 * RB rows.  RB = 1 runs two work-groups per
+// CU (small problems: more, smaller work items); RB = 2 one per CU with twice the work per LDS byte.
+template <int RB>
+__global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g, BatchDev b, AttnArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    int32_t *s_bid = (int32_t *)(lds + 2 * kStage);
+
+    const AttnItem it = a.items[blockIdx.x];
+    if (it.q < 0) return;                              // padding item (uniform for the work-group)
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, hh = lane >> 5;
+    const int G = g.G, P = it.P, S = it.S;
+    const int n_blk = (P + S + kBlockTokens - 1) >> 4;
+    const int m_rows = S * G;
+    const int wave_row0 = it.m0 + w * 32 * RB;
+    bool valid[RB];
+    int s_tok[RB], head[RB], limit[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int row_m = wave_row0 + rb * 32 + r32;
+        valid[rb] = row_m < m_rows;
+        const int rm = valid[rb] ? row_m : m_rows - 1;
+        s_tok[rb] = rm / G;
+        head[rb] = it.kvh * G + (rm - s_tok[rb] * G);
+        limit[rb] = P + s_tok[rb];                     // last visible key of this row
+    }
+    const int wave_limit_min = P + min(wave_row0, m_rows - 1) / G;
+    const int n_tiles = it.tile_end - it.tile_begin, last = n_tiles - 1;
+    const char *src_base = g.pool + (int64_t)a.layer * g.layer_stride + (int64_t)it.kvh * kHeadBlk + tid * 16;
+    const int64_t v_half = g.block_bytes >> 1;
+    const int64_t bb = g.block_bytes;
+
+    // Q^T fragments (B operand): lane (row r32, half hh) holds q[row][16*ks + 8*hh .. +8].
+    // Issued before any K/V load: vector loads return in order, so once the first K/V tile has
+    // arrived these have too, and no wait on them is left inside the tile loop (a wait there
+    // would drain the K/V prefetches every iteration).
+    bf16x8 qf[RB][8];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const char *qp = (const char *)a.q + ((int64_t)(it.cu + s_tok[rb]) * g.Hq + head[rb]) * 256 + hh * 16;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[rb][ks] = *(const bf16x8 *)(qp + ks * 32);
+    }
+    // named prefetch registers (arrays of uint4 end up in scratch): set A and set B
+    uint4 ka0, ka1, ka2, ka3, va0, va1, va2, va3;
+    uint4 kb0, kb1, kb2, kb3, vb0, vb1, vb2, vb3;
+#define TC_LD(kx, vx, bid_)                                              \
+    {                                                                    \
+        const char *src = src_base + (int64_t)(bid_) * bb;               \
+        kx = *(const uint4 *)src;                                        \
+        vx = *(const uint4 *)(src + v_half);                             \
+    }
+    // first two tiles: block ids come with the item
+    TC_LD(ka0, va0, it.bid[0]) TC_LD(ka1, va1, it.bid[1]) TC_LD(ka2, va2, it.bid[2]) TC_LD(ka3, va3, it.bid[3])
+    // Every prefetch below is issued unconditionally (past the end of the range the tile index is
+    // clamped and the data never used): with loads under a condition the compiler cannot count
+    // how many are outstanding and falls back to waiting for all of them, which empties the pipeline.
+    TC_LD(kb0, vb0, it.bid[4]) TC_LD(kb1, vb1, it.bid[5]) TC_LD(kb2, vb2, it.bid[6]) TC_LD(kb3, vb3, it.bid[7])
+    // block ids of the whole key range -> LDS
+    {
+        const int32_t *bt = b.block_table + (int64_t)it.q * b.max_blocks;
+        for (int idx = tid; idx < n_tiles * 4; idx += 256) {
+            int jb = it.tile_begin * 4 + idx;
+            jb = jb < n_blk ? jb : n_blk - 1;          // past the end: a valid block, masked in the math
+            s_bid[idx] = bt[jb];
+        }
+    }
+    RowState<RB> st;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) st.o[rb][db][e] = 0.f;
+        st.m_run[rb] = -INFINITY;
+        st.l_lane[rb] = 0.f;
+    }
+    const float c = a.scale_log2;
+
+    char *k_st = lds + (tid >> 4) * kKRow + (tid & 15) * 16;        // + stage * kStage
+    char *v_st = lds + kKTile + tid * 16;
+    const char *k_ld = lds + r32 * kKRow + hh * 16;
+    const char *v_ld = lds + kKTile + r32 * 32 + hh * 16;
+#define TC_ST(stage_, k0_, k1_, k2_, k3_, v0_, v1_, v2_, v3_)                                   \
+    {                                                                                             \
+        char *kd = k_st + (stage_) * kStage, *vd = v_st + (stage_) * kStage;                      \
+        *(uint4 *)(kd) = k0_;              *(uint4 *)(vd) = v0_;                                  \
+        *(uint4 *)(kd + 16 * kKRow) = k1_; *(uint4 *)(vd + kHeadBlk) = v1_;                       \
+        *(uint4 *)(kd + 32 * kKRow) = k2_; *(uint4 *)(vd + 2 * kHeadBlk) = v2_;                   \
+        *(uint4 *)(kd + 48 * kKRow) = k3_; *(uint4 *)(vd + 3 * kHeadBlk) = v3_;                   \
+    }
+#define TC_LD_TILE_A(r_)                                                                          \
+    {                                                                                             \
+        const int32_t *bp = s_bid + (r_) * 4;                                                     \
+        TC_LD(ka0, va0, bp[0]) TC_LD(ka1, va1, bp[1]) TC_LD(ka2, va2, bp[2]) TC_LD(ka3, va3, bp[3]) \
+    }
+#define TC_LD_TILE_B(r_)                                                                          \
+    {                                                                                             \
+        const int32_t *bp = s_bid + (r_) * 4;                                                     \
+        TC_LD(kb0, vb0, bp[0]) TC_LD(kb1, vb1, bp[1]) TC_LD(kb2, vb2, bp[2]) TC_LD(kb3, vb3, bp[3]) \
+    }
+
+    // Two key tiles (128 keys) per iteration: their K/V are loaded into the two register sets
+    // one whole iteration before they are stored to LDS, so the only wait the loads ever need is
+    // "all outstanding", at a point where a full iteration of math has covered their latency.
+    for (int r = 0; r < n_tiles; r += 2) {
+        __syncthreads();                               // both LDS stages free (s_bid visible on the first pass)
+        TC_ST(0, ka0, ka1, ka2, ka3, va0, va1, va2, va3)
+        TC_ST(1, kb0, kb1, kb2, kb3, vb0, vb1, vb2, vb3)
+        __syncthreads();
+        TC_LD_TILE_A(min(r + 2, last))
+        TC_LD_TILE_B(min(r + 3, last))
+        {
+            const int key0 = (it.tile_begin + r) * kAttnKeys;
+            tile_math<RB>(st, qf, k_ld, v_ld, key0, limit, key0 + kAttnKeys - 1 > wave_limit_min, hh, c);
+        }
+        if (r + 1 < n_tiles) {
+            const int key0 = (it.tile_begin + r + 1) * kAttnKeys;
+            tile_math<RB>(st, qf, k_ld + kStage, v_ld + kStage, key0, limit,
+                          key0 + kAttnKeys - 1 > wave_limit_min, hh, c);
+        }
+    }
+#undef TC_LD
+#undef TC_ST
+#undef TC_LD_TILE_A
+#undef TC_LD_TILE_B
+
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const float l = st.l_lane[rb] + __shfl_xor(st.l_lane[rb], 32);
+        if (it.n_splits > 1) {
+            // partial in accumulator-fragment order: 1 KB contiguous per (row block, db, q4);
+            // a group's slot holds 4 * RB row blocks of 32 rows
+            const int64_t slot = (int64_t)it.split * it.n_groups + it.group;
+            const int blk = w * RB + rb;
+            float4 *po = (float4 *)a.part_o + ((slot * (4 * RB) + blk) * 16) * 64 + lane;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    po[(db * 4 + q4) * 64] = make_float4(st.o[rb][db][4 * q4], st.o[rb][db][4 * q4 + 1],
+                                                         st.o[rb][db][4 * q4 + 2], st.o[rb][db][4 * q4 + 3]);
+            if (hh == 0)
+                ((float2 *)a.part_ml)[(slot * (4 * RB) + blk) * 32 + r32] = make_float2(st.m_run[rb], l);
+            continue;
+        }
+        if (!valid[rb]) continue;
+        const int64_t row = (int64_t)(it.cu + s_tok[rb]) * g.Hq + head[rb];
         const float inv = 1.f / l;
         char *op = (char *)a.out + row * 256 + hh * 8;
 #pragma unroll
@@ -168,28 +285,81 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(Geom g, BatchDev b, A
             for (int q4 = 0; q4 < 4; ++q4) {
                 bf16x4 v;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (__bf16)(o[db][4 * q4 + e] * inv);
+                for (int e = 0; e < 4; ++e) v[e] = (__bf16)(st.o[rb][db][4 * q4 + e] * inv);
                 *(bf16x4 *)(op + (32 * db + 8 * q4) * 2) = v;
             }
-    } else {
-        const int64_t prow = (int64_t)it.split * b.total_S * g.Hq + row;
-        float *op = a.part_o + prow * 128 + hh * 4;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                float4 v = make_float4(o[db][4 * q4], o[db][4 * q4 + 1], o[db][4 * q4 + 2], o[db][4 * q4 + 3]);
-                *(float4 *)(op + 32 * db + 8 * q4) = v;
-            }
-        if (hh == 0) { a.part_ml[prow * 2] = m_run; a.part_ml[prow * 2 + 1] = l; }
     }
 }
 
-hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, hipStream_t s)
+// Combine the partitions of split queries.  One thread per float4 of a group's accumulator
+// fragment: index = ((group * n_rb + row_block) * 16 + fragment) * 64 + lane, the order the
+// attention kernel stored it in, so loads are fully coalesced.  With reference maxima m_s, sums
+// l_s and unnormalised partial outputs O_s:  out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+__global__ __launch_bounds__(256) void merge_bf16_kernel(Geom g, AttnArgs a, const MergeGroup *groups,
+                                                         int n_groups, int n_rb)
+{
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    const int lane = idx & 63, frag = (idx >> 6) & 15, gb = idx >> 10;
+    const int group = gb / n_rb, blk = gb - group * n_rb;
+    if (group >= n_groups) return;
+    const MergeGroup mg = groups[group];
+    if (mg.n_splits <= 1) return;                      // written directly by the attention kernel
+    const int r32 = lane & 31, hh = lane >> 5;
+    const int row_m = mg.m0 + blk * 32 + r32;
+    if (row_m >= mg.S * g.G) return;
+    float M = -INFINITY;
+    for (int s = 0; s < mg.n_splits; ++s)
+        M = fmaxf(M, ((const float2 *)a.part_ml)[(((int64_t)s * n_groups + group) * n_rb + blk) * 32 + r32].x);
+    float l = 0.f;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < mg.n_splits; ++s) {
+        const int64_t sb = ((int64_t)s * n_groups + group) * n_rb + blk;
+        const float2 ml = ((const float2 *)a.part_ml)[sb * 32 + r32];
+        const float wgt = (ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml.x - M);
+        l = fmaf(wgt, ml.y, l);
+        const float4 v = ((const float4 *)a.part_o)[(sb * 16 + frag) * 64 + lane];
+        acc.x = fmaf(wgt, v.x, acc.x); acc.y = fmaf(wgt, v.y, acc.y);
+        acc.z = fmaf(wgt, v.z, acc.z); acc.w = fmaf(wgt, v.w, acc.w);
+    }
+    const float inv = 1.f / l;
+    const int s_tok = row_m / g.G;
+    const int head = mg.kvh * g.G + (row_m - s_tok * g.G);
+    const int db = frag >> 2, q4 = frag & 3;
+    bf16x4 o;
+    o[0] = (__bf16)(acc.x * inv); o[1] = (__bf16)(acc.y * inv);
+    o[2] = (__bf16)(acc.z * inv); o[3] = (__bf16)(acc.w * inv);
+    *(bf16x4 *)((char *)a.out + ((int64_t)(mg.cu + s_tok) * g.Hq + head) * 256 + (32 * db + 8 * q4 + 4 * hh) * 2) = o;
+}
+
+template <int RB>
+static hipError_t launch_attn_rb(const Geom &g, const BatchDev &b, const AttnArgs &a, hipStream_t s)
+{
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)attn_bf16_kernel<RB>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    attn_bf16_kernel<RB><<<a.n_items, 256, kLdsBytes, s>>>(g, b, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, int row_blocks, hipStream_t s)
 {
     if (a.n_items == 0) return hipSuccess;
     if (g.D != 128 || g.esize != 2) return hipErrorInvalidValue;
-    attn_bf16_kernel<<<a.n_items, 256, 0, s>>>(g, b, a);
+    if (row_blocks == 1) return launch_attn_rb<1>(g, b, a, s);
+    if (row_blocks == 2) return launch_attn_rb<2>(g, b, a, s);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_merge_bf16(const Geom &g, const AttnArgs &a, const MergeGroup *groups, int n_groups,
+                             int row_blocks, hipStream_t s)
+{
+    if (n_groups == 0) return hipSuccess;
+    const int n_rb = 4 * row_blocks;                   // 32-row blocks per group
+    merge_bf16_kernel<<<n_groups * n_rb * 4, 256, 0, s>>>(g, a, groups, n_groups, n_rb);
     return hipGetLastError();
 }
 

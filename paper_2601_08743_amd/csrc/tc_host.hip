@@ -102,10 +102,11 @@ struct Slot {
 // The integer plan of one batch, host copy and layout of the device copy.
 struct Plan {
     bool valid = false;
-    int32_t B = 0, max_blocks = 0, total_S = 0, n_stitch_blk = 0, n_items = 0, max_splits = 1;
+    int32_t B = 0, max_blocks = 0, total_S = 0, n_stitch_blk = 0, n_items = 0, max_splits = 1, n_groups = 0, row_blocks = 1;
     std::vector<int32_t> block_table, cu_seqlens, prefix_len, suffix_len;
     BatchDev dev{};
     const AttnItem *items_dev = nullptr;
+    const MergeGroup *groups_dev = nullptr;
 };
 
 inline size_t align8(size_t n) { return (n + 7) & ~size_t(7); }
@@ -132,6 +133,14 @@ struct tc_ctx {
     hipEvent_t stage_ev = nullptr; bool stage_pending = false;
     float *d_part = nullptr; size_t d_part_floats = 0;
     int32_t forced_splits = 0;
+    int32_t forced_row_blocks = 0;
+    // per-kernel timing (tc_profile_*): pairs of events around launches, drained on read
+    bool profiling = false;
+    struct Timed { int kind; hipEvent_t a, b; };
+    std::vector<Timed> timed;
+    std::vector<hipEvent_t> ev_pool;
+    double prof_ms[4] = {0, 0, 0, 0};
+    int64_t prof_n[4] = {0, 0, 0, 0};
     std::string err;
 };
 
@@ -154,6 +163,28 @@ tc_status fail(tc_ctx *ctx, tc_status code, const char *fmt, ...)
         if (e_ != hipSuccess)                                                                   \
             return fail(ctx, TC_ERR_HIP, "%s: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
     } while (0)
+
+hipEvent_t take_event(tc_ctx *ctx)
+{
+    hipEvent_t e = nullptr;
+    if (!ctx->ev_pool.empty()) { e = ctx->ev_pool.back(); ctx->ev_pool.pop_back(); return e; }
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+// Run `launch` on `stream`; with profiling on, bracket it with two timing events.
+template <typename F>
+hipError_t timed_launch(tc_ctx *ctx, int kind, hipStream_t stream, F launch)
+{
+    if (!ctx->profiling) return launch();
+    hipEvent_t a = take_event(ctx), b = take_event(ctx);
+    if (!a || !b) return hipErrorOutOfMemory;
+    hipError_t e = hipEventRecord(a, stream);
+    if (e == hipSuccess) e = launch();
+    if (e == hipSuccess) e = hipEventRecord(b, stream);
+    ctx->timed.push_back(tc_ctx::Timed{kind, a, b});
+    return e;
+}
 
 bool config_ok(const tc_config *c)
 {
@@ -204,13 +235,23 @@ struct SegInfo { int32_t start, len, slot; };
 // modulo 8 so that they land on the same XCD and share its L2 (work-groups go to the 8 XCDs
 // round-robin by id).  Holes are padded with no-op items (q = -1).
 void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
-                    std::vector<int32_t> &splits_of_q)
+                    std::vector<int32_t> &splits_of_q, std::vector<MergeGroup> &groups)
 {
     const tc_config &c = ctx->cfg;
     const int G = c.n_q_heads / c.n_kv_heads;
     const bool bf16 = c.dtype == TC_BF16;
-    const int RT = bf16 ? kAttnRows : kF32Rows;
     const int KT = bf16 ? kAttnKeys : kF32Keys;
+    // bf16: 128 rows per work-group, or 256 (two row blocks per wave: half the LDS traffic per flop)
+    // when that still leaves enough work-groups to fill the chip
+    int rb = 1;
+    if (bf16) {
+        int64_t base2 = 0;
+        for (int i = 0; i < p.B; ++i)
+            if (p.suffix_len[i] > 0) base2 += (int64_t)c.n_kv_heads * ((p.suffix_len[i] * G + 2 * kAttnRows - 1) / (2 * kAttnRows));
+        rb = ctx->forced_row_blocks > 0 ? ctx->forced_row_blocks : (base2 >= 192 ? 2 : 1);
+    }
+    p.row_blocks = rb;
+    const int RT = bf16 ? kAttnRows * rb : kF32Rows;
     int64_t base = 0;
     for (int i = 0; i < p.B; ++i)
         if (p.suffix_len[i] > 0) base += (int64_t)c.n_kv_heads * ((p.suffix_len[i] * G + RT - 1) / RT);
@@ -223,30 +264,47 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
     splits_of_q.assign(p.B, 1);
     p.max_splits = 1;
     std::vector<std::vector<AttnItem>> per_xcd(8);
-    int group = 0;
+    int bucket = 0, n_groups = 0;
     for (int i = 0; i < p.B; ++i) {
         const int S = p.suffix_len[i], P = p.prefix_len[i];
         if (S <= 0) continue;
         const int n_tiles = (P + S + KT - 1) / KT;
+        const int n_blk = (P + S + kBlockTokens - 1) / kBlockTokens;
         int ns = std::min(want, ctx->forced_splits > 0 ? n_tiles : std::max(1, n_tiles / 4));
+        if (bf16) ns = std::max(ns, (n_tiles + kAttnMaxTiles - 1) / kAttnMaxTiles);   // block ids of a range fit LDS
         ns = std::max(1, std::min(ns, n_tiles));
         splits_of_q[i] = ns;
         p.max_splits = std::max(p.max_splits, ns);
         const int n_mt = (S * G + RT - 1) / RT;
-        for (int h = 0; h < c.n_kv_heads; ++h)
+        const int32_t *bt = p.block_table.data() + (size_t)i * p.max_blocks;
+        for (int h = 0; h < c.n_kv_heads; ++h) {
             for (int s = 0; s < ns; ++s) {
                 const int t0 = (int)((int64_t)n_tiles * s / ns), t1 = (int)((int64_t)n_tiles * (s + 1) / ns);
-                for (int mt = 0; mt < n_mt; ++mt)
-                    per_xcd[group & 7].push_back(AttnItem{i, h, mt * RT, t0, t1, s, ns, 0});
-                ++group;
+                for (int mt = 0; mt < n_mt; ++mt) {
+                    AttnItem it{};
+                    it.q = i; it.kvh = h; it.m0 = mt * RT; it.tile_begin = t0; it.tile_end = t1;
+                    it.split = s; it.n_splits = ns; it.group = n_groups + mt;
+                    it.P = P; it.S = S; it.cu = p.cu_seqlens[i];
+                    for (int k = 0; k < 8; ++k)
+                        it.bid[k] = bt[std::min(t0 * (KT / kBlockTokens) + k, n_blk - 1)];
+                    per_xcd[bucket & 7].push_back(it);
+                }
+                ++bucket;
             }
+            for (int mt = 0; mt < n_mt; ++mt) groups.push_back(MergeGroup{h, mt * RT, ns, p.cu_seqlens[i], S, {0, 0, 0}});
+            n_groups += n_mt;
+        }
     }
+    p.n_groups = n_groups;
+    for (auto &v : per_xcd)
+        for (auto &it : v) it.n_groups = n_groups;
     size_t longest = 0;
     for (auto &v : per_xcd) longest = std::max(longest, v.size());
     items.clear();
     for (size_t k = 0; k < longest; ++k)
         for (int x = 0; x < 8; ++x)
-            items.push_back(k < per_xcd[x].size() ? per_xcd[x][k] : AttnItem{-1, 0, 0, 0, 0, 0, 1, 0});
+            if (k < per_xcd[x].size()) items.push_back(per_xcd[x][k]);
+            else { AttnItem pad{}; pad.q = -1; pad.n_splits = 1; items.push_back(pad); }
     while (!items.empty() && items.back().q < 0) items.pop_back();
     p.n_items = (int32_t)items.size();
 }
@@ -258,7 +316,8 @@ tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
 {
     std::vector<AttnItem> items;
     std::vector<int32_t> splits_of_q;
-    plan_attention(ctx, p, items, splits_of_q);
+    std::vector<MergeGroup> groups;
+    plan_attention(ctx, p, items, splits_of_q, groups);
 
     const size_t B = p.B, nseg = segs.size();
     size_t off = 0;
@@ -266,7 +325,8 @@ tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
     const size_t o_bt = take(B * p.max_blocks), o_cu = take(B + 1), o_pl = take(B), o_sl = take(B);
     const size_t o_ss = take(nseg), o_sn = take(nseg), o_st = take(nseg), o_se = take(B);
     const size_t o_sb = take(sblk.size() * 4), o_sp = take(B), o_tq = take(p.total_S);
-    const size_t o_it = take(items.size() * 8);
+    const size_t o_it = take(items.size() * (sizeof(AttnItem) / 4));
+    const size_t o_gr = take(groups.size() * (sizeof(MergeGroup) / 4));
     const size_t total = std::max(off, size_t(8));
     tc_status st = ensure_stage(ctx, total);
     if (st != TC_OK) return st;
@@ -287,6 +347,7 @@ tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
     for (int i = 0; i < p.B; ++i)
         for (int n = p.cu_seqlens[i]; n < p.cu_seqlens[i + 1]; ++n) h[o_tq + n] = i;
     if (!items.empty()) std::memcpy(h + o_it, items.data(), items.size() * sizeof(AttnItem));
+    if (!groups.empty()) std::memcpy(h + o_gr, groups.data(), groups.size() * sizeof(MergeGroup));
 
     TC_HIP(ctx, hipMemcpyAsync(ctx->d_plan, h, total * sizeof(int32_t), hipMemcpyHostToDevice, stream));
     TC_HIP(ctx, hipEventRecord(ctx->stage_ev, stream));
@@ -302,9 +363,14 @@ tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
     p.dev.n_stitch_blk = (int32_t)sblk.size();
     p.n_stitch_blk = (int32_t)sblk.size();
     p.items_dev = (const AttnItem *)(d + o_it);
+    p.groups_dev = (const MergeGroup *)(d + o_gr);
 
     if (p.max_splits > 1) {
-        const size_t need = (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * (ctx->cfg.head_dim + 2);
+        // bf16 kernel: per (partition, group) 128 rows x (128 + 2) floats in fragment order;
+        // fp32 kernel: per (partition, suffix token, head) D + 2 floats
+        const size_t need = ctx->cfg.dtype == TC_BF16
+            ? (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * (128 + 2)
+            : (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * (ctx->cfg.head_dim + 2);
         if (need > ctx->d_part_floats) {
             if (ctx->d_part) TC_HIP(ctx, hipFree(ctx->d_part));
             ctx->d_part = nullptr; ctx->d_part_floats = 0;
@@ -398,6 +464,8 @@ tc_status tc_destroy(tc_ctx *ctx)
     if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
     if (ctx->d_plan) (void)hipFree(ctx->d_plan);
     if (ctx->d_part) (void)hipFree(ctx->d_part);
+    for (auto &t : ctx->timed) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); }
+    for (auto &e : ctx->ev_pool) (void)hipEventDestroy(e);
     delete ctx;
     return TC_OK;
 }
@@ -586,7 +654,7 @@ tc_status tc_stitch_kv(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_
             TC_HIP(ctx, hipStreamWaitEvent(stream, sl.ready, 0));
     }
     ctx->plan = std::move(p);
-    TC_HIP(ctx, launch_stitch(ctx->geom, ctx->plan.dev, 0, L, stream));
+    TC_HIP(ctx, timed_launch(ctx, 0, stream, [&] { return launch_stitch(ctx->geom, ctx->plan.dev, 0, L, stream); }));
     if (!used_slots.empty()) {
         const int32_t ev = ctx->read_next;
         ctx->read_next = (ctx->read_next + 1) % (int32_t)ctx->read_ring.size();
@@ -649,15 +717,24 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
     if (((uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)out) & 15)
         return fail(ctx, TC_ERR_INVALID, "attn: tensors must be 16-byte aligned");
 
-    TC_HIP(ctx, launch_append(ctx->geom, p.dev, layer, k_new, v_new, stream));
+    TC_HIP(ctx, timed_launch(ctx, 1, stream, [&] { return launch_append(ctx->geom, p.dev, layer, k_new, v_new, stream); }));
     AttnArgs a{};
     a.q = q; a.out = out; a.items = p.items_dev; a.n_items = p.n_items; a.layer = layer;
     a.scale_log2 = sm_scale * 1.4426950408889634f;
     a.part_o = ctx->d_part;
-    a.part_ml = ctx->d_part ? ctx->d_part + (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * ctx->cfg.head_dim : nullptr;
-    if (ctx->cfg.dtype == TC_BF16) TC_HIP(ctx, launch_attn_bf16(ctx->geom, p.dev, a, stream));
-    else TC_HIP(ctx, launch_attn_f32(ctx->geom, p.dev, a, stream));
-    if (p.max_splits > 1) TC_HIP(ctx, launch_merge(ctx->geom, p.dev, a, stream));
+    const bool bf16 = ctx->cfg.dtype == TC_BF16;
+    a.part_ml = !ctx->d_part ? nullptr
+              : bf16 ? ctx->d_part + (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * 128
+                     : ctx->d_part + (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * ctx->cfg.head_dim;
+    TC_HIP(ctx, timed_launch(ctx, 2, stream, [&] {
+        return ctx->cfg.dtype == TC_BF16 ? launch_attn_bf16(ctx->geom, p.dev, a, p.row_blocks, stream)
+                                         : launch_attn_f32(ctx->geom, p.dev, a, stream);
+    }));
+    if (p.max_splits > 1)
+        TC_HIP(ctx, timed_launch(ctx, 3, stream, [&] {
+            return bf16 ? launch_merge_bf16(ctx->geom, a, p.groups_dev, p.n_groups, p.row_blocks, stream)
+                        : launch_merge(ctx->geom, p.dev, a, stream);
+        }));
     return TC_OK;
 }
 
@@ -710,12 +787,46 @@ tc_status tc_read_seq_kv(tc_ctx *ctx, int32_t layer, const int32_t *blocks, int3
     return st;
 }
 
+tc_status tc_profile_enable(tc_ctx *ctx, int32_t on)
+{
+    if (!ctx) return TC_ERR_INVALID;
+    ctx->profiling = on != 0;
+    return TC_OK;
+}
+
+tc_status tc_profile_read(tc_ctx *ctx, double *ms_out, int64_t *count_out)
+{
+    if (!ctx || !ms_out || !count_out) return TC_ERR_INVALID;
+    for (auto &t : ctx->timed) {
+        float ms = 0.f;
+        TC_HIP(ctx, hipEventSynchronize(t.b));
+        TC_HIP(ctx, hipEventElapsedTime(&ms, t.a, t.b));
+        ctx->prof_ms[t.kind] += ms;
+        ctx->prof_n[t.kind] += 1;
+        ctx->ev_pool.push_back(t.a); ctx->ev_pool.push_back(t.b);
+    }
+    ctx->timed.clear();
+    for (int k = 0; k < 4; ++k) {
+        ms_out[k] = ctx->prof_ms[k]; count_out[k] = ctx->prof_n[k];
+        ctx->prof_ms[k] = 0; ctx->prof_n[k] = 0;
+    }
+    return TC_OK;
+}
+
 int32_t tc_kv_splits(const tc_ctx *ctx) { return (ctx && ctx->plan.valid) ? ctx->plan.max_splits : 1; }
 
 tc_status tc_set_kv_splits(tc_ctx *ctx, int32_t n_splits)
 {
     if (!ctx || n_splits < 0) return TC_ERR_INVALID;
     ctx->forced_splits = n_splits;
+    ctx->plan.valid = false;
+    return TC_OK;
+}
+
+tc_status tc_set_row_blocks(tc_ctx *ctx, int32_t row_blocks)
+{
+    if (!ctx || row_blocks < 0 || row_blocks > 2) return TC_ERR_INVALID;
+    ctx->forced_row_blocks = row_blocks;
     ctx->plan.valid = false;
     return TC_OK;
 }

@@ -7,8 +7,9 @@
 namespace tc {
 
 constexpr int kBlockTokens = 16;     // tokens per pool block
-constexpr int kAttnRows = 128;       // bf16 kernel: rows (suffix token x group head) per work-group
+constexpr int kAttnRows = 128;       // bf16 kernel: rows (suffix token x group head) per work-group and row block
 constexpr int kAttnKeys = 64;        // bf16 kernel: keys per tile (4 pool blocks)
+constexpr int kAttnMaxTiles = 256;   // bf16 kernel: key tiles per work item (block ids kept in LDS)
 constexpr int kF32Rows = 4;          // fp32 kernel: rows per work-group (one per wave)
 constexpr int kF32Keys = 64;         // fp32 kernel: keys per tile
 
@@ -51,23 +52,34 @@ struct BatchDev {
 };
 
 // One unit of attention work: a tile of rows of one (query, KV head) against a range of key tiles.
+// Everything the work-group needs to start loading is in the item itself (one scalar fetch):
+// the query's lengths and the block ids of its first two key tiles.
 struct AttnItem {
-    int32_t q;
+    int32_t q;           // query index, -1 = padding item
     int32_t kvh;
     int32_t m0;          // first row (row = suffix_token * G + head_in_group)
     int32_t tile_begin;  // first key tile
     int32_t tile_end;    // one past the last key tile
     int32_t split;       // which partition this is (0 when n_splits == 1)
     int32_t n_splits;    // partitions of this query
-    int32_t pad;
+    int32_t group;       // index of the (query, KV head, row tile): partial slots and arrival counter
+    int32_t P, S, cu;    // prefix length, suffix length, first suffix row of the query
+    int32_t n_groups;    // total number of groups in the batch
+    int32_t bid[8];      // block ids of key tiles tile_begin and tile_begin+1 (clamped to the sequence)
+};
+static_assert(sizeof(AttnItem) == 80, "AttnItem layout");
+
+// A (query, KV head, row tile) whose partitions the bf16 merge kernel combines.
+struct MergeGroup {
+    int32_t kvh, m0, n_splits, cu, S, pad[3];
 };
 
 struct AttnArgs {
     const void *q;
     void *out;
     const AttnItem *items;
-    float *part_o;       // [max_splits][total_S][Hq][D] unnormalised partial outputs
-    float *part_ml;      // [max_splits][total_S][Hq][2] (reference max in log2 units, sum)
+    float *part_o;       // split-KV partial outputs, unnormalised (layout private to each kernel)
+    float *part_ml;      // per partial row: (reference max in log2 units, sum of weights)
     float scale_log2;    // sm_scale * log2(e)
     int32_t layer;
     int32_t n_items;
@@ -80,8 +92,10 @@ hipError_t launch_append(const Geom &g, const BatchDev &b, int layer, const void
 hipError_t launch_readback(const Geom &g, int layer, const int32_t *blocks_dev, int n_tokens,
                            void *k_out_dev, void *v_out_dev, hipStream_t s);
 // prefill_attn_bf16.hip / prefill_attn_f32.hip
-hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, hipStream_t s);
+hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, int row_blocks, hipStream_t s);
 hipError_t launch_attn_f32(const Geom &g, const BatchDev &b, const AttnArgs &a, hipStream_t s);
 hipError_t launch_merge(const Geom &g, const BatchDev &b, const AttnArgs &a, hipStream_t s);
+hipError_t launch_merge_bf16(const Geom &g, const AttnArgs &a, const MergeGroup *groups, int n_groups,
+                             int row_blocks, hipStream_t s);
 
 }  // namespace tc
