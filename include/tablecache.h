@@ -27,14 +27,15 @@
  *
  * The device KV pool
  *   The caller allocates one device buffer of tc_pool_bytes(cfg) bytes and hands it
- *   to tc_create.  It is carved into n_pool_blocks blocks of block_size (16) tokens,
- *   layer-major: the bytes of (layer l, block b) start at (l * n_pool_blocks + b) *
- *   tc_block_bytes(cfg).  Blocks [0, table_capacity * slot_blocks) are TABLE slots,
- *   slot_blocks = ceil(max_table_tokens / block_size): slot s holds one resident
- *   table, per layer its K rows [n_tokens][Hkv][D] as registered, then its V rows at
- *   half the slot.  The remaining blocks are SEQUENCE blocks handed out by
- *   tc_stitch_kv, lowest-numbered free block first; their in-block layout is private
- *   to the library (read them back with tc_read_seq_kv).
+ *   to tc_create.  It counts n_pool_blocks blocks of block_size (16) tokens in all layers.
+ *   The first table_capacity * slot_blocks of them (slot_blocks = ceil(max_table_tokens /
+ *   block_size)) form the TABLE region: slot s is one contiguous piece of slot_blocks *
+ *   n_layers * tc_block_bytes(cfg) bytes holding one resident table as registered - its K
+ *   rows [L][n_tokens][Hkv][D], then, at half the slot, its V rows - so a table (or a run
+ *   of its layers) arrives as two large host->device transfers.  The remaining blocks are
+ *   SEQUENCE blocks handed out by tc_stitch_kv, lowest-numbered free block first, stored
+ *   layer-major behind the table region; their in-block layout is private to the library
+ *   (read them back with tc_read_seq_kv).
  */
 #ifndef TABLECACHE_H
 #define TABLECACHE_H

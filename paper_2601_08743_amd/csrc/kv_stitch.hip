@@ -29,12 +29,13 @@ __global__ __launch_bounds__(256) void stitch_kernel(Geom g, BatchDev b, int l0)
         if (p < b.prefix_len[blk.q]) {
             int s = blk.seg;
             while (p >= b.seg_start[s] + b.seg_len[s]) ++s;
-            off = (int64_t)b.seg_slot[s] * g.slot_bytes + (int64_t)(p - b.seg_start[s]) * g.row_bytes;
+            off = (int64_t)b.seg_slot[s] * g.slot_bytes +
+                  ((int64_t)layer * b.seg_len[s] + (p - b.seg_start[s])) * g.row_bytes;
         }
         src_off[tid] = off;
     }
     __syncthreads();
-    const char *layer_base = g.pool + (int64_t)layer * g.layer_stride;
+    const char *layer_base = g.tab_base;             // source rows: table slots
     char *dst = g.pool + (int64_t)layer * g.layer_stride + (int64_t)blk.phys * g.block_bytes;
     const int cpr = g.row_bytes >> 4;              // 16-byte chunks per token row
     const int cph = g.head_bytes >> 4;             // ... per head

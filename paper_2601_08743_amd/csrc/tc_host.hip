@@ -241,25 +241,35 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
     const int G = c.n_q_heads / c.n_kv_heads;
     const bool bf16 = c.dtype == TC_BF16;
     const int KT = bf16 ? kAttnKeys : kF32Keys;
-    // bf16: 128 rows per work-group, or 256 (two row blocks per wave: half the LDS traffic per flop)
-    // when that still leaves enough work-groups to fill the chip
-    int rb = 1;
-    if (bf16) {
-        int64_t base2 = 0;
-        for (int i = 0; i < p.B; ++i)
-            if (p.suffix_len[i] > 0) base2 += (int64_t)c.n_kv_heads * ((p.suffix_len[i] * G + 2 * kAttnRows - 1) / (2 * kAttnRows));
-        rb = ctx->forced_row_blocks > 0 ? ctx->forced_row_blocks : (base2 >= 192 ? 2 : 1);
-    }
+    // bf16: 128 rows per work-group; 256 (two row blocks per wave, half the LDS traffic per flop but one
+    // wave per SIMD) is kept as an option: it is slower until its matrix and vector work overlap
+    const int rb = (bf16 && ctx->forced_row_blocks > 0) ? ctx->forced_row_blocks : 1;
     p.row_blocks = rb;
     const int RT = bf16 ? kAttnRows * rb : kF32Rows;
-    int64_t base = 0;
+    int64_t base = 0, tiles_sum = 0, n_q = 0;
     for (int i = 0; i < p.B; ++i)
-        if (p.suffix_len[i] > 0) base += (int64_t)c.n_kv_heads * ((p.suffix_len[i] * G + RT - 1) / RT);
+        if (p.suffix_len[i] > 0) {
+            base += (int64_t)c.n_kv_heads * ((p.suffix_len[i] * G + RT - 1) / RT);
+            tiles_sum += (p.prefix_len[i] + p.suffix_len[i] + KT - 1) / KT;
+            ++n_q;
+        }
+    // Number of key partitions: a small cost model, in units of one key tile of one work-group.
+    // Work-groups per CU x key tiles per work-group (two co-resident work-groups overlap each other's
+    // stalls: x0.7), plus a fixed start-up/epilogue cost, plus the merge (grows with the partial
+    // traffic).  The constants were fitted to split-count sweeps on c2 and c5-sized batches.
     int want = 1;
     if (ctx->forced_splits > 0) want = ctx->forced_splits;
     else if (base > 0) {
-        const int64_t target = bf16 ? 256 : 512;       // work-groups that fill the chip once
-        want = (int)std::max<int64_t>(1, target / base);
+        const double cus = 256.0;
+        const double tiles = (double)tiles_sum / (double)n_q;
+        double best = 1e30;
+        for (int ns = 1; ns <= 32; ++ns) {
+            if (ns > 1 && tiles / ns < 2.0) break;
+            const double per_cu = std::ceil((double)base * ns / cus);
+            const double cost = per_cu * (tiles / ns) * (per_cu >= 2.0 ? 0.7 : 1.0) + 3.0 +
+                                (ns > 1 ? 1.0 + 0.4 * ns : 0.0);
+            if (cost < best - 1e-9) { best = cost; want = ns; }
+        }
     }
     splits_of_q.assign(p.B, 1);
     p.max_splits = 1;
@@ -270,7 +280,7 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
         if (S <= 0) continue;
         const int n_tiles = (P + S + KT - 1) / KT;
         const int n_blk = (P + S + kBlockTokens - 1) / kBlockTokens;
-        int ns = std::min(want, ctx->forced_splits > 0 ? n_tiles : std::max(1, n_tiles / 4));
+        int ns = std::min(want, ctx->forced_splits > 0 ? n_tiles : std::max(1, n_tiles / 2));
         if (bf16) ns = std::max(ns, (n_tiles + kAttnMaxTiles - 1) / kAttnMaxTiles);   // block ids of a range fit LDS
         ns = std::max(1, std::min(ns, n_tiles));
         splits_of_q[i] = ns;
@@ -424,10 +434,12 @@ tc_status tc_create(const tc_config *cfg, void *kv_pool_dev, size_t pool_bytes, 
     ctx->slot_blocks = (cfg->max_table_tokens + kBlockTokens - 1) / kBlockTokens;
     ctx->first_seq = tc_first_seq_block(cfg);
     Geom &g = ctx->geom;
-    g.pool = (char *)kv_pool_dev;
     g.block_bytes = (int64_t)tc_block_bytes(cfg);
-    g.layer_stride = g.block_bytes * cfg->n_pool_blocks;
-    g.slot_bytes = g.block_bytes * ctx->slot_blocks;
+    g.tab_base = (char *)kv_pool_dev;
+    g.slot_bytes = g.block_bytes * ctx->slot_blocks * cfg->n_layers;
+    const int64_t n_seq = cfg->n_pool_blocks - ctx->first_seq;
+    g.layer_stride = g.block_bytes * n_seq;
+    g.pool = (char *)kv_pool_dev + g.slot_bytes * cfg->table_capacity - ctx->first_seq * g.block_bytes;
     g.first_seq = (int32_t)ctx->first_seq;
     g.n_blocks = (int32_t)cfg->n_pool_blocks;
     g.Hq = cfg->n_q_heads; g.Hkv = cfg->n_kv_heads; g.D = cfg->head_dim; g.G = g.Hq / g.Hkv;
@@ -529,17 +541,21 @@ tc_status tc_load_async(tc_ctx *ctx, const int32_t *table_ids, int32_t n, int32_
                 TC_HIP(ctx, hipStreamWaitEvent(stream, s.ready, 0));
         }
         ctx->trace.push_back(id); ctx->trace.push_back(hit ? 1 : 0); ctx->trace.push_back(evicted);
-        // copy the layers of the range that are not on the device yet: per layer, the table's K rows
-        // and V rows are each one contiguous transfer
+        // copy the layers of the range that are not on the device yet: a run of consecutive layers of
+        // one table is contiguous on both sides, so it goes as two large transfers (K, V); small
+        // transfers reach only ~60 % of the link rate
         const size_t width = (size_t)t.n_tokens * g.row_bytes;
-        for (int l = l0; l < l1; ++l) {
-            if (t.layer_loaded[l]) continue;
-            char *dst = g.pool + (int64_t)l * g.layer_stride + (int64_t)t.slot * g.slot_bytes;
-            TC_HIP(ctx, hipMemcpyAsync(dst, t.host_k + (size_t)l * width, width, hipMemcpyHostToDevice, stream));
-            TC_HIP(ctx, hipMemcpyAsync(dst + (g.slot_bytes >> 1), t.host_v + (size_t)l * width, width,
+        for (int l = l0; l < l1;) {
+            if (t.layer_loaded[l]) { ++l; continue; }
+            int e = l;
+            while (e < l1 && !t.layer_loaded[e]) ++e;
+            char *dst = g.tab_base + (int64_t)t.slot * g.slot_bytes + (size_t)l * width;
+            TC_HIP(ctx, hipMemcpyAsync(dst, t.host_k + (size_t)l * width, width * (e - l), hipMemcpyHostToDevice, stream));
+            TC_HIP(ctx, hipMemcpyAsync(dst + (g.slot_bytes >> 1), t.host_v + (size_t)l * width, width * (e - l),
                                        hipMemcpyHostToDevice, stream));
-            t.layer_loaded[l] = 1;
+            for (int x = l; x < e; ++x) t.layer_loaded[x] = 1;
             touched.insert(t.slot);
+            l = e;
         }
     }
     for (int32_t s : touched) {

@@ -15,10 +15,13 @@ constexpr int kF32Keys = 64;         // fp32 kernel: keys per tile
 
 // Pool geometry, passed by value to kernels.
 struct Geom {
-    char *pool;              // device base of the pool
-    int64_t layer_stride;    // bytes between the same block in consecutive layers
+    char *pool;              // sequence region, biased so that block id b of layer l starts at
+                             // pool + l * layer_stride + b * block_bytes (b counts from first_seq)
+    int64_t layer_stride;    // bytes between the same sequence block in consecutive layers
     int64_t block_bytes;     // bytes of one block in one layer (K half then V half)
-    int64_t slot_bytes;      // bytes of one table slot in one layer (slot_blocks * block_bytes)
+    char *tab_base;          // table region: slot s starts at tab_base + s * slot_bytes
+    int64_t slot_bytes;      // bytes of one table slot, all layers (K part, then V part at half);
+                             // layer l of a table of n tokens starts n * l * row_bytes into its part
     int32_t first_seq;       // first sequence block
     int32_t n_blocks;        // total blocks
     int32_t Hq, Hkv, D, G;
