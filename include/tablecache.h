@@ -200,9 +200,9 @@ tc_status tc_set_kv_splits(tc_ctx *ctx, int32_t n_splits);
 tc_status tc_set_row_blocks(tc_ctx *ctx, int32_t row_blocks);
 
 /*
- * Measurement support.  With profiling on, every kernel the library launches is bracketed by
- * two HIP timing events on the stream it is launched on.  tc_profile_read waits for them and
- * returns, per kernel kind (0 stitch, 1 append, 2 attention, 3 split-KV merge), the summed
+ * Measurement support.  With profiling on, every kernel the library launches carries two HIP
+ * events that receive the begin and end timestamps of its own dispatch on the stream it is launched
+ * on (no extra packets between kernels).  tc_profile_read waits for them and returns, per kernel kind (0 stitch, 1 append, 2 attention, 3 split-KV merge), the summed
  * elapsed milliseconds and the number of launches since the previous read.
  *   ms_out HOST double[4], count_out HOST int64_t[4].
  */

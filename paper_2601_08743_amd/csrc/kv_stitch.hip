@@ -6,11 +6,10 @@
 //   V half: fp32: [Hkv][16 tokens][D]
 //           bf16: [Hkv][D][16 tokens], token t stored at position vperm(t) so that the two
 //                 8-token groups a PV matrix-core operand needs are 16 contiguous bytes.
+#include "kv_append.h"
 #include "tc_internal.h"
 
 namespace tc {
-
-__device__ __forceinline__ int vperm(int t) { return (t & 3) | ((t & 4) << 1) | ((t & 8) >> 1); }
 
 // ------------------------------------------------------------------------------------ stitch
 // Paper Sec. 4.1.2: the matched tables' KV caches are concatenated in match order.
@@ -89,89 +88,35 @@ __global__ __launch_bounds__(256) void stitch_kernel(Geom g, BatchDev b, int l0)
     }
 }
 
-hipError_t launch_stitch(const Geom &g, const BatchDev &b, int l0, int l1, hipStream_t s)
+hipError_t launch_stitch(const Geom &g, const BatchDev &b, int l0, int l1, const Launch &L)
 {
     if (b.n_stitch_blk == 0 || l1 <= l0) return hipSuccess;
     dim3 grid(b.n_stitch_blk, l1 - l0);
     if (g.esize == 2)
-        stitch_kernel<true><<<grid, 256, kBlockTokens * g.row_bytes, s>>>(g, b, l0);
+        TC_LAUNCH(stitch_kernel<true>, grid, kBlockTokens * g.row_bytes, L, g, b, l0);
     else
-        stitch_kernel<false><<<grid, 256, 0, s>>>(g, b, l0);
+        TC_LAUNCH(stitch_kernel<false>, grid, 0, L, g, b, l0);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------ append
-// The suffix tokens' own K/V go to logical positions [P_i, P_i + S_i) of the sequence, so the
-// attention kernel reads one uniform paged sequence.  Work-group n < total_S handles suffix
-// token n; work-group total_S + i zero-fills the unused tail of query i's last block.
+// Stand-alone launch of the append units (fp32 path), one work-group per unit.
 template <bool kTransposeV>
 __global__ __launch_bounds__(256) void append_kernel(Geom g, BatchDev b, int layer,
                                                      const char *k_new, const char *v_new)
 {
-    const int tid = threadIdx.x;
-    const int n = blockIdx.x;
-    char *layer_base = g.pool + (int64_t)layer * g.layer_stride;
-    const int cpr = g.row_bytes >> 4, cph = g.head_bytes >> 4;
-    if (n < b.total_S) {
-        const int i = b.tok_q[n];
-        const int p = b.prefix_len[i] + (n - b.cu_seqlens[i]);
-        const int phys = b.block_table[(int64_t)i * b.max_blocks + (p >> 4)];
-        const int t = p & 15;
-        char *kd = layer_base + (int64_t)phys * g.block_bytes;
-        char *vd = kd + (g.block_bytes >> 1);
-        for (int w = tid; w < cpr; w += 256) {
-            const int h = w / cph, dc = w - h * cph;
-            const uint4 kv = *(const uint4 *)(k_new + (int64_t)n * g.row_bytes + (w << 4));
-            *(uint4 *)(kd + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = kv;
-            const uint4 vv = *(const uint4 *)(v_new + (int64_t)n * g.row_bytes + (w << 4));
-            if (!kTransposeV) {
-                *(uint4 *)(vd + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = vv;
-            } else {
-                const unsigned u[4] = {vv.x, vv.y, vv.z, vv.w};
-                unsigned short *v16 = (unsigned short *)vd;
-                const int d0 = dc << 3;            // 8 bf16 per chunk
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const unsigned short e = (unsigned short)(u[k >> 1] >> ((k & 1) * 16));
-                    v16[((int64_t)(h * g.D + d0 + k) << 4) + vperm(t)] = e;
-                }
-            }
-        }
-    } else {
-        const int i = n - b.total_S;
-        const int end = b.prefix_len[i] + b.suffix_len[i];
-        const int t0 = end & 15;
-        if (t0 == 0) return;
-        const int phys = b.block_table[(int64_t)i * b.max_blocks + (end >> 4)];
-        char *kd = layer_base + (int64_t)phys * g.block_bytes;
-        char *vd = kd + (g.block_bytes >> 1);
-        const uint4 zero = make_uint4(0, 0, 0, 0);
-        const int n_tail = kBlockTokens - t0;
-        for (int c = tid; c < n_tail * cpr; c += 256) {
-            const int t = t0 + c / cpr, w = c % cpr;
-            const int h = w / cph, dc = w - h * cph;
-            *(uint4 *)(kd + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = zero;
-            if (!kTransposeV) {
-                *(uint4 *)(vd + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = zero;
-            } else {
-                unsigned short *v16 = (unsigned short *)vd;
-                const int d0 = dc << 3;
-#pragma unroll
-                for (int k = 0; k < 8; ++k) v16[((int64_t)(h * g.D + d0 + k) << 4) + vperm(t)] = 0;
-            }
-        }
-    }
+    append_unit<kTransposeV>(g, b, layer, k_new, v_new, blockIdx.x, threadIdx.x);
 }
 
 hipError_t launch_append(const Geom &g, const BatchDev &b, int layer, const void *k_new,
-                         const void *v_new, hipStream_t s)
+                         const void *v_new, const Launch &L)
 {
     const int n = b.total_S + b.B;
     if (n == 0) return hipSuccess;
     if (g.esize == 2)
-        append_kernel<true><<<n, 256, 0, s>>>(g, b, layer, (const char *)k_new, (const char *)v_new);
+        TC_LAUNCH(append_kernel<true>, n, 0, L, g, b, layer, (const char *)k_new, (const char *)v_new);
     else
-        append_kernel<false><<<n, 256, 0, s>>>(g, b, layer, (const char *)k_new, (const char *)v_new);
+        TC_LAUNCH(append_kernel<false>, n, 0, L, g, b, layer, (const char *)k_new, (const char *)v_new);
     return hipGetLastError();
 }
 

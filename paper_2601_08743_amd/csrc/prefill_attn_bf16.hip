@@ -13,6 +13,12 @@
 // The exponentials, packed to bf16, are directly the B operand of O^T[d][row] += V^T . P^T; the
 // pool stores V transposed inside a block with the token order the operand wants (kv_stitch.hip).
 //
+// Key tiles of a query: first the tiles of its stitched schema prefix, read from the pool through
+// the block table (the last one ragged: keys >= P masked); then the tiles of its own suffix, read
+// straight from k_new / v_new (token-major; V is transposed on its way into LDS) with the causal
+// mask.  Because attention never reads the suffix from the pool, the append of the suffix to the
+// pool is independent work: it runs in extra work-groups of the same launch.
+//
 // Memory pipeline: the work item carries the block ids of its first two tiles, the rest are
 // fetched into LDS once; each iteration handles two key tiles, whose K/V travel global ->
 // registers (issued a whole iteration ahead) -> two LDS buffers.  At batch 1 the kernel is
@@ -24,6 +30,7 @@
 // a second kernel combines the partitions.  (Combining inside this kernel - last work-group to
 // arrive folds the others in - was measured 3x slower: device-scope release/acquire on this chip
 // writes back and invalidates the XCD's whole L2, which every work-group would do.)
+#include "kv_append.h"
 #include "tc_internal.h"
 
 namespace tc {
@@ -137,11 +144,17 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
     extern __shared__ __attribute__((aligned(16))) char lds[];
     int32_t *s_bid = (int32_t *)(lds + 2 * kStage);
 
+    if ((int)blockIdx.x >= a.n_items) {                // extra work-groups: append the suffix to the pool
+        append_unit<true>(g, b, a.layer, (const char *)a.k_new, (const char *)a.v_new,
+                          blockIdx.x - a.n_items, threadIdx.x);
+        return;
+    }
     const AttnItem it = a.items[blockIdx.x];
     if (it.q < 0) return;                              // padding item (uniform for the work-group)
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, hh = lane >> 5;
     const int G = g.G, P = it.P, S = it.S;
-    const int n_blk = (P + S + kBlockTokens - 1) >> 4;
+    const int npt = (P + kAttnKeys - 1) >> 6;          // prefix tiles; suffix tiles follow
+    const int last_pblk = max(((P + kBlockTokens - 1) >> 4) - 1, 0);
     const int m_rows = S * G;
     const int wave_row0 = it.m0 + w * 32 * RB;
     bool valid[RB];
@@ -153,13 +166,24 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
         const int rm = valid[rb] ? row_m : m_rows - 1;
         s_tok[rb] = rm / G;
         head[rb] = it.kvh * G + (rm - s_tok[rb] * G);
-        limit[rb] = P + s_tok[rb];                     // last visible key of this row
+        limit[rb] = s_tok[rb];                         // last visible suffix key of this row
     }
-    const int wave_limit_min = P + min(wave_row0, m_rows - 1) / G;
+    const int wave_stok_min = min(wave_row0, m_rows - 1) / G;
     const int n_tiles = it.tile_end - it.tile_begin, last = n_tiles - 1;
-    const char *src_base = g.pool + (int64_t)a.layer * g.layer_stride + (int64_t)it.kvh * kHeadBlk + tid * 16;
-    const int64_t v_half = g.block_bytes >> 1;
+    // Addresses are (uniform 64-bit base) + (32-bit per-thread offset), so that the loads take their
+    // base from scalar registers and no 64-bit address arithmetic or registers are spent per load.
+    const char *pool_l = g.pool + (int64_t)a.layer * g.layer_stride + (int64_t)it.kvh * kHeadBlk;
+    const uint32_t v_half = (uint32_t)(g.block_bytes >> 1);
     const int64_t bb = g.block_bytes;
+    const uint32_t t_off = tid * 16;
+    // suffix rows: this thread's 16-byte chunk of the row of token (16*i + tid/16) of a suffix tile
+    const uint32_t new_row = (uint32_t)g.Hkv * 256;
+    const char *kn_s = (const char *)a.k_new + (int64_t)it.cu * new_row + it.kvh * 256;
+    const char *vn_s = (const char *)a.v_new + (int64_t)it.cu * new_row + it.kvh * 256;
+    const uint32_t c_off = (tid & 15) * 16;
+    const int t16 = tid >> 4;
+    const int tv = tid & 15;                           // V of suffix tiles: token within the block,
+    const uint32_t cv_off = (tid >> 4) * 16;           // and 16-byte chunk of its row
 
     // Q^T fragments (B operand): lane (row r32, half hh) holds q[row][16*ks + 8*hh .. +8].
     // Issued before any K/V load: vector loads return in order, so once the first K/V tile has
@@ -175,26 +199,41 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
     // named prefetch registers (arrays of uint4 end up in scratch): set A and set B
     uint4 ka0, ka1, ka2, ka3, va0, va1, va2, va3;
     uint4 kb0, kb1, kb2, kb3, vb0, vb1, vb2, vb3;
-#define TC_LD(kx, vx, bid_)                                              \
-    {                                                                    \
-        const char *src = src_base + (int64_t)(bid_) * bb;               \
-        kx = *(const uint4 *)src;                                        \
-        vx = *(const uint4 *)(src + v_half);                             \
+#define TC_LD(kx, vx, bid_)                                                                    \
+    {                                                                                          \
+        const char *src = pool_l + (int64_t)__builtin_amdgcn_readfirstlane(bid_) * bb;        \
+        kx = *(const uint4 *)(src + t_off);                                                    \
+        vx = *(const uint4 *)(src + (v_half + t_off));                                         \
     }
-    // first two tiles: block ids come with the item
-    TC_LD(ka0, va0, it.bid[0]) TC_LD(ka1, va1, it.bid[1]) TC_LD(ka2, va2, it.bid[2]) TC_LD(ka3, va3, it.bid[3])
-    // Every prefetch below is issued unconditionally (past the end of the range the tile index is
-    // clamped and the data never used): with loads under a condition the compiler cannot count
-    // how many are outstanding and falls back to waiting for all of them, which empties the pipeline.
-    TC_LD(kb0, vb0, it.bid[4]) TC_LD(kb1, vb1, it.bid[5]) TC_LD(kb2, vb2, it.bid[6]) TC_LD(kb3, vb3, it.bid[7])
+    // suffix tile: K chunk of row (tok_ + tid/16), like a pool block; V chunk of row (tok_ + tid%16),
+    // eight d-values starting at 8 * (tid/16) - the assignment the transposing LDS store wants
+#define TC_LD_NEW(kx, vx, tok_)                                                                \
+    {                                                                                          \
+        kx = *(const uint4 *)(kn_s + ((uint32_t)min((tok_) + t16, S - 1) * new_row + c_off));  \
+        vx = *(const uint4 *)(vn_s + ((uint32_t)min((tok_) + tv, S - 1) * new_row + cv_off));  \
+    }
+    // Every prefetch is issued unconditionally, eight loads per tile whatever its kind (past the
+    // end of the range the tile index is clamped and the data never used): with loads under a
+    // condition the compiler cannot count how many are outstanding and falls back to waiting for
+    // all of them, which empties the pipeline.
+    // First two tiles: block ids come with the item.
+    if (it.tile_begin < npt) {
+        TC_LD(ka0, va0, it.bid[0]) TC_LD(ka1, va1, it.bid[1]) TC_LD(ka2, va2, it.bid[2]) TC_LD(ka3, va3, it.bid[3])
+    } else {
+        const int t0_ = (it.tile_begin - npt) * kAttnKeys;
+        TC_LD_NEW(ka0, va0, t0_) TC_LD_NEW(ka1, va1, t0_ + 16) TC_LD_NEW(ka2, va2, t0_ + 32) TC_LD_NEW(ka3, va3, t0_ + 48)
+    }
+    if (it.tile_begin + 1 < npt) {
+        TC_LD(kb0, vb0, it.bid[4]) TC_LD(kb1, vb1, it.bid[5]) TC_LD(kb2, vb2, it.bid[6]) TC_LD(kb3, vb3, it.bid[7])
+    } else {
+        const int t0_ = max(it.tile_begin + 1 - npt, 0) * kAttnKeys;
+        TC_LD_NEW(kb0, vb0, t0_) TC_LD_NEW(kb1, vb1, t0_ + 16) TC_LD_NEW(kb2, vb2, t0_ + 32) TC_LD_NEW(kb3, vb3, t0_ + 48)
+    }
     // block ids of the whole key range -> LDS
     {
         const int32_t *bt = b.block_table + (int64_t)it.q * b.max_blocks;
-        for (int idx = tid; idx < n_tiles * 4; idx += 256) {
-            int jb = it.tile_begin * 4 + idx;
-            jb = jb < n_blk ? jb : n_blk - 1;          // past the end: a valid block, masked in the math
-            s_bid[idx] = bt[jb];
-        }
+        for (int idx = tid; idx < n_tiles * 4; idx += 256)     // past the prefix: a valid block, never used
+            s_bid[idx] = bt[min(it.tile_begin * 4 + idx, last_pblk)];
     }
     RowState<RB> st;
 #pragma unroll
@@ -212,49 +251,89 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
     char *v_st = lds + kKTile + tid * 16;
     const char *k_ld = lds + r32 * kKRow + hh * 16;
     const char *v_ld = lds + kKTile + r32 * 32 + hh * 16;
-#define TC_ST(stage_, k0_, k1_, k2_, k3_, v0_, v1_, v2_, v3_)                                   \
+    // V of a suffix tile arrives token-major and must land as [d][token] (the pool's transposed
+    // block layout, which the PV operand reads).  Lanes l and l^1 hold the same eight d-values of
+    // two adjacent tokens: they swap registers (DPP), the even lane packs the even d of both tokens
+    // into dwords, the odd lane the odd d, so each lane issues 4 dword stores per chunk.
+    const int odd_tok = tv & 1;
+    const uint32_t vt_off = (uint32_t)(tid >> 4) * 256 + odd_tok * 32 + (vperm(tv) >> 1) * 4;
+#define TC_ST_VT(vd_, v_)                                                                         \
+    {                                                                                             \
+        const unsigned u_[4] = {(v_).x, (v_).y, (v_).z, (v_).w};                                  \
+        _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                        \
+            const unsigned p_ = (unsigned)__builtin_amdgcn_update_dpp(0, (int)u_[j_], 0xB1, 0xF, 0xF, false); \
+            const unsigned w_ = odd_tok ? ((p_ >> 16) | (u_[j_] & 0xffff0000u))                   \
+                                        : ((u_[j_] & 0xffffu) | (p_ << 16));                      \
+            *(unsigned *)((vd_) + vt_off + j_ * 64) = w_;                                         \
+        }                                                                                         \
+    }
+#define TC_ST(stage_, is_new_, k0_, k1_, k2_, k3_, v0_, v1_, v2_, v3_)                           \
     {                                                                                             \
         char *kd = k_st + (stage_) * kStage, *vd = v_st + (stage_) * kStage;                      \
-        *(uint4 *)(kd) = k0_;              *(uint4 *)(vd) = v0_;                                  \
-        *(uint4 *)(kd + 16 * kKRow) = k1_; *(uint4 *)(vd + kHeadBlk) = v1_;                       \
-        *(uint4 *)(kd + 32 * kKRow) = k2_; *(uint4 *)(vd + 2 * kHeadBlk) = v2_;                   \
-        *(uint4 *)(kd + 48 * kKRow) = k3_; *(uint4 *)(vd + 3 * kHeadBlk) = v3_;                   \
+        *(uint4 *)(kd) = k0_;                                                                     \
+        *(uint4 *)(kd + 16 * kKRow) = k1_;                                                        \
+        *(uint4 *)(kd + 32 * kKRow) = k2_;                                                        \
+        *(uint4 *)(kd + 48 * kKRow) = k3_;                                                        \
+        if (!(is_new_)) {                                                                         \
+            *(uint4 *)(vd) = v0_;                                                                 \
+            *(uint4 *)(vd + kHeadBlk) = v1_;                                                      \
+            *(uint4 *)(vd + 2 * kHeadBlk) = v2_;                                                  \
+            *(uint4 *)(vd + 3 * kHeadBlk) = v3_;                                                  \
+        } else {                                                                                  \
+            char *vt = lds + (stage_) * kStage + kKTile;                                          \
+            TC_ST_VT(vt, v0_) TC_ST_VT(vt + kHeadBlk, v1_)                                        \
+            TC_ST_VT(vt + 2 * kHeadBlk, v2_) TC_ST_VT(vt + 3 * kHeadBlk, v3_)                     \
+        }                                                                                         \
     }
-#define TC_LD_TILE_A(r_)                                                                          \
+#define TC_LD_TILE(r_, k0_, k1_, k2_, k3_, v0_, v1_, v2_, v3_)                                    \
     {                                                                                             \
-        const int32_t *bp = s_bid + (r_) * 4;                                                     \
-        TC_LD(ka0, va0, bp[0]) TC_LD(ka1, va1, bp[1]) TC_LD(ka2, va2, bp[2]) TC_LD(ka3, va3, bp[3]) \
+        const int rr_ = (r_);                                                                     \
+        if (it.tile_begin + rr_ < npt) {                                                          \
+            const int32_t *bp = s_bid + rr_ * 4;                                                  \
+            TC_LD(k0_, v0_, bp[0]) TC_LD(k1_, v1_, bp[1]) TC_LD(k2_, v2_, bp[2]) TC_LD(k3_, v3_, bp[3]) \
+        } else {                                                                                  \
+            const int t0_ = (it.tile_begin + rr_ - npt) * kAttnKeys;                              \
+            TC_LD_NEW(k0_, v0_, t0_) TC_LD_NEW(k1_, v1_, t0_ + 16)                                \
+            TC_LD_NEW(k2_, v2_, t0_ + 32) TC_LD_NEW(k3_, v3_, t0_ + 48)                           \
+        }                                                                                         \
     }
-#define TC_LD_TILE_B(r_)                                                                          \
+#define TC_LD_TILE_A(r_) TC_LD_TILE(r_, ka0, ka1, ka2, ka3, va0, va1, va2, va3)
+#define TC_LD_TILE_B(r_) TC_LD_TILE(r_, kb0, kb1, kb2, kb3, vb0, vb1, vb2, vb3)
+    // prefix tile: keys count from 0 and the last valid one is P-1; suffix tile: keys count from the
+    // first suffix token and row r sees those up to its own token
+#define TC_MATH(r_, stage_)                                                                       \
     {                                                                                             \
-        const int32_t *bp = s_bid + (r_) * 4;                                                     \
-        TC_LD(kb0, vb0, bp[0]) TC_LD(kb1, vb1, bp[1]) TC_LD(kb2, vb2, bp[2]) TC_LD(kb3, vb3, bp[3]) \
+        const int tt_ = it.tile_begin + (r_);                                                     \
+        const bool pre_ = tt_ < npt;                                                              \
+        const int key0 = (pre_ ? tt_ : tt_ - npt) * kAttnKeys;                                    \
+        int lim_[RB];                                                                             \
+        _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) lim_[rb] = pre_ ? P - 1 : limit[rb];    \
+        tile_math<RB>(st, qf, k_ld + (stage_) * kStage, v_ld + (stage_) * kStage, key0, lim_,     \
+                      key0 + kAttnKeys - 1 > (pre_ ? P - 1 : wave_stok_min), hh, c);              \
     }
 
     // Two key tiles (128 keys) per iteration: their K/V are loaded into the two register sets
     // one whole iteration before they are stored to LDS, so the only wait the loads ever need is
     // "all outstanding", at a point where a full iteration of math has covered their latency.
     for (int r = 0; r < n_tiles; r += 2) {
+        const bool new_a = it.tile_begin + min(r, last) >= npt, new_b = it.tile_begin + min(r + 1, last) >= npt;
         __syncthreads();                               // both LDS stages free (s_bid visible on the first pass)
-        TC_ST(0, ka0, ka1, ka2, ka3, va0, va1, va2, va3)
-        TC_ST(1, kb0, kb1, kb2, kb3, vb0, vb1, vb2, vb3)
+        TC_ST(0, new_a, ka0, ka1, ka2, ka3, va0, va1, va2, va3)
+        TC_ST(1, new_b, kb0, kb1, kb2, kb3, vb0, vb1, vb2, vb3)
         __syncthreads();
         TC_LD_TILE_A(min(r + 2, last))
         TC_LD_TILE_B(min(r + 3, last))
-        {
-            const int key0 = (it.tile_begin + r) * kAttnKeys;
-            tile_math<RB>(st, qf, k_ld, v_ld, key0, limit, key0 + kAttnKeys - 1 > wave_limit_min, hh, c);
-        }
-        if (r + 1 < n_tiles) {
-            const int key0 = (it.tile_begin + r + 1) * kAttnKeys;
-            tile_math<RB>(st, qf, k_ld + kStage, v_ld + kStage, key0, limit,
-                          key0 + kAttnKeys - 1 > wave_limit_min, hh, c);
-        }
+        TC_MATH(r, 0)
+        if (r + 1 < n_tiles) TC_MATH(r + 1, 1)
     }
 #undef TC_LD
+#undef TC_LD_NEW
 #undef TC_ST
+#undef TC_ST_VT
+#undef TC_LD_TILE
 #undef TC_LD_TILE_A
 #undef TC_LD_TILE_B
+#undef TC_MATH
 
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -332,7 +411,7 @@ __global__ __launch_bounds__(256) void merge_bf16_kernel(Geom g, AttnArgs a, con
 }
 
 template <int RB>
-static hipError_t launch_attn_rb(const Geom &g, const BatchDev &b, const AttnArgs &a, hipStream_t s)
+static hipError_t launch_attn_rb(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L)
 {
     static bool configured = false;
     if (!configured) {
@@ -341,25 +420,25 @@ static hipError_t launch_attn_rb(const Geom &g, const BatchDev &b, const AttnArg
         if (e != hipSuccess) return e;
         configured = true;
     }
-    attn_bf16_kernel<RB><<<a.n_items, 256, kLdsBytes, s>>>(g, b, a);
+    TC_LAUNCH(attn_bf16_kernel<RB>, a.n_items + a.n_append, kLdsBytes, L, g, b, a);
     return hipGetLastError();
 }
 
-hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, int row_blocks, hipStream_t s)
+hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, int row_blocks, const Launch &L)
 {
-    if (a.n_items == 0) return hipSuccess;
+    if (a.n_items + a.n_append == 0) return hipSuccess;
     if (g.D != 128 || g.esize != 2) return hipErrorInvalidValue;
-    if (row_blocks == 1) return launch_attn_rb<1>(g, b, a, s);
-    if (row_blocks == 2) return launch_attn_rb<2>(g, b, a, s);
+    if (row_blocks == 1) return launch_attn_rb<1>(g, b, a, L);
+    if (row_blocks == 2) return launch_attn_rb<2>(g, b, a, L);
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_merge_bf16(const Geom &g, const AttnArgs &a, const MergeGroup *groups, int n_groups,
-                             int row_blocks, hipStream_t s)
+                             int row_blocks, const Launch &L)
 {
     if (n_groups == 0) return hipSuccess;
     const int n_rb = 4 * row_blocks;                   // 32-row blocks per group
-    merge_bf16_kernel<<<n_groups * n_rb * 4, 256, 0, s>>>(g, a, groups, n_groups, n_rb);
+    TC_LAUNCH(merge_bf16_kernel, n_groups * n_rb * 4, 0, L, g, a, groups, n_groups, n_rb);
     return hipGetLastError();
 }
 

@@ -112,13 +112,13 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(Geom g, BatchDev b, AttnA
     }
 }
 
-hipError_t launch_attn_f32(const Geom &g, const BatchDev &b, const AttnArgs &a, hipStream_t s)
+hipError_t launch_attn_f32(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L)
 {
     if (a.n_items == 0) return hipSuccess;
     if (g.D == 64)
-        attn_f32_kernel<64><<<a.n_items, 256, 0, s>>>(g, b, a);
+        TC_LAUNCH(attn_f32_kernel<64>, a.n_items, 0, L, g, b, a);
     else if (g.D == 128)
-        attn_f32_kernel<128><<<a.n_items, 256, 0, s>>>(g, b, a);
+        TC_LAUNCH(attn_f32_kernel<128>, a.n_items, 0, L, g, b, a);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
@@ -156,15 +156,15 @@ __global__ __launch_bounds__(256) void merge_kernel(Geom g, BatchDev b, AttnArgs
     for (int c = 0; c * 64 < D; ++c) o[lane + 64 * c] = (OutT)(acc[c] * inv);
 }
 
-hipError_t launch_merge(const Geom &g, const BatchDev &b, const AttnArgs &a, hipStream_t s)
+hipError_t launch_merge(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L)
 {
     const int64_t n_rows = (int64_t)b.total_S * g.Hq;
     if (n_rows == 0) return hipSuccess;
     const int grid = (int)((n_rows + 3) / 4);
     if (g.esize == 2)
-        merge_kernel<__bf16><<<grid, 256, 0, s>>>(g, b, a);
+        TC_LAUNCH(merge_kernel<__bf16>, grid, 0, L, g, b, a);
     else
-        merge_kernel<float><<<grid, 256, 0, s>>>(g, b, a);
+        TC_LAUNCH(merge_kernel<float>, grid, 0, L, g, b, a);
     return hipGetLastError();
 }
 

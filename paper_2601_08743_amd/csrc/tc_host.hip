@@ -172,16 +172,15 @@ hipEvent_t take_event(tc_ctx *ctx)
     return e;
 }
 
-// Run `launch` on `stream`; with profiling on, bracket it with two timing events.
+// Run `launch` on `stream`; with profiling on, give it two events that receive the dispatch's
+// begin and end timestamps.
 template <typename F>
 hipError_t timed_launch(tc_ctx *ctx, int kind, hipStream_t stream, F launch)
 {
-    if (!ctx->profiling) return launch();
+    if (!ctx->profiling) return launch(Launch{stream, nullptr, nullptr});
     hipEvent_t a = take_event(ctx), b = take_event(ctx);
     if (!a || !b) return hipErrorOutOfMemory;
-    hipError_t e = hipEventRecord(a, stream);
-    if (e == hipSuccess) e = launch();
-    if (e == hipSuccess) e = hipEventRecord(b, stream);
+    hipError_t e = launch(Launch{stream, a, b});
     ctx->timed.push_back(tc_ctx::Timed{kind, a, b});
     return e;
 }
@@ -241,6 +240,11 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
     const int G = c.n_q_heads / c.n_kv_heads;
     const bool bf16 = c.dtype == TC_BF16;
     const int KT = bf16 ? kAttnKeys : kF32Keys;
+    // key tiles of a query.  bf16 kernel: the tiles of the prefix (from the pool), then the tiles of
+    // the suffix (from k_new / v_new); fp32 kernel: one paged sequence of P + S keys
+    auto tiles_of = [&](int P, int S) {
+        return bf16 ? (P + KT - 1) / KT + (S + KT - 1) / KT : (P + S + KT - 1) / KT;
+    };
     // bf16: 128 rows per work-group; 256 (two row blocks per wave, half the LDS traffic per flop but one
     // wave per SIMD) is kept as an option: it is slower until its matrix and vector work overlap
     const int rb = (bf16 && ctx->forced_row_blocks > 0) ? ctx->forced_row_blocks : 1;
@@ -250,64 +254,102 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
     for (int i = 0; i < p.B; ++i)
         if (p.suffix_len[i] > 0) {
             base += (int64_t)c.n_kv_heads * ((p.suffix_len[i] * G + RT - 1) / RT);
-            tiles_sum += (p.prefix_len[i] + p.suffix_len[i] + KT - 1) / KT;
+            tiles_sum += tiles_of(p.prefix_len[i], p.suffix_len[i]);
             ++n_q;
         }
-    // Number of key partitions: a small cost model, in units of one key tile of one work-group.
-    // Work-groups per CU x key tiles per work-group (two co-resident work-groups overlap each other's
-    // stalls: x0.7), plus a fixed start-up/epilogue cost, plus the merge (grows with the partial
-    // traffic).  The constants were fitted to split-count sweeps on c2 and c5-sized batches.
+    // Number of key partitions: a small cost model, in units of one key tile of one work-group
+    // (~1.4 us).  The work items of one (query, KV head, partition) - a bucket - go to one XCD (they
+    // share its L2), so what counts is the most loaded XCD: buckets per XCD x items per bucket over
+    // its 32 CUs gives the work-groups per CU (a whole number while the chip is not full: 35 items
+    // on an XCD mean 3 CUs run two and the launch takes as long as with 64); times the key tiles per
+    // work-group (co-resident work-groups overlap each other's stalls: x0.7); plus a fixed start-up
+    // and epilogue cost; plus the merge: a launch and the partials written and read back at about
+    // 4 TB/s.  Fitted to split-count sweeps and per-work-group traces on c2, c3 and c5-sized batches.
     int want = 1;
     if (ctx->forced_splits > 0) want = ctx->forced_splits;
     else if (base > 0) {
-        const double cus = 256.0;
         const double tiles = (double)tiles_sum / (double)n_q;
+        const double items_per_bucket = (double)base / (double)(n_q * c.n_kv_heads);
+        const double rows = (double)p.total_S * c.n_q_heads;
         double best = 1e30;
         for (int ns = 1; ns <= 32; ++ns) {
             if (ns > 1 && tiles / ns < 2.0) break;
-            const double per_cu = std::ceil((double)base * ns / cus);
-            const double cost = per_cu * (tiles / ns) * (per_cu >= 2.0 ? 0.7 : 1.0) + 3.0 +
-                                (ns > 1 ? 1.0 + 0.4 * ns : 0.0);
+            const double load = std::ceil((double)n_q * c.n_kv_heads * ns / 8.0) * items_per_bucket / 32.0;
+            const double per_cu = load <= 1.0 ? 1.0 : (load <= 2.0 ? 2.0 : load);
+            const double merge = ns > 1 ? 1.0 + 1.86e-4 * ns * rows : 0.0;
+            const double cost = per_cu * (tiles / ns) * (per_cu >= 2.0 ? 0.7 : 1.0) + 3.0 + merge;
             if (cost < best - 1e-9) { best = cost; want = ns; }
         }
     }
     splits_of_q.assign(p.B, 1);
     p.max_splits = 1;
-    std::vector<std::vector<AttnItem>> per_xcd(8);
-    int bucket = 0, n_groups = 0;
+    std::vector<std::vector<AttnItem>> buckets;     // items of one (query, KV head, partition)
+    int n_groups = 0;
     for (int i = 0; i < p.B; ++i) {
         const int S = p.suffix_len[i], P = p.prefix_len[i];
         if (S <= 0) continue;
-        const int n_tiles = (P + S + KT - 1) / KT;
-        const int n_blk = (P + S + kBlockTokens - 1) / kBlockTokens;
+        const int n_tiles = tiles_of(P, S);
+        // last block a tile load may touch: bf16 reads only prefix blocks from the pool
+        const int last_blk = std::max(0, (bf16 ? (P + kBlockTokens - 1) / kBlockTokens
+                                               : (P + S + kBlockTokens - 1) / kBlockTokens) - 1);
         int ns = std::min(want, ctx->forced_splits > 0 ? n_tiles : std::max(1, n_tiles / 2));
         if (bf16) ns = std::max(ns, (n_tiles + kAttnMaxTiles - 1) / kAttnMaxTiles);   // block ids of a range fit LDS
         ns = std::max(1, std::min(ns, n_tiles));
         splits_of_q[i] = ns;
         p.max_splits = std::max(p.max_splits, ns);
         const int n_mt = (S * G + RT - 1) / RT;
+        // Partition boundaries.  A suffix tile of the bf16 kernel costs about 3 prefix tiles (its V
+        // is transposed on the way into LDS), so the tiles are cut by weight, not by count.
+        std::vector<int> cut(ns + 1, 0);
+        {
+            const int npt = bf16 ? (P + KT - 1) / KT : n_tiles;
+            const int w_new = 3;
+            const int64_t total_w = npt + (int64_t)(n_tiles - npt) * w_new;
+            int t = 0;
+            int64_t acc = 0;
+            for (int s = 1; s < ns; ++s) {
+                const int64_t goal = total_w * s / ns;
+                while (t < n_tiles - (ns - s) && acc + (t < npt ? 1 : w_new) <= goal) { acc += (t < npt ? 1 : w_new); ++t; }
+                if (t < s) { acc += (t < npt ? 1 : w_new); ++t; }        // every partition gets a tile
+                cut[s] = t;
+            }
+            cut[ns] = n_tiles;
+        }
         const int32_t *bt = p.block_table.data() + (size_t)i * p.max_blocks;
         for (int h = 0; h < c.n_kv_heads; ++h) {
             for (int s = 0; s < ns; ++s) {
-                const int t0 = (int)((int64_t)n_tiles * s / ns), t1 = (int)((int64_t)n_tiles * (s + 1) / ns);
+                const int t0 = cut[s], t1 = cut[s + 1];
+                std::vector<AttnItem> bucket;
                 for (int mt = 0; mt < n_mt; ++mt) {
                     AttnItem it{};
                     it.q = i; it.kvh = h; it.m0 = mt * RT; it.tile_begin = t0; it.tile_end = t1;
                     it.split = s; it.n_splits = ns; it.group = n_groups + mt;
                     it.P = P; it.S = S; it.cu = p.cu_seqlens[i];
                     for (int k = 0; k < 8; ++k)
-                        it.bid[k] = bt[std::min(t0 * (KT / kBlockTokens) + k, n_blk - 1)];
-                    per_xcd[bucket & 7].push_back(it);
+                        it.bid[k] = bt[std::min(t0 * (KT / kBlockTokens) + k, last_blk)];
+                    bucket.push_back(it);
                 }
-                ++bucket;
+                buckets.push_back(std::move(bucket));
             }
             for (int mt = 0; mt < n_mt; ++mt) groups.push_back(MergeGroup{h, mt * RT, ns, p.cu_seqlens[i], S, {0, 0, 0}});
             n_groups += n_mt;
         }
     }
     p.n_groups = n_groups;
-    for (auto &v : per_xcd)
-        for (auto &it : v) it.n_groups = n_groups;
+    // Longest buckets first, each to the XCD with the least work so far (key tiles x items): long
+    // work-groups start early, XCDs finish together.
+    std::stable_sort(buckets.begin(), buckets.end(), [](const std::vector<AttnItem> &x, const std::vector<AttnItem> &y) {
+        return x[0].tile_end - x[0].tile_begin > y[0].tile_end - y[0].tile_begin;
+    });
+    std::vector<std::vector<AttnItem>> per_xcd(8);
+    int64_t xcd_load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (auto &bk : buckets) {
+        int xcd = 0;
+        for (int x = 1; x < 8; ++x)
+            if (xcd_load[x] < xcd_load[xcd]) xcd = x;
+        xcd_load[xcd] += (int64_t)(bk[0].tile_end - bk[0].tile_begin + 3) * (int64_t)bk.size();
+        for (auto &it : bk) { it.n_groups = n_groups; per_xcd[xcd].push_back(it); }
+    }
     size_t longest = 0;
     for (auto &v : per_xcd) longest = std::max(longest, v.size());
     items.clear();
@@ -670,7 +712,7 @@ tc_status tc_stitch_kv(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_
             TC_HIP(ctx, hipStreamWaitEvent(stream, sl.ready, 0));
     }
     ctx->plan = std::move(p);
-    TC_HIP(ctx, timed_launch(ctx, 0, stream, [&] { return launch_stitch(ctx->geom, ctx->plan.dev, 0, L, stream); }));
+    TC_HIP(ctx, timed_launch(ctx, 0, stream, [&](const Launch &ln) { return launch_stitch(ctx->geom, ctx->plan.dev, 0, L, ln); }));
     if (!used_slots.empty()) {
         const int32_t ev = ctx->read_next;
         ctx->read_next = (ctx->read_next + 1) % (int32_t)ctx->read_ring.size();
@@ -733,23 +775,25 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
     if (((uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)out) & 15)
         return fail(ctx, TC_ERR_INVALID, "attn: tensors must be 16-byte aligned");
 
-    TC_HIP(ctx, timed_launch(ctx, 1, stream, [&] { return launch_append(ctx->geom, p.dev, layer, k_new, v_new, stream); }));
+    const bool bf16 = ctx->cfg.dtype == TC_BF16;
+    if (!bf16)      // the bf16 attention launch appends in extra work-groups of its own
+        TC_HIP(ctx, timed_launch(ctx, 1, stream, [&](const Launch &ln) { return launch_append(ctx->geom, p.dev, layer, k_new, v_new, ln); }));
     AttnArgs a{};
-    a.q = q; a.out = out; a.items = p.items_dev; a.n_items = p.n_items; a.layer = layer;
+    a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
+    a.n_append = bf16 ? p.total_S + p.B : 0; a.items = p.items_dev; a.n_items = p.n_items; a.layer = layer;
     a.scale_log2 = sm_scale * 1.4426950408889634f;
     a.part_o = ctx->d_part;
-    const bool bf16 = ctx->cfg.dtype == TC_BF16;
     a.part_ml = !ctx->d_part ? nullptr
               : bf16 ? ctx->d_part + (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * 128
                      : ctx->d_part + (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * ctx->cfg.head_dim;
-    TC_HIP(ctx, timed_launch(ctx, 2, stream, [&] {
-        return ctx->cfg.dtype == TC_BF16 ? launch_attn_bf16(ctx->geom, p.dev, a, p.row_blocks, stream)
-                                         : launch_attn_f32(ctx->geom, p.dev, a, stream);
+    TC_HIP(ctx, timed_launch(ctx, 2, stream, [&](const Launch &ln) {
+        return bf16 ? launch_attn_bf16(ctx->geom, p.dev, a, p.row_blocks, ln)
+                    : launch_attn_f32(ctx->geom, p.dev, a, ln);
     }));
     if (p.max_splits > 1)
-        TC_HIP(ctx, timed_launch(ctx, 3, stream, [&] {
-            return bf16 ? launch_merge_bf16(ctx->geom, a, p.groups_dev, p.n_groups, p.row_blocks, stream)
-                        : launch_merge(ctx->geom, p.dev, a, stream);
+        TC_HIP(ctx, timed_launch(ctx, 3, stream, [&](const Launch &ln) {
+            return bf16 ? launch_merge_bf16(ctx->geom, a, p.groups_dev, p.n_groups, p.row_blocks, ln)
+                        : launch_merge(ctx->geom, p.dev, a, ln);
         }));
     return TC_OK;
 }

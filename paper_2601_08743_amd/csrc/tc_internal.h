@@ -2,6 +2,7 @@
 // Nothing here is part of the public ABI (see include/tablecache.h).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace tc {
@@ -79,6 +80,8 @@ struct MergeGroup {
 
 struct AttnArgs {
     const void *q;
+    const void *k_new;   // suffix keys / values [sum S][Hkv][D] of this layer
+    const void *v_new;
     void *out;
     const AttnItem *items;
     float *part_o;       // split-KV partial outputs, unnormalised (layout private to each kernel)
@@ -86,19 +89,29 @@ struct AttnArgs {
     float scale_log2;    // sm_scale * log2(e)
     int32_t layer;
     int32_t n_items;
+    int32_t n_append;    // append units run by the bf16 attention launch (total_S + B), 0 = none
 };
 
+// Where a kernel goes: the stream, and optionally two events that receive the dispatch's own begin
+// and end timestamps (per-kernel timing without bracketing packets on the stream).
+struct Launch {
+    hipStream_t stream;
+    hipEvent_t start, stop;
+};
+#define TC_LAUNCH(kernel, grid, lds_bytes, L, ...) \
+    hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(256), (lds_bytes), (L).stream, (L).start, (L).stop, 0, __VA_ARGS__)
+
 // kv_stitch.hip
-hipError_t launch_stitch(const Geom &g, const BatchDev &b, int l0, int l1, hipStream_t s);
+hipError_t launch_stitch(const Geom &g, const BatchDev &b, int l0, int l1, const Launch &L);
 hipError_t launch_append(const Geom &g, const BatchDev &b, int layer, const void *k_new,
-                         const void *v_new, hipStream_t s);
+                         const void *v_new, const Launch &L);
 hipError_t launch_readback(const Geom &g, int layer, const int32_t *blocks_dev, int n_tokens,
                            void *k_out_dev, void *v_out_dev, hipStream_t s);
 // prefill_attn_bf16.hip / prefill_attn_f32.hip
-hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, int row_blocks, hipStream_t s);
-hipError_t launch_attn_f32(const Geom &g, const BatchDev &b, const AttnArgs &a, hipStream_t s);
-hipError_t launch_merge(const Geom &g, const BatchDev &b, const AttnArgs &a, hipStream_t s);
+hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, int row_blocks, const Launch &L);
+hipError_t launch_attn_f32(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L);
+hipError_t launch_merge(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L);
 hipError_t launch_merge_bf16(const Geom &g, const AttnArgs &a, const MergeGroup *groups, int n_groups,
-                             int row_blocks, hipStream_t s);
+                             int row_blocks, const Launch &L);
 
 }  // namespace tc
