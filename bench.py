@@ -190,6 +190,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="also time the layer loop replayed as a HIP graph")
     ap.add_argument("--micro-batch", type=int, default=8, help="queries per micro-batch (c5 pipeline)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="run one plain elementwise kernel of known size (reads 1 GiB, writes 1 GiB) before the "
+                         "timed region, as the reference for scaling HBM counters of a --pmc run")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -201,6 +204,12 @@ def main():
     from paper_2601_08743_amd import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate:
+        x = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
+        y = torch.empty_like(x)
+        torch.add(x, 1, out=y)
+        torch.cuda.synchronize()
+        del x, y
     if args.workload == "c5":
         if args.steps == 50:
             args.steps, args.warmup = 3, 1
