@@ -188,7 +188,7 @@ def main():
     ap.add_argument("--splits", type=int, default=0, help="force split-KV partitions (0 = automatic)")
     ap.add_argument("--row-blocks", type=int, default=0, help="force 128 (1) or 256 (2) rows per work-group")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--graph", action="store_true", help="also time the layer loop replayed as a HIP graph")
+    ap.add_argument("--no-graph", action="store_true", help="skip the extra timing of the layer loop replayed as a HIP graph")
     ap.add_argument("--micro-batch", type=int, default=8, help="queries per micro-batch (c5 pipeline)")
     ap.add_argument("--calibrate", action="store_true",
                     help="run one plain elementwise kernel of known size (reads 1 GiB, writes 1 GiB) before the "
@@ -310,7 +310,7 @@ def main():
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
     extra = {}
-    if args.graph:
+    if not args.no_graph:
         g = torch.cuda.CUDAGraph()
         layers(bt, pl)
         torch.cuda.synchronize()

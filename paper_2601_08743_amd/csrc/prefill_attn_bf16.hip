@@ -386,19 +386,36 @@ __global__ __launch_bounds__(256) void merge_bf16_kernel(Geom g, AttnArgs a, con
     const int r32 = lane & 31, hh = lane >> 5;
     const int row_m = mg.m0 + blk * 32 + r32;
     if (row_m >= mg.S * g.G) return;
-    float M = -INFINITY;
-    for (int s = 0; s < mg.n_splits; ++s)
-        M = fmaxf(M, ((const float2 *)a.part_ml)[(((int64_t)s * n_groups + group) * n_rb + blk) * 32 + r32].x);
-    float l = 0.f;
+    // partitions in chunks of 8: all loads of a chunk are issued before anything waits on them
+    float M = -INFINITY, l = 0.f;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = 0; s < mg.n_splits; ++s) {
-        const int64_t sb = ((int64_t)s * n_groups + group) * n_rb + blk;
-        const float2 ml = ((const float2 *)a.part_ml)[sb * 32 + r32];
-        const float wgt = (ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml.x - M);
-        l = fmaf(wgt, ml.y, l);
-        const float4 v = ((const float4 *)a.part_o)[(sb * 16 + frag) * 64 + lane];
-        acc.x = fmaf(wgt, v.x, acc.x); acc.y = fmaf(wgt, v.y, acc.y);
-        acc.z = fmaf(wgt, v.z, acc.z); acc.w = fmaf(wgt, v.w, acc.w);
+    const int64_t stride = (int64_t)n_groups * n_rb;          // (group, block) slots per partition
+    const int64_t gb0 = (int64_t)group * n_rb + blk;
+    for (int s0 = 0; s0 < mg.n_splits; s0 += 8) {
+        float4 v[8];
+        float2 ml[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int s = min(s0 + k, mg.n_splits - 1);
+            const int64_t sb = (int64_t)s * stride + gb0;
+            v[k] = ((const float4 *)a.part_o)[(sb * 16 + frag) * 64 + lane];
+            ml[k] = ((const float2 *)a.part_ml)[sb * 32 + r32];
+        }
+        float Mc = M;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (s0 + k < mg.n_splits) Mc = fmaxf(Mc, ml[k].x);
+        const float resc = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(M - Mc);   // earlier chunks -> new reference
+        l *= resc; acc.x *= resc; acc.y *= resc; acc.z *= resc; acc.w *= resc;
+        M = Mc;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            if (s0 + k >= mg.n_splits) continue;
+            const float wgt = (ml[k].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[k].x - M);
+            l = fmaf(wgt, ml[k].y, l);
+            acc.x = fmaf(wgt, v[k].x, acc.x); acc.y = fmaf(wgt, v[k].y, acc.y);
+            acc.z = fmaf(wgt, v[k].z, acc.z); acc.w = fmaf(wgt, v[k].w, acc.w);
+        }
     }
     const float inv = 1.f / l;
     const int s_tok = row_m / g.G;
