@@ -21,7 +21,9 @@
  *   - Streams are hipStream_t passed as void* (NULL = the default stream).  Work is
  *     enqueued and the call returns; errors of asynchronous work surface as
  *     TC_ERR_HIP from a later call.
- *   - One host thread per context at a time.
+ *   - One host thread per context at a time, and one compute stream: tc_stitch_kv uploads the
+ *     batch's integer plan on its stream, and the tc_prefill_attn calls of that batch must be
+ *     ordered after it (same stream, or the caller's own event).
  *   - Element type: TC_F32 (fp32 storage and arithmetic) or TC_BF16 (bf16 storage,
  *     fp32 accumulation on the matrix cores).  bf16 needs head_dim == 128.
  *

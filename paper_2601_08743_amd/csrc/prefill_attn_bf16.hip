@@ -25,9 +25,9 @@
 // latency-bound, so the depth of this pipeline and the length of the dependent-load chain at
 // start-up are what matter.
 //
-// Split-KV: when a query is cut into key partitions, every work-group stores its unnormalised
-// partial (O, max, sum) in accumulator-fragment order (1 KB contiguous per wave and fragment) and
-// a second kernel combines the partitions.  (Combining inside this kernel - last work-group to
+// Split-KV: when a query is cut into key partitions, every work-group stores its partial
+// (normalised O as fp16, max, sum) in accumulator-fragment order (512 B contiguous per wave and
+// fragment) and a second kernel combines the partitions.  (Combining inside this kernel - last work-group to
 // arrive folds the others in - was measured 3x slower: device-scope release/acquire on this chip
 // writes back and invalidates the XCD's whole L2, which every work-group would do.)
 #include "kv_append.h"
@@ -38,6 +38,7 @@ namespace tc {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kKRow = 272;                       // LDS bytes per K row: 256 + 16 pad (conflict-free b128 reads)
 constexpr int kHeadBlk = 4096;                   // bytes of one head's K (or V) in one block: 16 * 128 * 2
@@ -339,17 +340,23 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
     for (int rb = 0; rb < RB; ++rb) {
         const float l = st.l_lane[rb] + __shfl_xor(st.l_lane[rb], 32);
         if (it.n_splits > 1) {
-            // partial in accumulator-fragment order: 1 KB contiguous per (row block, db, q4);
-            // a group's slot holds 4 * RB row blocks of 32 rows
+            // partial in accumulator-fragment order, normalised and stored as fp16 (outputs of a
+            // softmax average are bounded by max|v|, so fp16's 11-bit mantissa costs ~3e-5 here and
+            // halves the partial traffic, the largest cost of a split launch): 512 B contiguous per
+            // (row block, db, q4); a group's slot holds 4 * RB row blocks of 32 rows
             const int64_t slot = (int64_t)it.split * it.n_groups + it.group;
             const int blk = w * RB + rb;
-            float4 *po = (float4 *)a.part_o + ((slot * (4 * RB) + blk) * 16) * 64 + lane;
+            const float inv = l > 0.f ? 1.f / l : 0.f;
+            f16x4 *po = (f16x4 *)a.part_o + ((slot * (4 * RB) + blk) * 16) * 64 + lane;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4)
-                    po[(db * 4 + q4) * 64] = make_float4(st.o[rb][db][4 * q4], st.o[rb][db][4 * q4 + 1],
-                                                         st.o[rb][db][4 * q4 + 2], st.o[rb][db][4 * q4 + 3]);
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    f16x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = (_Float16)(st.o[rb][db][4 * q4 + e] * inv);
+                    po[(db * 4 + q4) * 64] = v;
+                }
             if (hh == 0)
                 ((float2 *)a.part_ml)[(slot * (4 * RB) + blk) * 32 + r32] = make_float2(st.m_run[rb], l);
             continue;
@@ -370,10 +377,10 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
     }
 }
 
-// Combine the partitions of split queries.  One thread per float4 of a group's accumulator
+// Combine the partitions of split queries.  One thread per 4 values of a group's accumulator
 // fragment: index = ((group * n_rb + row_block) * 16 + fragment) * 64 + lane, the order the
 // attention kernel stored it in, so loads are fully coalesced.  With reference maxima m_s, sums
-// l_s and unnormalised partial outputs O_s:  out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// l_s and normalised partial outputs O_s:  out = sum_s w_s O_s / sum_s w_s,  w_s = 2^(m_s - M) l_s.
 __global__ __launch_bounds__(256) void merge_bf16_kernel(Geom g, AttnArgs a, const MergeGroup *groups,
                                                          int n_groups, int n_rb)
 {
@@ -392,13 +399,13 @@ __global__ __launch_bounds__(256) void merge_bf16_kernel(Geom g, AttnArgs a, con
     const int64_t stride = (int64_t)n_groups * n_rb;          // (group, block) slots per partition
     const int64_t gb0 = (int64_t)group * n_rb + blk;
     for (int s0 = 0; s0 < mg.n_splits; s0 += 8) {
-        float4 v[8];
+        f16x4 v[8];
         float2 ml[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int s = min(s0 + k, mg.n_splits - 1);
             const int64_t sb = (int64_t)s * stride + gb0;
-            v[k] = ((const float4 *)a.part_o)[(sb * 16 + frag) * 64 + lane];
+            v[k] = ((const f16x4 *)a.part_o)[(sb * 16 + frag) * 64 + lane];
             ml[k] = ((const float2 *)a.part_ml)[sb * 32 + r32];
         }
         float Mc = M;
@@ -411,10 +418,10 @@ __global__ __launch_bounds__(256) void merge_bf16_kernel(Geom g, AttnArgs a, con
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             if (s0 + k >= mg.n_splits) continue;
-            const float wgt = (ml[k].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[k].x - M);
-            l = fmaf(wgt, ml[k].y, l);
-            acc.x = fmaf(wgt, v[k].x, acc.x); acc.y = fmaf(wgt, v[k].y, acc.y);
-            acc.z = fmaf(wgt, v[k].z, acc.z); acc.w = fmaf(wgt, v[k].w, acc.w);
+            const float wgt = (ml[k].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[k].x - M) * ml[k].y;
+            l += wgt;
+            acc.x = fmaf(wgt, (float)v[k][0], acc.x); acc.y = fmaf(wgt, (float)v[k][1], acc.y);
+            acc.z = fmaf(wgt, (float)v[k][2], acc.z); acc.w = fmaf(wgt, (float)v[k][3], acc.w);
         }
     }
     const float inv = 1.f / l;

@@ -276,7 +276,7 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
             if (ns > 1 && tiles / ns < 2.0) break;
             const double load = std::ceil((double)n_q * c.n_kv_heads * ns / 8.0) * items_per_bucket / 32.0;
             const double per_cu = load <= 1.0 ? 1.0 : (load <= 2.0 ? 2.0 : load);
-            const double merge = ns > 1 ? 1.0 + 1.86e-4 * ns * rows : 0.0;
+            const double merge = ns > 1 ? 1.0 + 0.93e-4 * ns * rows : 0.0;   // fp16 partials: 264 B per row and partition
             const double cost = per_cu * (tiles / ns) * (per_cu >= 2.0 ? 0.7 : 1.0) + 3.0 + merge;
             if (cost < best - 1e-9) { best = cost; want = ns; }
         }
@@ -418,10 +418,10 @@ tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
     p.groups_dev = (const MergeGroup *)(d + o_gr);
 
     if (p.max_splits > 1) {
-        // bf16 kernel: per (partition, group) 128 rows x (128 + 2) floats in fragment order;
-        // fp32 kernel: per (partition, suffix token, head) D + 2 floats
+        // bf16 kernel: per (partition, group, row block) 128 rows x (128 fp16 + 2 floats) in fragment
+        // order, counted in floats; fp32 kernel: per (partition, suffix token, head) D + 2 floats
         const size_t need = ctx->cfg.dtype == TC_BF16
-            ? (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * (128 + 2)
+            ? (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * (64 + 2)
             : (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * (ctx->cfg.head_dim + 2);
         if (need > ctx->d_part_floats) {
             if (ctx->d_part) TC_HIP(ctx, hipFree(ctx->d_part));
@@ -784,7 +784,7 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
     a.scale_log2 = sm_scale * 1.4426950408889634f;
     a.part_o = ctx->d_part;
     a.part_ml = !ctx->d_part ? nullptr
-              : bf16 ? ctx->d_part + (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * 128
+              : bf16 ? ctx->d_part + (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * 64
                      : ctx->d_part + (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * ctx->cfg.head_dim;
     TC_HIP(ctx, timed_launch(ctx, 2, stream, [&](const Launch &ln) {
         return bf16 ? launch_attn_bf16(ctx->geom, p.dev, a, p.row_blocks, ln)

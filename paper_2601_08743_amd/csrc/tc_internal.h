@@ -84,7 +84,7 @@ struct AttnArgs {
     const void *v_new;
     void *out;
     const AttnItem *items;
-    float *part_o;       // split-KV partial outputs, unnormalised (layout private to each kernel)
+    float *part_o;       // split-KV partial outputs (layout and element type private to each kernel)
     float *part_ml;      // per partial row: (reference max in log2 units, sum of weights)
     float scale_log2;    // sm_scale * log2(e)
     int32_t layer;

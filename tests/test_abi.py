@@ -52,3 +52,11 @@ def test_size_helpers_are_pure_host_functions(lib):
     bad = B.make_config(1, 8, 2, 64, B.TC_F32, 10, 4, 600)              # slots do not fit the pool
     assert B.tc_pool_bytes(bad) == 0
     assert "gfx950" in B.tc_version()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N > 1 exits with a message (nothing here uses a second GPU)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr
