@@ -137,39 +137,68 @@ __device__ __forceinline__ void tile_math(RowState<RB> &st, const bf16x8 (&qf)[R
     }
 }
 
-// RB = row blocks per wave: the work-group covers 128 * RB rows.  RB = 1 runs two work-groups per
-// CU (small problems: more, smaller work items); RB = 2 one per CU with twice the work per LDS byte.
+// Geometry of one work item as every part of the kernel sees it.
 template <int RB>
-__global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g, BatchDev b, AttnArgs a)
-{
-    extern __shared__ __attribute__((aligned(16))) char lds[];
-    int32_t *s_bid = (int32_t *)(lds + 2 * kStage);
-
-    if ((int)blockIdx.x >= a.n_items) {                // extra work-groups: append the suffix to the pool
-        append_unit<true>(g, b, a.layer, (const char *)a.k_new, (const char *)a.v_new,
-                          blockIdx.x - a.n_items, threadIdx.x);
-        return;
-    }
-    const AttnItem it = a.items[blockIdx.x];
-    if (it.q < 0) return;                              // padding item (uniform for the work-group)
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, hh = lane >> 5;
-    const int G = g.G, P = it.P, S = it.S;
-    const int npt = (P + kAttnKeys - 1) >> 6;          // prefix tiles; suffix tiles follow
-    const int last_pblk = max(((P + kBlockTokens - 1) >> 4) - 1, 0);
-    const int m_rows = S * G;
-    const int wave_row0 = it.m0 + w * 32 * RB;
+struct ItemRows {
     bool valid[RB];
     int s_tok[RB], head[RB], limit[RB];
+    int wave_row0, wave_stok_min, m_rows;
+};
+
+template <int RB>
+__device__ __forceinline__ void item_rows(ItemRows<RB> &ir, const Geom &g, const AttnItem &it, int w, int r32)
+{
+    ir.m_rows = it.S * g.G;
+    ir.wave_row0 = it.m0 + w * 32 * RB;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        const int row_m = wave_row0 + rb * 32 + r32;
-        valid[rb] = row_m < m_rows;
-        const int rm = valid[rb] ? row_m : m_rows - 1;
-        s_tok[rb] = rm / G;
-        head[rb] = it.kvh * G + (rm - s_tok[rb] * G);
-        limit[rb] = s_tok[rb];                         // last visible suffix key of this row
+        const int row_m = ir.wave_row0 + rb * 32 + r32;
+        ir.valid[rb] = row_m < ir.m_rows;
+        const int rm = ir.valid[rb] ? row_m : ir.m_rows - 1;
+        ir.s_tok[rb] = rm / g.G;
+        ir.head[rb] = it.kvh * g.G + (rm - ir.s_tok[rb] * g.G);
+        ir.limit[rb] = ir.s_tok[rb];                   // last visible suffix key of this row
     }
-    const int wave_stok_min = min(wave_row0, m_rows - 1) / G;
+    ir.wave_stok_min = min(ir.wave_row0, ir.m_rows - 1) / g.G;
+}
+
+// Q^T fragments (B operand): lane (row r32, half hh) holds q[row][16*ks + 8*hh .. +8].
+template <int RB>
+__device__ __forceinline__ void load_q(bf16x8 (&qf)[RB][8], const Geom &g, const AttnArgs &a, const AttnItem &it,
+                                       const ItemRows<RB> &ir, int hh)
+{
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const char *qp = (const char *)a.q + ((int64_t)(it.cu + ir.s_tok[rb]) * g.Hq + ir.head[rb]) * 256 + hh * 16;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[rb][ks] = *(const bf16x8 *)(qp + ks * 32);
+    }
+}
+
+// Block ids of the item's key range -> LDS (past the prefix: a valid block, never used).
+__device__ __forceinline__ void fill_bids(int32_t *s_bid, const BatchDev &b, const AttnItem &it, int tid)
+{
+    const int last_pblk = max(((it.P + kBlockTokens - 1) >> 4) - 1, 0);
+    const int n_tiles = it.tile_end - it.tile_begin;
+    const int32_t *bt = b.block_table + (int64_t)it.q * b.max_blocks;
+    for (int idx = tid; idx < n_tiles * 4; idx += 256) s_bid[idx] = bt[min(it.tile_begin * 4 + idx, last_pblk)];
+}
+
+// The general key-tile loop: tiles [r0, n_tiles) of the item, any mix of prefix tiles (pool, through
+// the block ids in LDS), the ragged last prefix tile and causal suffix tiles (k_new / v_new).
+// K/V travel global -> registers (issued a whole iteration = two tiles ahead) -> two LDS buffers of
+// kStage bytes at the start of `lds`.  With r0 == 0 the first two tiles take their block ids from the
+// item, so their loads do not wait for the block-id table; `do_fill` then fills that table here,
+// after the loads are on their way.
+template <int RB>
+__device__ __forceinline__ void tile_loop(RowState<RB> &st, const bf16x8 (&qf)[RB][8], const Geom &g,
+                                          const BatchDev &b, const AttnArgs &a, const AttnItem &it,
+                                          const ItemRows<RB> &ir, char *lds, int32_t *s_bid, int r0, bool do_fill,
+                                          int tid)
+{
+    const int lane = tid & 63, r32 = lane & 31, hh = lane >> 5;
+    const int P = it.P, S = it.S;
+    const int npt = (P + kAttnKeys - 1) >> 6;          // prefix tiles; suffix tiles follow
     const int n_tiles = it.tile_end - it.tile_begin, last = n_tiles - 1;
     // Addresses are (uniform 64-bit base) + (32-bit per-thread offset), so that the loads take their
     // base from scalar registers and no 64-bit address arithmetic or registers are spent per load.
@@ -186,17 +215,6 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
     const int tv = tid & 15;                           // V of suffix tiles: token within the block,
     const uint32_t cv_off = (tid >> 4) * 16;           // and 16-byte chunk of its row
 
-    // Q^T fragments (B operand): lane (row r32, half hh) holds q[row][16*ks + 8*hh .. +8].
-    // Issued before any K/V load: vector loads return in order, so once the first K/V tile has
-    // arrived these have too, and no wait on them is left inside the tile loop (a wait there
-    // would drain the K/V prefetches every iteration).
-    bf16x8 qf[RB][8];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const char *qp = (const char *)a.q + ((int64_t)(it.cu + s_tok[rb]) * g.Hq + head[rb]) * 256 + hh * 16;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[rb][ks] = *(const bf16x8 *)(qp + ks * 32);
-    }
     // named prefetch registers (arrays of uint4 end up in scratch): set A and set B
     uint4 ka0, ka1, ka2, ka3, va0, va1, va2, va3;
     uint4 kb0, kb1, kb2, kb3, vb0, vb1, vb2, vb3;
@@ -213,39 +231,43 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
         kx = *(const uint4 *)(kn_s + ((uint32_t)min((tok_) + t16, S - 1) * new_row + c_off));  \
         vx = *(const uint4 *)(vn_s + ((uint32_t)min((tok_) + tv, S - 1) * new_row + cv_off));  \
     }
+#define TC_LD_TILE(r_, k0_, k1_, k2_, k3_, v0_, v1_, v2_, v3_)                                    \
+    {                                                                                             \
+        const int rr_ = (r_);                                                                     \
+        if (it.tile_begin + rr_ < npt) {                                                          \
+            const int32_t *bp = s_bid + rr_ * 4;                                                  \
+            TC_LD(k0_, v0_, bp[0]) TC_LD(k1_, v1_, bp[1]) TC_LD(k2_, v2_, bp[2]) TC_LD(k3_, v3_, bp[3]) \
+        } else {                                                                                  \
+            const int t0_ = (it.tile_begin + rr_ - npt) * kAttnKeys;                              \
+            TC_LD_NEW(k0_, v0_, t0_) TC_LD_NEW(k1_, v1_, t0_ + 16)                                \
+            TC_LD_NEW(k2_, v2_, t0_ + 32) TC_LD_NEW(k3_, v3_, t0_ + 48)                           \
+        }                                                                                         \
+    }
+#define TC_LD_TILE_A(r_) TC_LD_TILE(r_, ka0, ka1, ka2, ka3, va0, va1, va2, va3)
+#define TC_LD_TILE_B(r_) TC_LD_TILE(r_, kb0, kb1, kb2, kb3, vb0, vb1, vb2, vb3)
     // Every prefetch is issued unconditionally, eight loads per tile whatever its kind (past the
     // end of the range the tile index is clamped and the data never used): with loads under a
     // condition the compiler cannot count how many are outstanding and falls back to waiting for
     // all of them, which empties the pipeline.
-    // First two tiles: block ids come with the item.
-    if (it.tile_begin < npt) {
-        TC_LD(ka0, va0, it.bid[0]) TC_LD(ka1, va1, it.bid[1]) TC_LD(ka2, va2, it.bid[2]) TC_LD(ka3, va3, it.bid[3])
+    if (r0 == 0) {
+        // first two tiles: block ids come with the item
+        if (it.tile_begin < npt) {
+            TC_LD(ka0, va0, it.bid[0]) TC_LD(ka1, va1, it.bid[1]) TC_LD(ka2, va2, it.bid[2]) TC_LD(ka3, va3, it.bid[3])
+        } else {
+            const int t0_ = (it.tile_begin - npt) * kAttnKeys;
+            TC_LD_NEW(ka0, va0, t0_) TC_LD_NEW(ka1, va1, t0_ + 16) TC_LD_NEW(ka2, va2, t0_ + 32) TC_LD_NEW(ka3, va3, t0_ + 48)
+        }
+        if (it.tile_begin + 1 < npt) {
+            TC_LD(kb0, vb0, it.bid[4]) TC_LD(kb1, vb1, it.bid[5]) TC_LD(kb2, vb2, it.bid[6]) TC_LD(kb3, vb3, it.bid[7])
+        } else {
+            const int t0_ = max(it.tile_begin + 1 - npt, 0) * kAttnKeys;
+            TC_LD_NEW(kb0, vb0, t0_) TC_LD_NEW(kb1, vb1, t0_ + 16) TC_LD_NEW(kb2, vb2, t0_ + 32) TC_LD_NEW(kb3, vb3, t0_ + 48)
+        }
     } else {
-        const int t0_ = (it.tile_begin - npt) * kAttnKeys;
-        TC_LD_NEW(ka0, va0, t0_) TC_LD_NEW(ka1, va1, t0_ + 16) TC_LD_NEW(ka2, va2, t0_ + 32) TC_LD_NEW(ka3, va3, t0_ + 48)
+        TC_LD_TILE_A(min(r0, last))
+        TC_LD_TILE_B(min(r0 + 1, last))
     }
-    if (it.tile_begin + 1 < npt) {
-        TC_LD(kb0, vb0, it.bid[4]) TC_LD(kb1, vb1, it.bid[5]) TC_LD(kb2, vb2, it.bid[6]) TC_LD(kb3, vb3, it.bid[7])
-    } else {
-        const int t0_ = max(it.tile_begin + 1 - npt, 0) * kAttnKeys;
-        TC_LD_NEW(kb0, vb0, t0_) TC_LD_NEW(kb1, vb1, t0_ + 16) TC_LD_NEW(kb2, vb2, t0_ + 32) TC_LD_NEW(kb3, vb3, t0_ + 48)
-    }
-    // block ids of the whole key range -> LDS
-    {
-        const int32_t *bt = b.block_table + (int64_t)it.q * b.max_blocks;
-        for (int idx = tid; idx < n_tiles * 4; idx += 256)     // past the prefix: a valid block, never used
-            s_bid[idx] = bt[min(it.tile_begin * 4 + idx, last_pblk)];
-    }
-    RowState<RB> st;
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) st.o[rb][db][e] = 0.f;
-        st.m_run[rb] = -INFINITY;
-        st.l_lane[rb] = 0.f;
-    }
+    if (do_fill) fill_bids(s_bid, b, it, tid);
     const float c = a.scale_log2;
 
     char *k_st = lds + (tid >> 4) * kKRow + (tid & 15) * 16;        // + stage * kStage
@@ -286,20 +308,6 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
             TC_ST_VT(vt + 2 * kHeadBlk, v2_) TC_ST_VT(vt + 3 * kHeadBlk, v3_)                     \
         }                                                                                         \
     }
-#define TC_LD_TILE(r_, k0_, k1_, k2_, k3_, v0_, v1_, v2_, v3_)                                    \
-    {                                                                                             \
-        const int rr_ = (r_);                                                                     \
-        if (it.tile_begin + rr_ < npt) {                                                          \
-            const int32_t *bp = s_bid + rr_ * 4;                                                  \
-            TC_LD(k0_, v0_, bp[0]) TC_LD(k1_, v1_, bp[1]) TC_LD(k2_, v2_, bp[2]) TC_LD(k3_, v3_, bp[3]) \
-        } else {                                                                                  \
-            const int t0_ = (it.tile_begin + rr_ - npt) * kAttnKeys;                              \
-            TC_LD_NEW(k0_, v0_, t0_) TC_LD_NEW(k1_, v1_, t0_ + 16)                                \
-            TC_LD_NEW(k2_, v2_, t0_ + 32) TC_LD_NEW(k3_, v3_, t0_ + 48)                           \
-        }                                                                                         \
-    }
-#define TC_LD_TILE_A(r_) TC_LD_TILE(r_, ka0, ka1, ka2, ka3, va0, va1, va2, va3)
-#define TC_LD_TILE_B(r_) TC_LD_TILE(r_, kb0, kb1, kb2, kb3, vb0, vb1, vb2, vb3)
     // prefix tile: keys count from 0 and the last valid one is P-1; suffix tile: keys count from the
     // first suffix token and row r sees those up to its own token
 #define TC_MATH(r_, stage_)                                                                       \
@@ -308,15 +316,15 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
         const bool pre_ = tt_ < npt;                                                              \
         const int key0 = (pre_ ? tt_ : tt_ - npt) * kAttnKeys;                                    \
         int lim_[RB];                                                                             \
-        _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) lim_[rb] = pre_ ? P - 1 : limit[rb];    \
+        _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) lim_[rb] = pre_ ? P - 1 : ir.limit[rb]; \
         tile_math<RB>(st, qf, k_ld + (stage_) * kStage, v_ld + (stage_) * kStage, key0, lim_,     \
-                      key0 + kAttnKeys - 1 > (pre_ ? P - 1 : wave_stok_min), hh, c);              \
+                      key0 + kAttnKeys - 1 > (pre_ ? P - 1 : ir.wave_stok_min), hh, c);           \
     }
 
     // Two key tiles (128 keys) per iteration: their K/V are loaded into the two register sets
     // one whole iteration before they are stored to LDS, so the only wait the loads ever need is
     // "all outstanding", at a point where a full iteration of math has covered their latency.
-    for (int r = 0; r < n_tiles; r += 2) {
+    for (int r = r0; r < n_tiles; r += 2) {
         const bool new_a = it.tile_begin + min(r, last) >= npt, new_b = it.tile_begin + min(r + 1, last) >= npt;
         __syncthreads();                               // both LDS stages free (s_bid visible on the first pass)
         TC_ST(0, new_a, ka0, ka1, ka2, ka3, va0, va1, va2, va3)
@@ -335,7 +343,14 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
 #undef TC_LD_TILE_A
 #undef TC_LD_TILE_B
 #undef TC_MATH
+}
 
+// Final normalisation and store: the output rows, or (split queries) this partition's partial.
+template <int RB>
+__device__ __forceinline__ void store_rows(const RowState<RB> &st, const Geom &g, const AttnArgs &a,
+                                           const AttnItem &it, const ItemRows<RB> &ir, int w, int lane)
+{
+    const int r32 = lane & 31, hh = lane >> 5;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         const float l = st.l_lane[rb] + __shfl_xor(st.l_lane[rb], 32);
@@ -361,8 +376,8 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
                 ((float2 *)a.part_ml)[(slot * (4 * RB) + blk) * 32 + r32] = make_float2(st.m_run[rb], l);
             continue;
         }
-        if (!valid[rb]) continue;
-        const int64_t row = (int64_t)(it.cu + s_tok[rb]) * g.Hq + head[rb];
+        if (!ir.valid[rb]) continue;
+        const int64_t row = (int64_t)(it.cu + ir.s_tok[rb]) * g.Hq + ir.head[rb];
         const float inv = 1.f / l;
         char *op = (char *)a.out + row * 256 + hh * 8;
 #pragma unroll
@@ -374,6 +389,411 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
                 for (int e = 0; e < 4; ++e) v[e] = (__bf16)(st.o[rb][db][4 * q4 + e] * inv);
                 *(bf16x4 *)(op + (32 * db + 8 * q4) * 2) = v;
             }
+    }
+}
+
+template <int RB>
+__device__ __forceinline__ void reset_rows(RowState<RB> &st)
+{
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) st.o[rb][db][e] = 0.f;
+        st.m_run[rb] = -INFINITY;
+        st.l_lane[rb] = 0.f;
+    }
+}
+
+// The plain kernel: the general tile loop over the whole key range.  RB = row blocks per wave: the
+// work-group covers 128 * RB rows; RB = 2 runs one work-group per CU with twice the work per LDS byte.
+template <int RB>
+__global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g, BatchDev b, AttnArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    int32_t *s_bid = (int32_t *)(lds + 2 * kStage);
+
+    if ((int)blockIdx.x >= a.n_items) {                // extra work-groups: append the suffix to the pool
+        append_unit<true>(g, b, a.layer, (const char *)a.k_new, (const char *)a.v_new,
+                          blockIdx.x - a.n_items, threadIdx.x);
+        return;
+    }
+    const AttnItem it = a.items[blockIdx.x];
+    if (it.q < 0) return;                              // padding item (uniform for the work-group)
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    ItemRows<RB> ir;
+    item_rows<RB>(ir, g, it, w, lane & 31);
+    // Q is issued before any K/V load: vector loads return in order, so once the first K/V tile has
+    // arrived these have too, and no wait on them is left inside the tile loop (a wait there
+    // would drain the K/V prefetches every iteration).
+    bf16x8 qf[RB][8];
+    load_q<RB>(qf, g, a, it, ir, lane >> 5);
+    RowState<RB> st;
+    reset_rows<RB>(st);
+    tile_loop<RB>(st, qf, g, b, a, it, ir, lds, s_bid, 0, true, tid);
+    store_rows<RB>(st, g, a, it, ir, w, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// The pipelined path for runs of full, unmasked prefix tiles (the bulk of a long schema prefix).
+//
+// Three things distinguish it from the general loop:
+//  * A fixed softmax reference per row (the maximum over the first 32 keys of the run) instead of
+//    a running maximum: p = 2^(s*c - ref) needs no per-tile maximum and O is never rescaled, so
+//    only matrix instructions touch O.  Any finite reference gives the same quotient O / l; what can
+//    go wrong is overflow when later scores exceed the reference by ~2^100, which is detected from l
+//    after the run and answered by redoing the item in the general loop (running maximum).
+//  * A three-stage software pipeline inside every wave: step s issues the matrix instructions of
+//    QK^T for tile s+1 and of PV for tile s-1 while the vector unit turns the scores of tile s into
+//    weights.  One matrix instruction, one LDS operand read (three slots ahead) and the fused
+//    multiply-add / exp2 / add / pack of one score - each belonging to a different score, so none waits
+//    on the one before - make a "slot"; a step is 32 slots in a fixed order.
+//  * K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes
+//    land at M0 + 16 l), which frees the 64 registers the general loop stages two tiles in and lets
+//    loads run four tiles ahead.  Four K buffers + four V buffers (128 KB) hold them; K rows are 256 B
+//    with the 16-byte chunk index XORed with (row & 15) - each lane picks the global chunk that
+//    belongs at its LDS position - so the operand reads are bank-conflict free without padding.
+//
+// Timeline (tiles of the run are 0 .. n-1):  prime: QK(0), reference, weights of its first 32 keys;
+// step s = 0 .. n: QK(s+1) | weights of tile s keys 32..63 and tile s+1 keys 0..31 | PV(s-1).
+// Between steps: wait for the tiles the next step reads, barrier, issue the loads that reuse the
+// buffers the finished step released: K(s+5) into K(s+1)'s, V(s+3) into V(s-1)'s.
+constexpr int kFastKTile = kAttnKeys * 256;               // 16 KB, swizzled rows
+constexpr int kFastBufs = 4;
+constexpr int kFastV = kFastBufs * kFastKTile;            // V buffers follow the K buffers
+constexpr int kFastBid = kFastV + kFastBufs * kVTile;     // block ids of the item's key range
+constexpr int kLdsBytesPipe = kFastBid + kBidBytes;
+static_assert(kLdsBytesPipe <= 160 * 1024 && 2 * kStage <= kFastBid, "LDS layout");
+constexpr int kFastMinTiles = 3;                          // shorter runs take the general loop
+
+#define TC_SB() __builtin_amdgcn_sched_barrier(0)
+
+// 16 bytes per lane from (uniform base + per-lane offset) to LDS at lds_dst + 16 * lane.
+__device__ __forceinline__ void load_to_lds(uint32_t lds_dst, const char *base, uint32_t voff)
+{
+    // both must sit in scalar registers: make their uniformity explicit
+    const uint64_t b64 = (uint64_t)(uintptr_t)base;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b64), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b64 >> 32));
+    const uint64_t sb = ((uint64_t)hi << 32) | lo;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_dst)), "v"(voff), "s"(sb) : "memory", "m0");
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct FastState {
+    f32x16 S[4];        // scores / weights in stream order: even tile keys 32..63, odd tile keys 0..31,
+                        // odd tile keys 32..63, even tile keys 0..31
+    u32x4 pE[4], pO[4]; // packed bf16 weights of the last even / odd tile, one register set per 16 keys
+    float l, nm;        // this lane's part of the row sum; minus the reference (log2 units)
+};
+
+// The instructions of the pipelined steps are written out one by one.  The compiler still allocates
+// the registers and inserts the waits for the LDS reads, but it neither reorders these instructions
+// nor chooses their register classes, and both matter here:
+//  * the kernel runs one work-group per CU (LDS), so a wave may use 512 registers, but only 256 of
+//    them are ordinary VGPRs; the others (AGPRs) can only be accumulators.  O is touched by nothing
+//    but matrix instructions in these steps, so it lives there ("a" below) and leaves the VGPRs to
+//    the scores, weights, Q and operand fragments ("v").  Left to itself the compiler puts every
+//    accumulator of such a kernel, the scores included, into AGPRs and copies them out one by one.
+//  * a matrix instruction's result must not be read by a vector instruction for 11 cycles after
+//    issue, and the hardware does not interlock this: the fixed order below keeps every such pair
+//    three or more slots (> 100 cycles) apart.
+__device__ __forceinline__ void mfma_first(f32x16 &acc, const bf16x8 &a, const bf16x8 &b)     // acc = a b
+{
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_v(f32x16 &acc, const bf16x8 &a, const bf16x8 &b)         // acc += a b
+{
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_a(f32x16 &acc, const bf16x8 &a, const u32x4 &b)          // same, AGPR accumulator
+{
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void v_scale(float &x, float c, float nm)                          // x = x c + nm
+{
+    asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(x) : "s"(c), "v"(nm));
+}
+__device__ __forceinline__ void v_exp2(float &x) { asm volatile("v_exp_f32 %0, %0" : "+v"(x)); }
+__device__ __forceinline__ void v_acc(float &l, float x) { asm volatile("v_add_f32 %0, %0, %1" : "+v"(l) : "v"(x)); }
+__device__ __forceinline__ void v_pack(uint32_t &d, float lo, float hi)
+{
+    asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(d) : "v"(lo), "v"(hi));
+}
+
+// One step.  PAR = parity of s.  kb / vb: this lane's LDS read addresses for K(s+1) / V(s-1); the
+// K chunk of k-step ks sits at kb ^ (ks << 5) (the XOR swizzle; bits 5..7 of kb hold the lane's key).
+// QK: tile s+1 exists, PV: tile s-1 exists - compile-time, because a run-time test per matrix
+// instruction costs 12 % of a step.  They switch only the matrix instructions: the vector
+// work runs unconditionally (on stale registers where a tile does not exist: finite, and never
+// used); the row sum collects the weights of tile s and of tile s+1 separately (l_cur, l_nxt) and
+// the caller adds each only if its tile exists.
+template <int PAR, bool QK, bool PV>
+__device__ __forceinline__ void fast_step(FastState &fs, f32x16 (&o)[4], const bf16x8 (&qf)[8], uint32_t kb,
+                                          uint32_t vb, float c, float &l_cur, float &l_nxt)
+{
+    u32x4 (&Pcur)[4] = PAR == 0 ? fs.pE : fs.pO;       // weights of tile s (parity PAR)
+    u32x4 (&Pnxt)[4] = PAR == 0 ? fs.pO : fs.pE;       // weights of tiles s-1 and s+1
+    const float nm = fs.nm;
+    float lc = 0.f, ln = 0.f;
+    bf16x8 fr[4];
+    typedef const __attribute__((address_space(3))) bf16x8 *lds_frag;
+    // LDS address of the A operand of slot j: even j = QK op j/2 (32-key half mb = op/8, k-step ks =
+    // op%8); odd j = PV op (j-1)/2 (16-key group kk = op/4, 32 d-values db = op%4)
+#define TC_OPADDR(j) ((((j) & 1) == 0) ? (kb ^ ((((j) >> 1) & 7) << 5)) + (((j) >> 4) * 32 * 256)             \
+                                      : vb + ((((j) >> 1) >> 2) * kHeadBlk + (((j) >> 1) & 3) * 1024))
+#define TC_OPLOAD(j) if ((((j) & 1) == 0) ? QK : PV) fr[(j) & 3] = *(lds_frag)(uintptr_t)(TC_OPADDR(j));
+    TC_OPLOAD(0) TC_OPLOAD(1) TC_OPLOAD(2)
+    // stream position x of this step: 0..15 -> S[2 PAR] (tile s, keys 32..63), 16..31 -> S[2 PAR + 1]
+    // (tile s+1, keys 0..31); negative: the previous step's positions 32 + x (tile s, keys 0..31)
+#define TC_SREG(x) fs.S[(x) >= 16 ? 2 * PAR + 1 : (x) >= 0 ? 2 * PAR : 3 - 2 * PAR][(x) & 15]
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        if (j + 3 < 32) TC_OPLOAD(j + 3)
+        // vector work, one stage for each of four different scores
+        {
+            const int xf = j - 2, xe = j - 3, xa = j - 4, xc = j - 5;
+            if (xf < 32) { float t = TC_SREG(xf); v_scale(t, c, nm); TC_SREG(xf) = t; }
+            if (xe < 32) { float t = TC_SREG(xe); v_exp2(t); TC_SREG(xe) = t; }
+            if (xa < 32) {
+                if (xa >= 16) v_acc(ln, TC_SREG(xa));
+                else v_acc(lc, TC_SREG(xa));
+            }
+            if (xc & 1) {
+                // pack scores xc-1, xc: element y of their tile -> dword y/2 of that tile's weights
+                const int y = xc >= 16 ? xc - 16 : 16 + xc;       // xc < 16: tile s (keys 0..31 if xc < 0)
+                const int d = (xc >= 16 || xc < 0) ? (y >> 1) : 8 + (xc >> 1);
+                uint32_t pk;
+                v_pack(pk, TC_SREG(xc - 1), TC_SREG(xc));
+                if (xc >= 16) Pnxt[d >> 2][d & 3] = pk;
+                else Pcur[d >> 2][d & 3] = pk;
+            }
+        }
+        if ((j & 1) == 0) {
+            if (QK) {
+                const int op = j >> 1, mb = op >> 3, ks = op & 7;
+                f32x16 &acc = fs.S[(2 * PAR + 1 + mb) & 3];
+                if (ks == 0) mfma_first(acc, fr[j & 3], qf[ks]);
+                else mfma_v(acc, fr[j & 3], qf[ks]);
+            }
+        } else {
+            if (PV) {
+                const int op = j >> 1, kk = op >> 2, db = op & 3;
+                mfma_a(o[db], fr[j & 3], Pnxt[kk]);
+            }
+        }
+        TC_SB();
+    }
+    // the stream's last stages (positions 27..31) run in the first slots of the next step
+    l_cur = lc;
+    l_nxt = ln;
+#undef TC_OPADDR
+#undef TC_OPLOAD
+#undef TC_SREG
+}
+
+// Runs the pipelined path over tiles [0, n) of the item's range (all full prefix tiles) and leaves
+// the row state as the general loop keeps it (reference in m_run).  Returns false (work-group
+// uniform) when a weight overflowed: the caller then redoes the item from scratch in the general loop.
+__device__ __forceinline__ bool fast_tiles(RowState<1> &st, const bf16x8 (&qf)[1][8], const Geom &g,
+                                           const AttnArgs &a, const AttnItem &it, char *lds,
+                                           const int32_t *s_bid, int n, int tid)
+{
+    const int lane = tid & 63, r32 = lane & 31, hh = lane >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const float c = a.scale_log2;
+    const char *pool_l = g.pool + (int64_t)a.layer * g.layer_stride + (int64_t)it.kvh * kHeadBlk;
+    const int64_t bb = g.block_bytes;
+    const uint32_t v_half = (uint32_t)(g.block_bytes >> 1);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
+
+    // ---- loads: wave w brings block w of a tile (16 keys): K as four 1 KB pieces of four rows each,
+    // chunk c of row r stored at chunk position c ^ r; V verbatim (4 KB per block and head)
+    // (the per-lane offsets are recomputed at every use rather than kept in registers across the steps)
+    const char *dummy = pool_l + (int64_t)it.bid[0] * bb;       // source of loads past the run: a valid block
+    auto issue_k = [&](int buf, int bid, bool real) {
+        const char *src = real ? pool_l + (int64_t)__builtin_amdgcn_readfirstlane(bid) * bb : dummy;
+        const uint32_t dst = lds0 + buf * kFastKTile + w * 4096;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int rb = 4 * i + (lane >> 4);
+            load_to_lds(dst + i * 1024, src, rb * 256 + (((lane & 15) ^ rb) * 16));
+        }
+    };
+    auto issue_v = [&](int buf, int bid, bool real) {
+        const char *src = (real ? pool_l + (int64_t)__builtin_amdgcn_readfirstlane(bid) * bb : dummy) + v_half;
+        const uint32_t dst = lds0 + kFastV + buf * kVTile + w * 4096;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) load_to_lds(dst + i * 1024, src + i * 1024, lane * 16);
+    };
+    // the item carries the block ids of its first four tiles
+    auto item_bid = [&](int t) {
+        const int b0 = it.bid[4 * t], b1 = it.bid[4 * t + 1], b2 = it.bid[4 * t + 2], b3 = it.bid[4 * t + 3];
+        return w == 0 ? b0 : w == 1 ? b1 : w == 2 ? b2 : b3;
+    };
+    issue_k(0, item_bid(0), true);
+    issue_k(1, item_bid(1), 1 < n);
+    issue_k(2, item_bid(2), 2 < n);
+    issue_v(0, item_bid(0), true);
+    issue_k(3, item_bid(3), 3 < n);
+    issue_v(1, item_bid(1), 1 < n);
+
+    // ---- operand read addresses (LDS byte addresses, 32 bit)
+    // chunk (2 ks + hh) ^ (r32 & 15) of row r32: the k-step only flips bits 5..7 of the byte address
+    uint32_t kb = lds0 + r32 * 256 + ((hh ^ (r32 & 15)) << 4);
+    uint32_t vb = lds0 + kFastV + r32 * 32 + hh * 16;
+
+    FastState fs;
+    fs.l = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { fs.pE[kk][e] = 0u; fs.pO[kk][e] = 0u; }
+
+    // ---- prime: QK(0) from K buffer 0; reference; weights of keys 0..31
+    asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+    __syncthreads();                                    // K(0) landed for every wave; block ids visible
+    {
+        typedef const __attribute__((address_space(3))) bf16x8 *lds_frag;
+        f32x16 z;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) z[e] = 0.f;
+        fs.S[3] = z;
+        fs.S[0] = z;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+            fs.S[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(lds_frag)(uintptr_t)(kb ^ (ks << 5)), qf[0][ks], fs.S[3], 0, 0, 0);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+            fs.S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(lds_frag)(uintptr_t)((kb ^ (ks << 5)) + 32 * 256), qf[0][ks], fs.S[0], 0, 0, 0);
+        float mx = fs.S[3][0];
+#pragma unroll
+        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fs.S[3][e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        st.m_run[0] = mx * c;
+        fs.nm = -st.m_run[0];
+        // weights of keys 0..31, left in the state the steps' stream expects at a step's start: the last
+        // five scores are in flight (27: summed, not packed; 28: exponentiated; 29: scaled; 30, 31: raw)
+#pragma unroll
+        for (int e = 0; e < 14; ++e) fs.S[3][e] = fmaf(fs.S[3][e], c, fs.nm);
+#pragma unroll
+        for (int e = 0; e < 13; ++e) fs.S[3][e] = __builtin_amdgcn_exp2f(fs.S[3][e]);
+#pragma unroll
+        for (int e = 0; e < 12; ++e) fs.l += fs.S[3][e];
+#pragma unroll
+        for (int d = 0; d < 5; ++d) {
+            uint32_t pk;
+            v_pack(pk, fs.S[3][2 * d], fs.S[3][2 * d + 1]);
+            fs.pE[d >> 2][d & 3] = pk;
+        }
+    }
+
+    // ---- steps.  Before step s: K reads go to buffer (s+1) & 3, V reads to buffer (s-1) & 3.
+    // boundary after step s (s = -1 for the prime step)
+    auto boundary = [&](int s, int bid_k, int bid_v) {
+        if (s + 2 < n) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");     // two younger batches may stay in flight
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (s + 3 < n) {
+            issue_k((s + 1) & 3, bid_k, s + 5 < n);
+            issue_v((s + 3) & 3, bid_v, true);
+        }
+    };
+    auto advance = [&](int s_next) {                    // read addresses for step s_next
+        const int dk = ((s_next + 1) & 3) == 0 ? -3 * kFastKTile : kFastKTile;
+        const int dv = ((s_next - 1) & 3) == 0 ? -3 * kVTile : kVTile;
+        kb += dk;
+        vb += dv;
+    };
+    // block ids for the loads of a boundary are fetched from LDS one step early
+    auto bid_of = [&](int t) { return s_bid[min(t, n - 1) * 4 + w]; };
+    {
+        const int bk = bid_of(4), bv = bid_of(2);
+        boundary(-1, bk, bv);
+    }
+    // step 0 reads K buffer 1 and (nothing from) V buffer 3
+    kb += kFastKTile;
+    vb += 3 * kVTile;
+    // step s with the matrix work that exists for it; then its boundary
+#define TC_STEP(PAR_, QK_, PV_, s_)                                                               \
+    {                                                                                             \
+        const int ss_ = (s_);                                                                     \
+        const int bk = bid_of(ss_ + 5), bv = bid_of(ss_ + 3);                                     \
+        float l_cur, l_nxt;                                                                       \
+        fast_step<PAR_, QK_, PV_>(fs, st.o[0], qf[0], kb, vb, c, l_cur, l_nxt);                   \
+        fs.l += (ss_ < n ? l_cur : 0.f) + (ss_ + 1 < n ? l_nxt : 0.f);                            \
+        if (ss_ < n) {                                                                            \
+            boundary(ss_, bk, bv);                                                                \
+            advance(ss_ + 1);                                                                     \
+        }                                                                                         \
+    }
+    TC_STEP(0, true, false, 0)                          // n >= 3: tile 1 exists
+    int s = 1;
+    for (; s + 1 <= n - 2; s += 2) {                    // steady state: steps 1 .. n-2
+        TC_STEP(1, true, true, s)
+        TC_STEP(0, true, true, s + 1)
+    }
+    if (s <= n - 2) {
+        TC_STEP(1, true, true, s)
+        TC_STEP(0, false, true, s + 1)                  // step n-1: no tile n
+        TC_STEP(1, false, true, s + 2)                  // step n: PV of the last tile
+    } else {
+        TC_STEP(1, false, true, s)
+        TC_STEP(0, false, true, s + 1)
+    }
+#undef TC_STEP
+    st.l_lane[0] = fs.l;
+    // a weight that overflowed shows in the sum (inf or nan)
+    const float l_row = fs.l + __shfl_xor(fs.l, 32);
+    return __syncthreads_or(!(l_row < 1e30f)) == 0;
+}
+
+// The kernel for one row block per wave: pipelined path over the leading run of full prefix tiles,
+// general loop for the rest (ragged last prefix tile, causal suffix tiles, short ranges).
+__global__ __launch_bounds__(256, 1) void attn_bf16_pipe_kernel(Geom g, BatchDev b, AttnArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    int32_t *s_bid = (int32_t *)(lds + kFastBid);
+
+    if ((int)blockIdx.x >= a.n_items) {                // extra work-groups: append the suffix to the pool
+        append_unit<true>(g, b, a.layer, (const char *)a.k_new, (const char *)a.v_new,
+                          blockIdx.x - a.n_items, threadIdx.x);
+        return;
+    }
+    const AttnItem it = a.items[blockIdx.x];
+    if (it.q < 0) return;                              // padding item (uniform for the work-group)
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    ItemRows<1> ir;
+    item_rows<1>(ir, g, it, w, lane & 31);
+    bf16x8 qf[1][8];
+    load_q<1>(qf, g, a, it, ir, lane >> 5);
+    RowState<1> st;
+    reset_rows<1>(st);
+    // leading full prefix tiles of the range
+    const int n_fast = min(it.tile_end, it.P >> 6) - it.tile_begin;
+    // (the XOR addressing of the K buffers needs the dynamic LDS segment 256-byte aligned)
+    if (n_fast >= kFastMinTiles && ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds & 255u) == 0) {
+        fill_bids(s_bid, b, it, tid);
+        const bool ok = fast_tiles(st, qf, g, a, it, lds, s_bid, n_fast, tid);
+        // Everything below is derived from a thread id the compiler cannot connect with the one
+        // above, so that none of it (row geometry, the general loop's per-thread offsets) is
+        // computed early and kept in registers across the pipelined path.
+        int tid2 = tid;
+        asm volatile("" : "+v"(tid2));
+        item_rows<1>(ir, g, it, tid2 >> 6, tid2 & 31);
+        if (ok) {
+            if (it.tile_begin + n_fast < it.tile_end)
+                tile_loop<1>(st, qf, g, b, a, it, ir, lds, s_bid, n_fast, false, tid2);
+        } else {
+            reset_rows<1>(st);
+            tile_loop<1>(st, qf, g, b, a, it, ir, lds, s_bid, 0, false, tid2);
+        }
+        store_rows<1>(st, g, a, it, ir, tid2 >> 6, tid2 & 63);
+    } else {
+        tile_loop<1>(st, qf, g, b, a, it, ir, lds, s_bid, 0, true, tid);
+        store_rows<1>(st, g, a, it, ir, w, lane);
     }
 }
 
@@ -452,7 +872,17 @@ hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a,
 {
     if (a.n_items + a.n_append == 0) return hipSuccess;
     if (g.D != 128 || g.esize != 2) return hipErrorInvalidValue;
-    if (row_blocks == 1) return launch_attn_rb<1>(g, b, a, L);
+    if (row_blocks == 1) {
+        static bool configured = false;
+        if (!configured) {
+            hipError_t e = hipFuncSetAttribute((const void *)attn_bf16_pipe_kernel,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesPipe);
+            if (e != hipSuccess) return e;
+            configured = true;
+        }
+        TC_LAUNCH(attn_bf16_pipe_kernel, a.n_items + a.n_append, kLdsBytesPipe, L, g, b, a);
+        return hipGetLastError();
+    }
     if (row_blocks == 2) return launch_attn_rb<2>(g, b, a, L);
     return hipErrorInvalidValue;
 }

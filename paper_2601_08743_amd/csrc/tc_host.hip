@@ -325,7 +325,7 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
                     it.q = i; it.kvh = h; it.m0 = mt * RT; it.tile_begin = t0; it.tile_end = t1;
                     it.split = s; it.n_splits = ns; it.group = n_groups + mt;
                     it.P = P; it.S = S; it.cu = p.cu_seqlens[i];
-                    for (int k = 0; k < 8; ++k)
+                    for (int k = 0; k < 16; ++k)
                         it.bid[k] = bt[std::min(t0 * (KT / kBlockTokens) + k, last_blk)];
                     bucket.push_back(it);
                 }

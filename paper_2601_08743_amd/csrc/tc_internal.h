@@ -69,9 +69,9 @@ struct AttnItem {
     int32_t group;       // index of the (query, KV head, row tile): partial slots and arrival counter
     int32_t P, S, cu;    // prefix length, suffix length, first suffix row of the query
     int32_t n_groups;    // total number of groups in the batch
-    int32_t bid[8];      // block ids of key tiles tile_begin and tile_begin+1 (clamped to the sequence)
+    int32_t bid[16];     // block ids of the first four key tiles of the range (clamped to the sequence)
 };
-static_assert(sizeof(AttnItem) == 80, "AttnItem layout");
+static_assert(sizeof(AttnItem) == 112, "AttnItem layout");
 
 // A (query, KV head, row tile) whose partitions the bf16 merge kernel combines.
 struct MergeGroup {
