@@ -200,6 +200,12 @@ tc_status tc_set_kv_splits(tc_ctx *ctx, int32_t n_splits);
  * blocks of 32 rows and reuses every K/V fragment twice), 0 = automatic (256 when the batch still
  * yields enough work-groups to fill the chip).  Results do not depend on it beyond rounding. */
 tc_status tc_set_row_blocks(tc_ctx *ctx, int32_t row_blocks);
+/* Which bf16 attention kernel serves work-groups of 128 rows: 0 = automatic (from the number and
+ * length of the batch's work items), 1 = the general kernel (register-staged K/V, running-maximum
+ * softmax, two work-groups per CU), 2 = the pipelined kernel (direct-to-LDS K/V, fixed softmax
+ * reference with overflow fallback, one work-group per CU).  Results do not depend on it beyond
+ * rounding.  Invalidates the cached plan. */
+tc_status tc_set_attn_kernel(tc_ctx *ctx, int32_t kind);
 
 /*
  * Measurement support.  With profiling on, every kernel the library launches carries two HIP

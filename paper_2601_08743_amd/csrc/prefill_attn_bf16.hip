@@ -477,7 +477,7 @@ __device__ __forceinline__ void load_to_lds(uint32_t lds_dst, const char *base, 
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b64), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b64 >> 32));
     const uint64_t sb = ((uint64_t)hi << 32) | lo;
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(__builtin_amdgcn_readfirstlane(lds_dst)), "v"(voff), "s"(sb) : "memory", "m0");
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_dst)), "v"(voff), "s"(sb) : "memory");
 }
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -598,8 +598,8 @@ __device__ __forceinline__ void fast_step(FastState &fs, f32x16 (&o)[4], const b
 // the row state as the general loop keeps it (reference in m_run).  Returns false (work-group
 // uniform) when a weight overflowed: the caller then redoes the item from scratch in the general loop.
 __device__ __forceinline__ bool fast_tiles(RowState<1> &st, const bf16x8 (&qf)[1][8], const Geom &g,
-                                           const AttnArgs &a, const AttnItem &it, char *lds,
-                                           const int32_t *s_bid, int n, int tid)
+                                           const BatchDev &b, const AttnArgs &a, const AttnItem &it, char *lds,
+                                           int32_t *s_bid, int n, int tid)
 {
     const int lane = tid & 63, r32 = lane & 31, hh = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -639,6 +639,9 @@ __device__ __forceinline__ bool fast_tiles(RowState<1> &st, const bf16x8 (&qf)[1
     issue_v(0, item_bid(0), true);
     issue_k(3, item_bid(3), 3 < n);
     issue_v(1, item_bid(1), 1 < n);
+    // the block-id table is filled behind these loads, so that its round trip to the block table
+    // does not delay them (the barrier of the prime step publishes it)
+    fill_bids(s_bid, b, it, tid);
 
     // ---- operand read addresses (LDS byte addresses, 32 bit)
     // chunk (2 ks + hh) ^ (r32 & 15) of row r32: the k-step only flips bits 5..7 of the byte address
@@ -744,6 +747,7 @@ __device__ __forceinline__ bool fast_tiles(RowState<1> &st, const bf16x8 (&qf)[1
         TC_STEP(0, false, true, s + 1)
     }
 #undef TC_STEP
+    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");   // O's last matrix instruction completes before O is read
     st.l_lane[0] = fs.l;
     // a weight that overflowed shows in the sum (inf or nan)
     const float l_row = fs.l + __shfl_xor(fs.l, 32);
@@ -775,8 +779,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_pipe_kernel(Geom g, BatchDev
     const int n_fast = min(it.tile_end, it.P >> 6) - it.tile_begin;
     // (the XOR addressing of the K buffers needs the dynamic LDS segment 256-byte aligned)
     if (n_fast >= kFastMinTiles && ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds & 255u) == 0) {
-        fill_bids(s_bid, b, it, tid);
-        const bool ok = fast_tiles(st, qf, g, a, it, lds, s_bid, n_fast, tid);
+        const bool ok = fast_tiles(st, qf, g, b, a, it, lds, s_bid, n_fast, tid);
         // Everything below is derived from a thread id the compiler cannot connect with the one
         // above, so that none of it (row geometry, the general loop's per-thread offsets) is
         // computed early and kept in registers across the pipelined path.
@@ -868,11 +871,12 @@ static hipError_t launch_attn_rb(const Geom &g, const BatchDev &b, const AttnArg
     return hipGetLastError();
 }
 
-hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, int row_blocks, const Launch &L)
+hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, int row_blocks, bool pipelined,
+                            const Launch &L)
 {
     if (a.n_items + a.n_append == 0) return hipSuccess;
     if (g.D != 128 || g.esize != 2) return hipErrorInvalidValue;
-    if (row_blocks == 1) {
+    if (row_blocks == 1 && pipelined) {
         static bool configured = false;
         if (!configured) {
             hipError_t e = hipFuncSetAttribute((const void *)attn_bf16_pipe_kernel,
@@ -883,6 +887,7 @@ hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a,
         TC_LAUNCH(attn_bf16_pipe_kernel, a.n_items + a.n_append, kLdsBytesPipe, L, g, b, a);
         return hipGetLastError();
     }
+    if (row_blocks == 1) return launch_attn_rb<1>(g, b, a, L);
     if (row_blocks == 2) return launch_attn_rb<2>(g, b, a, L);
     return hipErrorInvalidValue;
 }

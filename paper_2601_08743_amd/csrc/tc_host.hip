@@ -103,6 +103,7 @@ struct Slot {
 struct Plan {
     bool valid = false;
     int32_t B = 0, max_blocks = 0, total_S = 0, n_stitch_blk = 0, n_items = 0, max_splits = 1, n_groups = 0, row_blocks = 1;
+    bool pipelined = false;     // bf16, one row block per wave: the pipelined attention kernel
     std::vector<int32_t> block_table, cu_seqlens, prefix_len, suffix_len;
     BatchDev dev{};
     const AttnItem *items_dev = nullptr;
@@ -134,6 +135,7 @@ struct tc_ctx {
     float *d_part = nullptr; size_t d_part_floats = 0;
     int32_t forced_splits = 0;
     int32_t forced_row_blocks = 0;
+    int32_t forced_attn_kernel = 0;   // 0 automatic, 1 general, 2 pipelined
     // per-kernel timing (tc_profile_*): pairs of events around launches, drained on read
     bool profiling = false;
     struct Timed { int kind; hipEvent_t a, b; };
@@ -359,6 +361,19 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
             else { AttnItem pad{}; pad.q = -1; pad.n_splits = 1; items.push_back(pad); }
     while (!items.empty() && items.back().q < 0) items.pop_back();
     p.n_items = (int32_t)items.size();
+    // Which bf16 kernel (one row block per wave).  The pipelined one holds 132 KB of LDS, so one
+    // work-group per CU: nothing hides a work-group's start-up and drain.  It wins when a launch is a
+    // single round of work-groups or when they are long; many short ones (measured: 1140 work-groups
+    // of ~20 key tiles, 743 vs 647 TFLOP/s) are better off two per CU in the general kernel.
+    int64_t n_real = 0, fast_tiles = 0;
+    for (const AttnItem &it : items)
+        if (it.q >= 0) {
+            ++n_real;
+            fast_tiles += std::max(std::min(it.tile_end, it.P >> 6) - it.tile_begin, 0);
+        }
+    p.pipelined = bf16 && rb == 1 && n_real > 0 &&
+                  (ctx->forced_attn_kernel ? ctx->forced_attn_kernel == 2
+                                           : (n_real <= 2 * 256 || fast_tiles >= 48 * n_real));
 }
 
 // Serialise the plan into the staging buffer and enqueue its upload on `stream`.
@@ -787,7 +802,7 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
               : bf16 ? ctx->d_part + (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * 64
                      : ctx->d_part + (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * ctx->cfg.head_dim;
     TC_HIP(ctx, timed_launch(ctx, 2, stream, [&](const Launch &ln) {
-        return bf16 ? launch_attn_bf16(ctx->geom, p.dev, a, p.row_blocks, ln)
+        return bf16 ? launch_attn_bf16(ctx->geom, p.dev, a, p.row_blocks, p.pipelined, ln)
                     : launch_attn_f32(ctx->geom, p.dev, a, ln);
     }));
     if (p.max_splits > 1)
@@ -879,6 +894,14 @@ tc_status tc_set_kv_splits(tc_ctx *ctx, int32_t n_splits)
 {
     if (!ctx || n_splits < 0) return TC_ERR_INVALID;
     ctx->forced_splits = n_splits;
+    ctx->plan.valid = false;
+    return TC_OK;
+}
+
+tc_status tc_set_attn_kernel(tc_ctx *ctx, int32_t kind)
+{
+    if (!ctx || kind < 0 || kind > 2) return TC_ERR_INVALID;
+    ctx->forced_attn_kernel = kind;
     ctx->plan.valid = false;
     return TC_OK;
 }

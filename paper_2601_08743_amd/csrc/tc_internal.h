@@ -108,7 +108,8 @@ hipError_t launch_append(const Geom &g, const BatchDev &b, int layer, const void
 hipError_t launch_readback(const Geom &g, int layer, const int32_t *blocks_dev, int n_tokens,
                            void *k_out_dev, void *v_out_dev, hipStream_t s);
 // prefill_attn_bf16.hip / prefill_attn_f32.hip
-hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, int row_blocks, const Launch &L);
+hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, int row_blocks, bool pipelined,
+                            const Launch &L);
 hipError_t launch_attn_f32(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L);
 hipError_t launch_merge(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L);
 hipError_t launch_merge_bf16(const Geom &g, const AttnArgs &a, const MergeGroup *groups, int n_groups,

@@ -1,0 +1,200 @@
+"""GPU parity of the two bf16 attention kernels (general and pipelined) against the CPU checker:
+same workloads through both, run lengths that exercise every start-up / tail variant of the
+pipelined path, and score distributions that stress its fixed softmax reference (including the
+overflow that sends an item back to the running-maximum loop)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_08743_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2          # bf16 operands, fp32 accumulation: max-abs, as for the other bf16 parity tests
+
+
+@pytest.fixture(scope="module")
+def H():
+    import harness
+    assert torch.cuda.is_available()
+    return harness
+
+
+def _errs(H, dw, bt, pl, layer):
+    out, qkv = dw.attn_layer(layer, bt, pl)
+    ref = H.oracle_attn_layer(dw.wl, dw.tables_np, layer, qkv)
+    got = H.out_to_f64(out, dw.cfg)
+    res = {}
+    for i, r in ref.items():
+        sl = slice(int(dw.wl.cu_seqlens[i]), int(dw.wl.cu_seqlens[i + 1]))
+        assert np.isfinite(got[sl]).all(), "query %d: non-finite output" % i
+        res[i] = (float(np.abs(got[sl] - r).max()), float(np.abs(r).max()))
+    return res, out, qkv
+
+
+@pytest.mark.parametrize("kind", [1, 2])
+@pytest.mark.parametrize("splits", [1, 3, 8])
+def test_both_kernels_c2_shape(H, kind, splits):
+    """The c2 shape (P ~ 4.1k, S = 128, ragged last prefix tile, two causal suffix tiles) through
+    either kernel, unsplit and split."""
+    wl = W.make_workload(W.scaled(W.CONFIGS["c2"], n_layers=1))
+    used = sorted(set(wl.table_ids.tolist()))
+    dw = H.DeviceWorkload(wl, capacity=len(used), tables=used)
+    dw.ctx.tc_set_attn_kernel(kind)
+    dw.ctx.tc_set_kv_splits(splits)
+    bt, pl = dw.stitch()
+    res, _, _ = _errs(H, dw, bt, pl, 0)
+    err = max(e for e, _ in res.values())
+    print("kernel %d, %d partitions: max-abs %.3e" % (kind, splits, err))
+    assert err <= TOL
+    dw.close()
+
+
+def _one_table_per_query(prefix_lens, suffix_lens, seed, n_layers=1):
+    """A workload whose query i has exactly prefix_lens[i] schema tokens (one table each)."""
+    base = W.CONFIGS["c2"]
+    cfg = W.scaled(base, name="runs", n_layers=n_layers, n_tables=len(prefix_lens), batch=len(prefix_lens),
+                   tables_per_query=(1, 1), capacity=len(prefix_lens), seed=seed)
+    return W.Workload(cfg, np.asarray(prefix_lens, dtype=np.int32),
+                      [np.asarray([i], dtype=np.int32) for i in range(len(prefix_lens))],
+                      np.asarray(suffix_lens, dtype=np.int32))
+
+
+def test_pipelined_run_lengths(H):
+    """Unsplit queries whose prefixes hold 1 .. 13 full key tiles, with and without a ragged tile
+    behind them: the pipelined path's first step, steady pairs and both tail parities, the hand-over
+    to the general loop, and runs too short for it.  Both kernels must agree with the checker and
+    (closely) with each other."""
+    P = [65, 128, 192, 200, 256, 320, 391, 448, 512, 600, 704, 777, 832]
+    S = [16, 33, 5, 64, 19, 128, 1, 40, 18, 77, 20, 64, 31]
+    wl = _one_table_per_query(P, S, seed=4242)
+    outs = {}
+    for kind in (1, 2):
+        dw = H.DeviceWorkload(wl)
+        dw.ctx.tc_set_attn_kernel(kind)
+        dw.ctx.tc_set_kv_splits(1)
+        bt, pl = dw.stitch()
+        np.testing.assert_array_equal(pl, P)
+        res, out, _ = _errs(H, dw, bt, pl, 0)
+        for i, (e, _) in res.items():
+            print("kernel %d, P %4d S %3d: max-abs %.3e" % (kind, P[i], S[i], e))
+            assert e <= TOL, (kind, P[i], S[i])
+        outs[kind] = H.out_to_f64(out, dw.cfg)
+        dw.close()
+    assert np.abs(outs[1] - outs[2]).max() <= TOL
+
+
+class _SteeredScores(W.Workload):
+    """Keys whose scores follow a prescribed profile along the prefix: every query row is positive,
+    key t is `level[t]` times a positive vector, so score(row, t) grows with level[t] for all rows."""
+
+    def __init__(self, cfg, table_len, queries, suffix_len, level):
+        super().__init__(cfg, table_len, queries, suffix_len)
+        self._level = level
+
+    def table_kv(self, t):
+        k, v = super().table_kv(t)
+        c = self.cfg
+        kf = np.abs(W.bf16_bits_to_f32(k)) * 0.25 + 0.25               # positive, O(0.5)
+        kf *= self._level[t][None, :, None, None]
+        return W.f32_to_bf16_bits(kf.astype(np.float32)), v
+
+    def suffix_qkv(self, layer):
+        q, k, v = super().suffix_qkv(layer)
+        qf = np.abs(W.bf16_bits_to_f32(q)) + 0.5
+        return W.f32_to_bf16_bits(qf.astype(np.float32)), k, v
+
+
+@pytest.mark.parametrize("profile", ["rising_mild", "rising_overflow", "falling", "spike_late"])
+def test_fixed_reference_extremes(H, profile):
+    """The pipelined path measures every score against the maximum of the first 32 keys of a run.
+    Profiles: scores that rise along the prefix by ~60 (weights up to 2^60 relative to the reference:
+    still exact arithmetic), by ~300 (weights overflow: the item must be redone with a running
+    maximum), that fall by ~300 (all later weights underflow to zero, as they should), and a single
+    huge key late in the prefix.  The checker works in fp64 with the true maximum.
+
+    Tolerance.  In these profiles a handful of keys carry all the weight, so nothing averages out:
+    the weights enter the PV product rounded to bf16 (relative error <= 2^-9 each, so at most
+    2^-9 max|v| on the output) and the output itself is rounded to bf16 (<= 2^-8 |out|).  The
+    general kernel does a little better than that bound because its reference is the running
+    maximum, which makes the largest weight exactly 1; with a fixed reference no weight is special."""
+    n_tok = 640
+    t = np.arange(n_tok, dtype=np.float64)
+    # q . k ~ 128 * 0.9 * 0.5 * level ~ 58 * level; times scale (0.088) and log2(e): ~7.4 * level log2 units
+    if profile == "rising_mild":
+        level = 0.05 + 8.0 * t / n_tok
+    elif profile == "rising_overflow":
+        level = 0.05 + 40.0 * t / n_tok
+    elif profile == "falling":
+        level = 40.0 * (1.0 - t / n_tok) + 0.01
+    else:
+        level = np.full(n_tok, 0.05)
+        level[500] = 45.0
+    cfg = W.scaled(W.CONFIGS["c2"], name="steer", n_layers=1, n_tables=1, batch=1, tables_per_query=(1, 1),
+                   capacity=1, seed=777)
+    wl = _SteeredScores(cfg, np.asarray([n_tok], dtype=np.int32), [np.asarray([0], dtype=np.int32)],
+                        np.asarray([48], dtype=np.int32), {0: level.astype(np.float32)})
+    bad = []
+    for kind, splits in ((2, 1), (2, 2), (1, 1)):
+        dw = H.DeviceWorkload(wl)
+        dw.ctx.tc_set_attn_kernel(kind)
+        dw.ctx.tc_set_kv_splits(splits)
+        bt, pl = dw.stitch()
+        res, _, qkv = _errs(H, dw, bt, pl, 0)
+        e, _ = res[0]
+        vmax = max(float(np.abs(W.bf16_bits_to_f32(dw.tables_np[0][1])).max()),
+                   float(np.abs(W.bf16_bits_to_f32(qkv[2])).max()))
+        tol = max(TOL, 3.0 * 2.0 ** -9 * vmax)
+        print("%s, kernel %d, %d partitions: max-abs %.3e (max |v| %.2f, tolerance %.3e)" % (profile, kind, splits, e, vmax, tol))
+        if not e <= tol:
+            bad.append((profile, kind, splits, e))
+        dw.close()
+    assert not bad, bad
+
+
+class _CountingValues(W.Workload):
+    """All scores equal (K = 0 everywhere) and the value of sequence position t is the unit vector
+    e_(t mod 128): row r of the output then holds, in column d, the number of visible positions
+    congruent to d divided by the number of visible positions.  Every weight is exactly 1 in any
+    arithmetic, so a key that is dropped, doubled, or attributed to the wrong value row shows up as
+    a whole count, whatever the kernel's rounding."""
+
+    def table_kv(self, t):
+        c = self.cfg
+        n = int(self.table_len[t])
+        k = np.zeros((c.n_layers, n, c.n_kv_heads, c.head_dim), dtype=np.float32)
+        v = np.zeros_like(k)
+        v[:, np.arange(n), :, np.arange(n) % c.head_dim] = 1.0
+        return W.f32_to_bf16_bits(k), W.f32_to_bf16_bits(v)
+
+    def suffix_qkv(self, layer):
+        c = self.cfg
+        q, k, v = super().suffix_qkv(layer)
+        P, S = int(self.table_len[0]), int(self.suffix_len[0])
+        vf = np.zeros(v.shape, dtype=np.float32)
+        vf[np.arange(S), :, (P + np.arange(S)) % c.head_dim] = 1.0
+        return q, W.f32_to_bf16_bits(np.zeros(k.shape, dtype=np.float32)), W.f32_to_bf16_bits(vf)
+
+
+@pytest.mark.parametrize("P,S,splits", [(640, 48, 1), (4086, 128, 8), (4086, 128, 1), (200, 20, 1), (832, 31, 2),
+                                        (1283, 77, 3)])
+def test_every_key_counted_once(H, P, S, splits):
+    cfg = W.scaled(W.CONFIGS["c2"], name="count", n_layers=1, n_tables=1, batch=1, tables_per_query=(1, 1),
+                   capacity=1, seed=5)
+    wl = _CountingValues(cfg, np.asarray([P], dtype=np.int32), [np.asarray([0], dtype=np.int32)],
+                         np.asarray([S], dtype=np.int32))
+    n_vis = P + np.arange(S) + 1
+    want = np.stack([np.bincount(np.arange(n) % 128, minlength=128) for n in n_vis]).astype(np.float64)   # [S][128]
+    for kind in (1, 2):
+        dw = H.DeviceWorkload(wl)
+        dw.ctx.tc_set_attn_kernel(kind)
+        dw.ctx.tc_set_kv_splits(splits)
+        bt, pl = dw.stitch()
+        out, _ = dw.attn_layer(0, bt, pl)
+        got = H.out_to_f64(out, dw.cfg) * n_vis[:, None, None]          # counts, up to the output's bf16 rounding
+        dev = float(np.abs(got - want[:, None, :]).max())
+        print("P %d S %d, %d partitions, kernel %d: largest count error %.3f (counts up to %d)" %
+              (P, S, splits, kind, dev, int(want.max())))
+        assert dev < 0.5 * max(1.0, want.max() * 2.0 ** -7)      # a whole count cannot hide in the output rounding
+        assert dev <= want.max() * 2.0 ** -8 + 1e-6               # and what is left is that rounding
+        dw.close()
