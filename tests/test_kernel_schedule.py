@@ -1,0 +1,113 @@
+"""Static check of the pipelined attention kernel's machine code (no GPU needed).
+
+The pipelined steps issue their matrix and vector instructions through inline assembly, so the
+compiler's hazard recogniser does not see them.  On gfx950 the result of a 32x32x16 matrix
+instruction (8 passes) must not be read by a vector instruction, nor copied out of an accumulation
+register, for 11 wait states after issue, and the hardware does not interlock this.  The source
+keeps every such pair three or more slots apart; this test compiles the kernel to assembly and
+verifies it on what the compiler actually emitted: between a matrix instruction and the first
+non-matrix instruction that reads (or overwrites) any register of its result there are at least
+`MIN_GAP` issued instructions (an `s_nop n` counts n + 1)."""
+import os
+import re
+import subprocess
+import tempfile
+
+import pytest
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+SRC = os.path.join(ROOT, "paper_2601_08743_amd", "csrc", "prefill_attn_bf16.hip")
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+MIN_GAP = 12
+KERNEL = "attn_bf16_pipe_kernel"
+
+_REG = re.compile(r"\b([va])\[(\d+):(\d+)\]|\b([va])(\d+)\b")
+
+
+def _regs(text):
+    """Set of (file, index) registers named in an operand string."""
+    out = set()
+    for m in _REG.finditer(text):
+        if m.group(1):
+            out.update((m.group(1), i) for i in range(int(m.group(2)), int(m.group(3)) + 1))
+        else:
+            out.add((m.group(4), int(m.group(5))))
+    return out
+
+
+def _kernel_instructions(asm_text):
+    lines = asm_text.splitlines()
+    start = next(i for i, l in enumerate(lines) if re.match(r"^_ZN2tc\d+%s\w*:" % KERNEL, l))
+    end = next(i for i in range(start, len(lines)) if lines[i].startswith(".Lfunc_end"))
+    ins = []
+    for l in lines[start + 1:end]:
+        l = l.split(";")[0].strip()
+        if not l or l.endswith(":") or l.startswith("."):
+            continue
+        op, _, rest = l.partition(" ")
+        ins.append((op, rest.strip()))
+    return ins
+
+
+@pytest.fixture(scope="module")
+def instructions():
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not available")
+    with tempfile.TemporaryDirectory() as d:
+        out = os.path.join(d, "k.s")
+        cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+               "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", os.path.dirname(SRC),
+               "-S", "--cuda-device-only", SRC, "-o", out]
+        subprocess.check_call(cmd, stderr=subprocess.DEVNULL)
+        return _kernel_instructions(open(out).read())
+
+
+def test_matrix_results_are_not_read_too_early(instructions):
+    n_mfma, tightest = 0, None
+    for i, (op, rest) in enumerate(instructions):
+        if not op.startswith("v_mfma"):
+            continue
+        n_mfma += 1
+        dst = _regs(rest.split(",")[0])
+        gap = 0
+        for op2, rest2 in instructions[i + 1:i + 1 + 4 * MIN_GAP]:
+            if op2.startswith("v_mfma"):
+                gap += 1            # accumulating into the same registers is forwarded by the hardware
+                continue
+            if op2 == "s_nop":
+                gap += int(rest2) + 1
+                continue
+            if op2.startswith("s_cbranch") or op2 in ("s_branch", "s_endpgm", "s_barrier"):
+                break               # a barrier or the end of the block: far more than MIN_GAP cycles away
+            if _regs(rest2) & dst:
+                assert gap >= MIN_GAP, "instruction %d (%s %s): result touched by '%s %s' after %d wait states" % (
+                    i, op, rest, op2, rest2, gap)
+                tightest = gap if tightest is None else min(tightest, gap)
+                break
+            gap += 1
+            if gap >= MIN_GAP:
+                break
+    assert n_mfma >= 32 * 5, "the pipelined steps were not found in the kernel"
+    print("matrix instructions checked: %d, tightest gap seen: %s" % (n_mfma, tightest))
+
+
+def test_pipelined_steps_keep_their_slot_structure(instructions):
+    """In the two steady-state step bodies (one per parity) every matrix instruction is followed
+    by the vector work of exactly one score before the next one: 31 gaps per body with exactly one
+    `v_exp_f32` (the hand-placed one; the compiler's own are spelled v_exp_f32_e32).  This guards
+    against the slots collapsing into blocks of matrix instructions, which would still compute the
+    right thing but lose the overlap the schedule exists for."""
+    gaps, cur, seen_mfma = [], 0, False
+    for op, _ in instructions:
+        if op.startswith("v_mfma"):
+            if seen_mfma:
+                gaps.append(cur)
+            cur, seen_mfma = 0, True
+        elif op == "v_exp_f32":
+            cur += 1
+        elif op == "s_barrier":
+            seen_mfma = False
+    one = sum(1 for g in gaps if g == 1)
+    print("gaps between matrix instructions holding exactly one hand-placed exp: %d" % one)
+    assert one >= 2 * 31
