@@ -296,6 +296,7 @@ def main():
     n_splits = None
     bt, pl = ctx.tc_stitch_kv(ids, cu_t, sl, max_blocks, stream)
     n_splits = ctx.tc_kv_splits()
+    kernel_name = {0: "attn_%s_kernel" % c.dtype, 1: "attn_bf16_kernel<1>", 2: "attn_bf16_pipe_kernel"}[ctx.tc_attn_kernel()]
 
     flops_layer = attn_flops_per_layer(c, P, S)
     flops_step = flops_layer * c.n_layers
@@ -377,7 +378,7 @@ def main():
         "stitch_frac_hbm": round(stitch_bytes / (stitch_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4),
         "roofline": {"bound": "mfma" if c.dtype == "bf16" else "alu", "achieved": round(attn_tflops_kernel, 2),
                      "peak": peak, "unit": "TFLOP/s", "frac": round(attn_tflops_kernel / peak, 4),
-                     "traffic": read_traffic(c.name), "kernel": "attn_%s_kernel" % c.dtype},
+                     "traffic": read_traffic(c.name), "kernel": kernel_name},
         "cpu_baseline": cpu, "parity_max_abs_vs_oracle": parity, "setup_s": round(setup_s, 1),
     }
     res.update(extra)

@@ -204,8 +204,10 @@ tc_status tc_set_row_blocks(tc_ctx *ctx, int32_t row_blocks);
  * length of the batch's work items), 1 = the general kernel (register-staged K/V, running-maximum
  * softmax, two work-groups per CU), 2 = the pipelined kernel (direct-to-LDS K/V, fixed softmax
  * reference with overflow fallback, one work-group per CU).  Results do not depend on it beyond
- * rounding.  Invalidates the cached plan. */
+ * rounding.  Invalidates the cached plan.  tc_attn_kernel reports the kernel of the current plan
+ * (1 or 2; 0 when no plan is cached, for fp32 contexts and for 256-row work-groups). */
 tc_status tc_set_attn_kernel(tc_ctx *ctx, int32_t kind);
+int32_t tc_attn_kernel(const tc_ctx *ctx);
 
 /*
  * Measurement support.  With profiling on, every kernel the library launches carries two HIP

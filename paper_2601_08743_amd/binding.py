@@ -33,7 +33,7 @@ TC_POLICY_LRU, TC_POLICY_FIFO, TC_POLICY_LFU = 0, 1, 2
 EXPORTS = ["tc_block_bytes", "tc_pool_bytes", "tc_first_seq_block", "tc_create", "tc_destroy",
            "tc_register_table_kv", "tc_load_async", "tc_load_trace", "tc_is_resident",
            "tc_stitch_kv", "tc_prefill_attn", "tc_release_seqs", "tc_read_seq_kv",
-           "tc_kv_splits", "tc_set_kv_splits", "tc_set_row_blocks", "tc_set_attn_kernel", "tc_profile_enable", "tc_profile_read", "tc_last_error", "tc_version"]
+           "tc_kv_splits", "tc_set_kv_splits", "tc_set_row_blocks", "tc_set_attn_kernel", "tc_attn_kernel", "tc_profile_enable", "tc_profile_read", "tc_last_error", "tc_version"]
 
 
 class tc_config(ctypes.Structure):
@@ -66,6 +66,7 @@ _sig = {
     "tc_set_kv_splits": (_i32, [_vp, _i32]),
     "tc_set_row_blocks": (_i32, [_vp, _i32]),
     "tc_set_attn_kernel": (_i32, [_vp, _i32]),
+    "tc_attn_kernel": (_i32, [_vp]),
     "tc_profile_enable": (_i32, [_vp, _i32]),
     "tc_profile_read": (_i32, [_vp, _vp, _vp]),
     "tc_last_error": (ctypes.c_char_p, [_vp]),
@@ -216,6 +217,9 @@ class Context:
 
     def tc_set_row_blocks(self, n: int):
         self._check(_lib.tc_set_row_blocks(self._h, n))
+
+    def tc_attn_kernel(self) -> int:
+        return int(_lib.tc_attn_kernel(self._h))
 
     def tc_set_attn_kernel(self, kind: int):
         self._check(_lib.tc_set_attn_kernel(self._h, kind))

@@ -370,10 +370,16 @@ __device__ __forceinline__ void store_rows(const RowState<RB> &st, const Geom &g
                     f16x4 v;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = (_Float16)(st.o[rb][db][4 * q4 + e] * inv);
-                    po[(db * 4 + q4) * 64] = v;
+                    __builtin_nontemporal_store(v, &po[(db * 4 + q4) * 64]);
                 }
             if (hh == 0)
-                ((float2 *)a.part_ml)[(slot * (4 * RB) + blk) * 32 + r32] = make_float2(st.m_run[rb], l);
+            {
+                typedef float f32x2 __attribute__((ext_vector_type(2)));
+                f32x2 ml;
+                ml[0] = st.m_run[rb];
+                ml[1] = l;
+                __builtin_nontemporal_store(ml, &((f32x2 *)a.part_ml)[(slot * (4 * RB) + blk) * 32 + r32]);
+            }
             continue;
         }
         if (!ir.valid[rb]) continue;

@@ -300,12 +300,12 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
         splits_of_q[i] = ns;
         p.max_splits = std::max(p.max_splits, ns);
         const int n_mt = (S * G + RT - 1) / RT;
-        // Partition boundaries.  A suffix tile of the bf16 kernel costs about 3 prefix tiles (its V
+        // Partition boundaries.  A suffix tile of the bf16 kernel costs about 4 prefix tiles (its V
         // is transposed on the way into LDS), so the tiles are cut by weight, not by count.
         std::vector<int> cut(ns + 1, 0);
         {
             const int npt = bf16 ? (P + KT - 1) / KT : n_tiles;
-            const int w_new = 3;
+            const int w_new = 4;
             const int64_t total_w = npt + (int64_t)(n_tiles - npt) * w_new;
             int t = 0;
             int64_t acc = 0;
@@ -896,6 +896,12 @@ tc_status tc_set_kv_splits(tc_ctx *ctx, int32_t n_splits)
     ctx->forced_splits = n_splits;
     ctx->plan.valid = false;
     return TC_OK;
+}
+
+int32_t tc_attn_kernel(const tc_ctx *ctx)
+{
+    if (!ctx || !ctx->plan.valid || ctx->cfg.dtype != TC_BF16 || ctx->plan.row_blocks != 1) return 0;
+    return ctx->plan.pipelined ? 2 : 1;
 }
 
 tc_status tc_set_attn_kernel(tc_ctx *ctx, int32_t kind)
