@@ -57,6 +57,9 @@ def _load():
         lib.orc_prefill_attn.restype = ctypes.c_int
         lib.orc_prefill_attn.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_int32] * 5 + \
             [ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p]
+        lib.orc_reencode_keys.restype = ctypes.c_int
+        lib.orc_reencode_keys.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                          ctypes.c_void_p, ctypes.c_double]
         _lib = lib
     return _lib
 
@@ -91,6 +94,21 @@ def stitch(tables: Dict[int, np.ndarray], ids: Sequence[int]) -> np.ndarray:
         n = lib.orc_concat_tokens(ptrs, n_tok.ctypes.data, len(ids), row_bytes,
                                   out[l].ctypes.data if P else None)
         assert n == P
+    return out
+
+
+def reencode_keys(k: np.ndarray, positions: Sequence[int], theta: float) -> np.ndarray:
+    """Rotary re-encoding of position-free keys (Sec. 4.1.1): k is [n][H][D] (any float
+    type, widened exactly to fp64), positions[t] the global position of token t in the
+    concatenated sequence.  Returns the encoded keys, fp64."""
+    lib = _load()
+    out = np.array(k, dtype=np.float64, order="C", copy=True)
+    pos = np.ascontiguousarray(positions, dtype=np.int64)
+    n, H, D = out.shape
+    assert pos.shape == (n,)
+    rc = lib.orc_reencode_keys(out.ctypes.data, n, H, D, pos.ctypes.data, float(theta))
+    if rc != 0:
+        raise ValueError("orc_reencode_keys: bad arguments")
     return out
 
 

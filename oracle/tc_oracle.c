@@ -12,11 +12,16 @@
  *   orc_concat_tokens   - the stitched sequence: table segments laid end to end
  *   orc_prefill_attn    - softmax attention of the suffix rows over
  *                         {all stitched schema keys} U {suffix keys 0..r}
+ *   orc_reencode_keys   - Sec. 4.1.1, last paragraph: table keys are stored without
+ *                         positional encoding and get it at inference from their global
+ *                         position in the concatenated sequence (rotary encoding)
  *
  * Parity pins (tests/test_oracle_*.py): rows P..P+S-1 of a library causal
  * attention over the whole sequence; softmax rows summing to one; brute-force
  * enumeration of the visible-key set; closed forms (equal keys, constant V,
- * one dominating logit); GQA reductions; position-coded gather.
+ * one dominating logit); GQA reductions; position-coded gather; the rotary
+ * re-encoding against complex multiplication, its group properties and the
+ * relative-position invariance of rotated dot products.
  */
 #include <math.h>
 #include <stdint.h>
@@ -117,4 +122,33 @@ int orc_prefill_attn(const double *q, const double *k_seq, const double *v_seq,
             free(s);
         }
     return failed ? -2 : 0;
+}
+
+/*
+ * Positional re-encoding of stitched keys (Sec. 4.1.1: keys are stored position-free;
+ * at inference every token is encoded by its global position in the concatenation).
+ * The paper names no encoding; its models are rotary-position decoders, so this is the
+ * rotary encoding in the half-split convention of those models: with D the head size,
+ * frequency w_i = theta^(-2i/D) for i < D/2, and a = pos * w_i,
+ *     k'[i]       = k[i] cos a - k[i + D/2] sin a
+ *     k'[i + D/2] = k[i + D/2] cos a + k[i] sin a
+ * k is [n_tokens][n_heads][D] fp64, rotated in place; pos[t] is token t's position.
+ */
+int orc_reencode_keys(double *k, int64_t n_tokens, int32_t n_heads, int32_t D, const int64_t *pos, double theta)
+{
+    if (D <= 0 || (D & 1) || n_heads <= 0 || n_tokens < 0 || !(theta > 0.0)) return -1;
+    const int32_t half = D / 2;
+    for (int64_t t = 0; t < n_tokens; ++t)
+        for (int32_t h = 0; h < n_heads; ++h) {
+            double *row = k + (t * n_heads + h) * D;
+            for (int32_t i = 0; i < half; ++i) {
+                const double w = pow(theta, -2.0 * (double)i / (double)D);
+                const double a = (double)pos[t] * w;
+                const double c = cos(a), sn = sin(a);
+                const double x = row[i], y = row[i + half];
+                row[i] = x * c - y * sn;
+                row[i + half] = y * c + x * sn;
+            }
+        }
+    return 0;
 }
