@@ -311,6 +311,22 @@ def main():
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
     extra = {}
+    # the re-encoding stitch (keys rotary-encoded by position while they are copied): same bytes, an
+    # extra measurement beside the step; the step itself uses the plain stitch
+    ctx.tc_release_seqs(bt)
+    ctx.tc_profile_enable(True)
+    ctx.tc_profile_read()
+    for _ in range(max(3, args.steps // 5)):
+        bt_r, _ = ctx.tc_stitch_kv_rope(ids, cu_t, sl, None, 1.0e6, max_blocks, stream)
+        ctx.tc_release_seqs(bt_r)
+    torch.cuda.synchronize()
+    prof_r = ctx.tc_profile_read()
+    ctx.tc_profile_enable(False)
+    rope_us = prof_r["stitch"][0] * 1e3 / max(prof_r["stitch"][1], 1)
+    extra["stitch_rope_kernel_us"] = round(rope_us, 2)
+    extra["stitch_rope_gbps"] = round(stitch_bytes / (rope_us * 1e-6) / 1e9, 1)
+    extra["stitch_rope_frac_hbm"] = round(stitch_bytes / (rope_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4)
+    bt, pl = ctx.tc_stitch_kv(ids, cu_t, sl, max_blocks, stream)
     if not args.no_graph:
         g = torch.cuda.CUDAGraph()
         layers(bt, pl)

@@ -157,6 +157,26 @@ tc_status tc_stitch_kv(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_
                        int32_t *prefix_len, void *stream);
 
 /*
+ * Stitch with positional re-encoding (Sec. 4.1.1, last paragraph: table KV is stored without
+ * positional encoding, and at inference every token is encoded by its global position in the
+ * concatenated sequence).  Same as tc_stitch_kv, except that the registered keys are taken to be
+ * position-free and each key row is written to the pool rotary-encoded for position
+ * pos0[i] + p, p being the token's index in query i's concatenation: in every head, elements
+ * (j, j + D/2) are turned by (pos0[i] + p) * rope_theta^(-2j/D) radians (the half-split convention
+ * of the rotary-position decoders the paper evaluates).  Values are copied unchanged and so are
+ * block tables and prefix lengths.  The turn is reduced in fp64, the rotation is fp32, the result
+ * is rounded once to the element type.  The caller's q and k_new are expected to be encoded
+ * already (for positions pos0[i] + P_i + s), as a model's attention layer produces them.
+ *   pos0         HOST in [B], position of each query's first schema token; NULL = all zero
+ *   rope_theta   the encoding's base (> 1), e.g. 1e6 or 1e4
+ * Further errors: TC_ERR_INVALID for a bad base, a negative position or a head size whose
+ * half is not a whole number of 16-byte chunks.
+ */
+tc_status tc_stitch_kv_rope(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_tables, int32_t B,
+                            const int32_t *suffix_len, const int32_t *pos0, double rope_theta,
+                            int32_t *block_table, int32_t max_blocks, int32_t *prefix_len, void *stream);
+
+/*
  * Suffix prefill attention, one layer (App. E.4: only the uncached part of the prompt
  * is computed, and it attends to all preceding table content; it is causal to itself).
  * First the suffix keys/values are appended to the sequence blocks at logical positions

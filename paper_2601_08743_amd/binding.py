@@ -32,7 +32,7 @@ TC_POLICY_LRU, TC_POLICY_FIFO, TC_POLICY_LFU = 0, 1, 2
 
 EXPORTS = ["tc_block_bytes", "tc_pool_bytes", "tc_first_seq_block", "tc_create", "tc_destroy",
            "tc_register_table_kv", "tc_load_async", "tc_load_trace", "tc_is_resident",
-           "tc_stitch_kv", "tc_prefill_attn", "tc_release_seqs", "tc_read_seq_kv",
+           "tc_stitch_kv", "tc_stitch_kv_rope", "tc_prefill_attn", "tc_release_seqs", "tc_read_seq_kv",
            "tc_kv_splits", "tc_set_kv_splits", "tc_set_row_blocks", "tc_set_attn_kernel", "tc_attn_kernel", "tc_profile_enable", "tc_profile_read", "tc_last_error", "tc_version"]
 
 
@@ -58,6 +58,7 @@ _sig = {
     "tc_load_trace": (_i32, [_vp, _vp, _i32]),
     "tc_is_resident": (_i32, [_vp, _i32, _i32, _i32]),
     "tc_stitch_kv": (_i32, [_vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp]),
+    "tc_stitch_kv_rope": (_i32, [_vp, _vp, _vp, _i32, _vp, _vp, ctypes.c_double, _vp, _i32, _vp, _vp]),
     "tc_prefill_attn": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32,
                                ctypes.c_float, _vp]),
     "tc_release_seqs": (_i32, [_vp, _vp, _i32, _i32]),
@@ -182,6 +183,18 @@ class Context:
         pl = np.full((B,), -7, dtype=np.int32)
         self._check(_lib.tc_stitch_kv(self._h, ids.ctypes.data, cu.ctypes.data, B, sl.ctypes.data,
                                       bt.ctypes.data, max_blocks, pl.ctypes.data, _stream(stream)))
+        return bt, pl
+
+    def tc_stitch_kv_rope(self, table_ids, cu_tables, suffix_len, pos0, rope_theta: float, max_blocks: int,
+                          stream=None) -> Tuple[np.ndarray, np.ndarray]:
+        ids, cu, sl = _i32arr(table_ids), _i32arr(cu_tables), _i32arr(suffix_len)
+        B = cu.size - 1
+        p0 = None if pos0 is None else _i32arr(pos0)
+        bt = np.full((B, max_blocks), -7, dtype=np.int32)
+        pl = np.full((B,), -7, dtype=np.int32)
+        self._check(_lib.tc_stitch_kv_rope(self._h, ids.ctypes.data, cu.ctypes.data, B, sl.ctypes.data,
+                                           None if p0 is None else p0.ctypes.data, float(rope_theta),
+                                           bt.ctypes.data, max_blocks, pl.ctypes.data, _stream(stream)))
         return bt, pl
 
     def tc_prefill_attn(self, layer: int, q, k_new, v_new, out, cu_seqlens, block_table,

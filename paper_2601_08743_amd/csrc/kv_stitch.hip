@@ -6,6 +6,8 @@
 //   V half: fp32: [Hkv][16 tokens][D]
 //           bf16: [Hkv][D][16 tokens], token t stored at position vperm(t) so that the two
 //                 8-token groups a PV matrix-core operand needs are 16 contiguous bytes.
+#include <algorithm>
+
 #include "kv_append.h"
 #include "tc_internal.h"
 
@@ -14,10 +16,20 @@ namespace tc {
 // ------------------------------------------------------------------------------------ stitch
 // Paper Sec. 4.1.2: the matched tables' KV caches are concatenated in match order.
 // One work-group per (destination block, layer).
-template <bool kTransposeV>
+//
+// kRope (Sec. 4.1.1, last paragraph): the stored keys carry no positional encoding and get it
+// here, while they are copied, from their global position in the concatenated sequence: rotary
+// encoding in the half-split convention, pair (i, i + D/2) of every head turned by
+// pos * theta^(-2i/D).  The turn is taken as a fraction of a revolution in fp64 (pos times a
+// per-frequency constant the host computed in fp64; only the fraction matters), so positions of
+// tens of thousands lose nothing; sine and cosine of that fraction (fp32 storage: accurate library
+// routine; bf16 storage: the hardware instructions, whose ~1e-6 error is far below the result's
+// rounding) and the rotation itself are fp32, the result is rounded once to the storage type.
+// V is copied unchanged.
+template <bool kTransposeV, bool kRope>
 __global__ __launch_bounds__(256) void stitch_kernel(Geom g, BatchDev b, int l0)
 {
-    extern __shared__ uint4 lds[];                 // transposing path: [16][row_bytes/16]
+    extern __shared__ uint4 lds[];                 // the rotation table, then (transposing path) V rows [16][row_bytes/16]
     __shared__ int64_t src_off[kBlockTokens];
     const StitchBlk blk = b.stitch_blk[blockIdx.x];
     const int layer = l0 + blockIdx.y;
@@ -40,13 +52,111 @@ __global__ __launch_bounds__(256) void stitch_kernel(Geom g, BatchDev b, int l0)
     const int cph = g.head_bytes >> 4;             // ... per head
     const int n_chunks = kBlockTokens * cpr;
     const uint4 zero = make_uint4(0, 0, 0, 0);
-    // K: [t][h][d] -> [h][t][d]
-    for (int c = tid; c < n_chunks; c += 256) {
-        const int t = c / cpr, w = c - t * cpr;
-        const int h = w / cph, dc = w - h * cph;
-        const int64_t so = src_off[t];
-        const uint4 v = so >= 0 ? *(const uint4 *)(layer_base + so + ((int64_t)w << 4)) : zero;
-        *(uint4 *)(dst + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = v;
+    if (!kRope) {
+        // K: [t][h][d] -> [h][t][d]
+        for (int c = tid; c < n_chunks; c += 256) {
+            const int t = c / cpr, w = c - t * cpr;
+            const int h = w / cph, dc = w - h * cph;
+            const int64_t so = src_off[t];
+            const uint4 v = so >= 0 ? *(const uint4 *)(layer_base + so + ((int64_t)w << 4)) : zero;
+            *(uint4 *)(dst + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = v;
+        }
+    } else {
+        // one unit = the two 16-byte chunks of a head row that hold elements i and i + D/2.  The
+        // loads of a pass of kUnits units per thread are issued first; the rotation table is built
+        // while they are in flight.
+        const int half_d = g.D >> 1;
+        const int half_c = cph >> 1;
+        const int n_units = kBlockTokens * g.Hkv * half_c;
+        constexpr int kElems = kTransposeV ? 8 : 4;                 // elements per chunk: bf16 or fp32
+        constexpr int kUnits = 4;
+        float2 *cs = (float2 *)lds;             // shares the V staging area: a barrier separates the two uses
+        const int64_t pos_base = (int64_t)b.rope_pos0[blk.q] + blk.p0;
+        bool table_ready = false;
+        for (int u0 = tid; u0 < n_units; u0 += 256 * kUnits) {
+            uint4 va[kUnits], vb[kUnits];
+#pragma unroll
+            for (int j = 0; j < kUnits; ++j) {
+                const int u = u0 + 256 * j;
+                va[j] = zero;
+                vb[j] = zero;
+                if (u < n_units) {
+                    const int t = u / (g.Hkv * half_c), r = u - t * (g.Hkv * half_c);
+                    const int h = r / half_c, cc = r - h * half_c;
+                    const int64_t so = src_off[t];
+                    if (so >= 0) {
+                        const char *src = layer_base + so + ((int64_t)(h * cph + cc) << 4);
+                        va[j] = *(const uint4 *)src;
+                        vb[j] = *(const uint4 *)(src + (half_c << 4));
+                    }
+                }
+            }
+            if (!table_ready) {
+                // (cos, sin) of every (token of the block, frequency): [16][D/2] float2
+                for (int idx = tid; idx < kBlockTokens * half_d; idx += 256) {
+                    const int t = idx / half_d, i = idx - t * half_d;
+                    const double turns = (double)(pos_base + t) * b.rope_rev_freq[i];
+                    const float frac = (float)(turns - floor(turns));      // [0, 1) of a revolution
+                    float sn, c;
+                    if (kTransposeV) {                                      // bf16 results: the hardware's sine / cosine
+                        sn = __builtin_amdgcn_sinf(frac);                   // (argument in revolutions, ~1e-6 absolute)
+                        c = __builtin_amdgcn_cosf(frac);
+                    } else {
+                        sincospif(2.0f * frac, &sn, &c);
+                    }
+                    cs[idx] = make_float2(c, sn);
+                }
+                __syncthreads();
+                table_ready = true;
+            }
+#pragma unroll
+            for (int j = 0; j < kUnits; ++j) {
+                const int u = u0 + 256 * j;
+                if (u >= n_units) continue;
+                const int t = u / (g.Hkv * half_c), r = u - t * (g.Hkv * half_c);
+                const int h = r / half_c, cc = r - h * half_c;
+                const float2 *csr = cs + t * half_d + cc * kElems;
+                uint4 oa, ob;
+                if (kTransposeV) {                                      // bf16 storage
+                    const unsigned ua[4] = {va[j].x, va[j].y, va[j].z, va[j].w}, ub[4] = {vb[j].x, vb[j].y, vb[j].z, vb[j].w};
+                    unsigned ra[4], rb[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        float xa[2] = {__uint_as_float(ua[k] << 16), __uint_as_float(ua[k] & 0xffff0000u)};
+                        float xb[2] = {__uint_as_float(ub[k] << 16), __uint_as_float(ub[k] & 0xffff0000u)};
+                        unsigned short pa[2], pb[2];
+#pragma unroll
+                        for (int e = 0; e < 2; ++e) {
+                            const float2 w = csr[2 * k + e];
+                            const __bf16 na = (__bf16)(xa[e] * w.x - xb[e] * w.y);
+                            const __bf16 nb = (__bf16)(xb[e] * w.x + xa[e] * w.y);
+                            pa[e] = *(const unsigned short *)&na;
+                            pb[e] = *(const unsigned short *)&nb;
+                        }
+                        ra[k] = pa[0] | ((unsigned)pa[1] << 16);
+                        rb[k] = pb[0] | ((unsigned)pb[1] << 16);
+                    }
+                    oa = make_uint4(ra[0], ra[1], ra[2], ra[3]);
+                    ob = make_uint4(rb[0], rb[1], rb[2], rb[3]);
+                } else {                                                // fp32 storage
+                    const float xa[4] = {__uint_as_float(va[j].x), __uint_as_float(va[j].y), __uint_as_float(va[j].z), __uint_as_float(va[j].w)};
+                    const float xb[4] = {__uint_as_float(vb[j].x), __uint_as_float(vb[j].y), __uint_as_float(vb[j].z), __uint_as_float(vb[j].w)};
+                    float na[4], nb[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float2 w = csr[e];
+                        na[e] = xa[e] * w.x - xb[e] * w.y;
+                        nb[e] = xb[e] * w.x + xa[e] * w.y;
+                    }
+                    oa = make_uint4(__float_as_uint(na[0]), __float_as_uint(na[1]), __float_as_uint(na[2]), __float_as_uint(na[3]));
+                    ob = make_uint4(__float_as_uint(nb[0]), __float_as_uint(nb[1]), __float_as_uint(nb[2]), __float_as_uint(nb[3]));
+                }
+                char *d = dst + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (cc << 4);
+                *(uint4 *)d = oa;
+                *(uint4 *)(d + (half_c << 4)) = ob;
+            }
+        }
+        __syncthreads();                        // the rotation table is dead: the V staging may overwrite it
     }
     const char *vsrc_base = layer_base + (g.slot_bytes >> 1);
     char *vdst = dst + (g.block_bytes >> 1);
@@ -88,14 +198,20 @@ __global__ __launch_bounds__(256) void stitch_kernel(Geom g, BatchDev b, int l0)
     }
 }
 
-hipError_t launch_stitch(const Geom &g, const BatchDev &b, int l0, int l1, const Launch &L)
+hipError_t launch_stitch(const Geom &g, const BatchDev &b, int l0, int l1, bool rope, const Launch &L)
 {
     if (b.n_stitch_blk == 0 || l1 <= l0) return hipSuccess;
     dim3 grid(b.n_stitch_blk, l1 - l0);
-    if (g.esize == 2)
-        TC_LAUNCH(stitch_kernel<true>, grid, kBlockTokens * g.row_bytes, L, g, b, l0);
-    else
-        TC_LAUNCH(stitch_kernel<false>, grid, 0, L, g, b, l0);
+    const size_t cs_bytes = rope ? (size_t)kBlockTokens * (g.D >> 1) * sizeof(float2) : 0;
+    const size_t v_bytes = (size_t)kBlockTokens * g.row_bytes;
+    if (rope && (!b.rope_pos0 || !b.rope_rev_freq || (g.D & 1) || ((g.head_bytes >> 4) & 1))) return hipErrorInvalidValue;
+    if (g.esize == 2) {
+        if (rope) TC_LAUNCH((stitch_kernel<true, true>), grid, std::max(v_bytes, cs_bytes), L, g, b, l0);
+        else TC_LAUNCH((stitch_kernel<true, false>), grid, kBlockTokens * g.row_bytes, L, g, b, l0);
+    } else {
+        if (rope) TC_LAUNCH((stitch_kernel<false, true>), grid, cs_bytes, L, g, b, l0);
+        else TC_LAUNCH((stitch_kernel<false, false>), grid, 0, L, g, b, l0);
+    }
     return hipGetLastError();
 }
 

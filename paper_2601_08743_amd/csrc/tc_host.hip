@@ -104,6 +104,9 @@ struct Plan {
     bool valid = false;
     int32_t B = 0, max_blocks = 0, total_S = 0, n_stitch_blk = 0, n_items = 0, max_splits = 1, n_groups = 0, row_blocks = 1;
     bool pipelined = false;     // bf16, one row block per wave: the pipelined attention kernel
+    bool rope = false;          // the stitch re-encodes keys by position (Sec. 4.1.1)
+    std::vector<int32_t> rope_pos0;      // [B]
+    std::vector<double> rope_rev_freq;   // [D/2]
     std::vector<int32_t> block_table, cu_seqlens, prefix_len, suffix_len;
     BatchDev dev{};
     const AttnItem *items_dev = nullptr;
@@ -394,6 +397,7 @@ tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
     const size_t o_sb = take(sblk.size() * 4), o_sp = take(B), o_tq = take(p.total_S);
     const size_t o_it = take(items.size() * (sizeof(AttnItem) / 4));
     const size_t o_gr = take(groups.size() * (sizeof(MergeGroup) / 4));
+    const size_t o_rp = take(p.rope ? B : 0), o_rf = take(p.rope ? p.rope_rev_freq.size() * 2 : 0);
     const size_t total = std::max(off, size_t(8));
     tc_status st = ensure_stage(ctx, total);
     if (st != TC_OK) return st;
@@ -415,6 +419,10 @@ tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
         for (int n = p.cu_seqlens[i]; n < p.cu_seqlens[i + 1]; ++n) h[o_tq + n] = i;
     if (!items.empty()) std::memcpy(h + o_it, items.data(), items.size() * sizeof(AttnItem));
     if (!groups.empty()) std::memcpy(h + o_gr, groups.data(), groups.size() * sizeof(MergeGroup));
+    if (p.rope) {
+        if (B) std::memcpy(h + o_rp, p.rope_pos0.data(), B * 4);
+        std::memcpy(h + o_rf, p.rope_rev_freq.data(), p.rope_rev_freq.size() * sizeof(double));
+    }
 
     TC_HIP(ctx, hipMemcpyAsync(ctx->d_plan, h, total * sizeof(int32_t), hipMemcpyHostToDevice, stream));
     TC_HIP(ctx, hipEventRecord(ctx->stage_ev, stream));
@@ -426,6 +434,8 @@ tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
     p.dev.seg_slot = d + o_st; p.dev.seg_end_of_q = d + o_se;
     p.dev.stitch_blk = (const StitchBlk *)(d + o_sb); p.dev.splits_of_q = d + o_sp;
     p.dev.tok_q = d + o_tq;
+    p.dev.rope_pos0 = p.rope ? d + o_rp : nullptr;
+    p.dev.rope_rev_freq = p.rope ? (const double *)(d + o_rf) : nullptr;
     p.dev.B = p.B; p.dev.max_blocks = p.max_blocks; p.dev.total_S = p.total_S;
     p.dev.n_stitch_blk = (int32_t)sblk.size();
     p.n_stitch_blk = (int32_t)sblk.size();
@@ -644,15 +654,26 @@ int32_t tc_is_resident(const tc_ctx *ctx, int32_t table_id, int32_t l0, int32_t 
     return 1;
 }
 
-tc_status tc_stitch_kv(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_tables, int32_t B,
-                       const int32_t *suffix_len, int32_t *block_table, int32_t max_blocks,
-                       int32_t *prefix_len, void *stream_)
+}  // extern "C"
+
+// Common body of tc_stitch_kv and tc_stitch_kv_rope (rope: re-encode the keys by position).
+static tc_status stitch_common(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_tables, int32_t B,
+                               const int32_t *suffix_len, int32_t *block_table, int32_t max_blocks,
+                               int32_t *prefix_len, void *stream_, bool rope, const int32_t *pos0,
+                               double rope_theta)
 {
     if (!ctx) return TC_ERR_INVALID;
     if (B < 0 || max_blocks < 0) return fail(ctx, TC_ERR_INVALID, "stitch: negative size");
     if (B > 0 && (!cu_tables || !suffix_len || !block_table || !prefix_len))
         return fail(ctx, TC_ERR_INVALID, "stitch: null argument");
     if (B > 0 && (cu_tables[0] != 0)) return fail(ctx, TC_ERR_INVALID, "stitch: cu_tables[0] != 0");
+    if (rope) {
+        if (!(rope_theta > 1.0) || !std::isfinite(rope_theta)) return fail(ctx, TC_ERR_INVALID, "stitch: rope_theta must be finite and > 1");
+        if (ctx->cfg.head_dim % (ctx->cfg.dtype == TC_BF16 ? 16 : 8))
+            return fail(ctx, TC_ERR_INVALID, "stitch: re-encoding needs head_dim/2 to be a whole number of 16-byte chunks");
+        for (int i = 0; pos0 && i < B; ++i)
+            if (pos0[i] < 0 || pos0[i] > (1 << 28)) return fail(ctx, TC_ERR_INVALID, "stitch: pos0[%d] out of range", i);
+    }
     hipStream_t stream = (hipStream_t)stream_;
     const int L = ctx->cfg.n_layers;
 
@@ -695,6 +716,15 @@ tc_status tc_stitch_kv(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_
     p.prefix_len = P;
     p.suffix_len.assign(suffix_len, suffix_len + B);
     for (int i = 0; i < B; ++i) p.cu_seqlens[i + 1] = p.cu_seqlens[i] + suffix_len[i];
+    p.rope = rope;
+    if (rope) {
+        p.rope_pos0.assign(B, 0);
+        if (pos0) p.rope_pos0.assign(pos0, pos0 + B);
+        const int D = ctx->cfg.head_dim;
+        p.rope_rev_freq.resize(D / 2);
+        const double two_pi = 6.283185307179586476925286766559;
+        for (int i = 0; i < D / 2; ++i) p.rope_rev_freq[i] = std::pow(rope_theta, -2.0 * i / D) / two_pi;
+    }
     auto next_free = ctx->free_seq.begin();
     std::vector<StitchBlk> sblk;
     for (int i = 0; i < B; ++i) {
@@ -727,7 +757,7 @@ tc_status tc_stitch_kv(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_
             TC_HIP(ctx, hipStreamWaitEvent(stream, sl.ready, 0));
     }
     ctx->plan = std::move(p);
-    TC_HIP(ctx, timed_launch(ctx, 0, stream, [&](const Launch &ln) { return launch_stitch(ctx->geom, ctx->plan.dev, 0, L, ln); }));
+    TC_HIP(ctx, timed_launch(ctx, 0, stream, [&](const Launch &ln) { return launch_stitch(ctx->geom, ctx->plan.dev, 0, L, ctx->plan.rope, ln); }));
     if (!used_slots.empty()) {
         const int32_t ev = ctx->read_next;
         ctx->read_next = (ctx->read_next + 1) % (int32_t)ctx->read_ring.size();
@@ -739,6 +769,24 @@ tc_status tc_stitch_kv(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_
         std::memcpy(prefix_len, ctx->plan.prefix_len.data(), (size_t)B * sizeof(int32_t));
     }
     return TC_OK;
+}
+
+extern "C" {
+
+tc_status tc_stitch_kv(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_tables, int32_t B,
+                       const int32_t *suffix_len, int32_t *block_table, int32_t max_blocks,
+                       int32_t *prefix_len, void *stream)
+{
+    return stitch_common(ctx, table_ids, cu_tables, B, suffix_len, block_table, max_blocks, prefix_len, stream,
+                         false, nullptr, 0.0);
+}
+
+tc_status tc_stitch_kv_rope(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_tables, int32_t B,
+                            const int32_t *suffix_len, const int32_t *pos0, double rope_theta,
+                            int32_t *block_table, int32_t max_blocks, int32_t *prefix_len, void *stream)
+{
+    return stitch_common(ctx, table_ids, cu_tables, B, suffix_len, block_table, max_blocks, prefix_len, stream,
+                         true, pos0, rope_theta);
 }
 
 tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,

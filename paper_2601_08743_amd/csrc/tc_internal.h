@@ -52,6 +52,8 @@ struct BatchDev {
     const StitchBlk *stitch_blk;  // [n_stitch_blk]
     const int32_t *splits_of_q;   // [B] split-KV partitions used for query q
     const int32_t *tok_q;         // [sum S] query index of each suffix token
+    const int32_t *rope_pos0;     // [B] position of each query's first schema token (re-encoding stitch), else null
+    const double *rope_rev_freq;  // [D/2] theta^(-2i/D) / (2 pi): revolutions per position step, else null
     int32_t B, max_blocks, total_S, n_stitch_blk;
 };
 
@@ -102,7 +104,7 @@ struct Launch {
     hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(256), (lds_bytes), (L).stream, (L).start, (L).stop, 0, __VA_ARGS__)
 
 // kv_stitch.hip
-hipError_t launch_stitch(const Geom &g, const BatchDev &b, int l0, int l1, const Launch &L);
+hipError_t launch_stitch(const Geom &g, const BatchDev &b, int l0, int l1, bool rope, const Launch &L);
 hipError_t launch_append(const Geom &g, const BatchDev &b, int layer, const void *k_new,
                          const void *v_new, const Launch &L);
 hipError_t launch_readback(const Geom &g, int layer, const int32_t *blocks_dev, int n_tokens,

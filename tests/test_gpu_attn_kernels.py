@@ -114,8 +114,9 @@ def test_fixed_reference_extremes(H, profile):
     huge key late in the prefix.  The checker works in fp64 with the true maximum.
 
     Tolerance.  In these profiles a handful of keys carry all the weight, so nothing averages out:
-    the weights enter the PV product rounded to bf16 (relative error <= 2^-9 each, so at most
-    2^-9 max|v| on the output) and the output itself is rounded to bf16 (<= 2^-8 |out|).  The
+    the weights enter the PV product rounded to bf16 (relative error <= 2^-8 each, 2^-9 on average)
+    and the output itself is rounded to bf16, so |err| <= 2^-8 (max|v| + |out|); the test asks for
+    3 * 2^-9 max|v|, inside that bound.  The
     general kernel does a little better than that bound because its reference is the running
     maximum, which makes the largest weight exactly 1; with a fixed reference no weight is special."""
     n_tok = 640
