@@ -256,3 +256,46 @@ def replay(model, accesses: Sequence[int]) -> List[Tuple[int, int, int]]:
         hit, ev = model.access(int(t))
         out.append((int(t), int(hit), -1 if ev is None else int(ev)))
     return out
+
+
+# ----------------------------------------------------------------------------- front end (upstream of the path)
+
+def trie_match(tables: Dict[int, Sequence[int]], s: Sequence[int]) -> List[Tuple[int, int]]:
+    """Alg. 1 (Table Trie Matching) by brute force, without a trie: scan the prompt's token
+    sequence `s` from p = 0; at p, among the tables whose whole token content equals
+    s[p : p + len], take the longest (Sec. 4.1.2: longest prefix match, exact match of a table);
+    found -> record (table id, p) and continue at the end of the match, else p + 1.
+    Returns the matches in order.  `tables` maps table id -> token ids (non-empty, distinct)."""
+    s = list(s)
+    out, p = [], 0
+    while p < len(s):
+        best_id, best_len = None, 0
+        for tid, toks in tables.items():
+            n = len(toks)
+            if n > best_len and p + n <= len(s) and all(s[p + k] == toks[k] for k in range(n)):
+                best_id, best_len = tid, n
+        if best_id is None:
+            p += 1
+        else:
+            out.append((best_id, p))
+            p += best_len
+    return out
+
+
+def rerank(table_sets: Sequence[Sequence[int]], anchor: int) -> List[int]:
+    """Query reranking (Sec. 4.2.1, Eq. 1-2) by brute force with Python sets: start from the
+    anchor query; repeatedly move to the remaining query whose table set differs least from the
+    current one's - the distance of Eq. 2 is the size of the symmetric difference - lowest index
+    on ties.  Returns the visiting order (a permutation of the query indices)."""
+    sets = [frozenset(int(t) for t in ts) for ts in table_sets]
+    n = len(sets)
+    if n == 0:
+        return []
+    left = [i for i in range(n) if i != anchor]
+    order, cur = [anchor], anchor
+    while left:
+        best = min(left, key=lambda j: (len(sets[cur] ^ sets[j]), j))
+        left.remove(best)
+        order.append(best)
+        cur = best
+    return order
