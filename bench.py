@@ -179,6 +179,32 @@ def bench_pipeline(args):
     print(json.dumps(res))
 
 
+def frontend_extras(wl):
+    """Host front end (Table Trie matching of Alg. 1, reranking of Eq. 1-2): rates on this workload's
+    prompts and on a batch of 1024 zipf-drawn table sets; results checked (ids recovered, order valid)."""
+    from paper_2601_08743_amd import binding as B
+    from paper_2601_08743_amd import workloads as W
+    c = wl.cfg
+    trie = B.Trie()
+    for t in range(c.n_tables):
+        trie.tc_trie_insert(t, wl.table_tokens(t))
+    prompts = [wl.prompt_tokens(i) for i in range(c.batch)]
+    reps = max(1, 200 // c.batch)
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        got = [trie.tc_trie_match(p)[0] for p in prompts]
+    dt = (time.perf_counter() - t0) / reps
+    for i, m in enumerate(got):
+        assert [tid for tid, _ in m][:len(wl.queries[i])] == wl.queries[i].tolist(), "front end: tables not recovered"
+    n_tok = sum(p.size for p in prompts)
+    big = W.make_workload(W.scaled(c, batch=1024, choice="zipf", tables_per_query=(4, 12), seed=c.seed + 77))
+    t0 = time.perf_counter()
+    order = B.tc_rerank(big.table_ids, big.cu_tables, c.n_tables, 0)
+    dt_r = time.perf_counter() - t0
+    assert sorted(order.tolist()) == list(range(1024))
+    return {"frontend_match_mtok_s": round(n_tok / dt / 1e6, 2), "frontend_rerank_1024q_ms": round(dt_r * 1e3, 3)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -327,6 +353,7 @@ def main():
     extra["stitch_rope_gbps"] = round(stitch_bytes / (rope_us * 1e-6) / 1e9, 1)
     extra["stitch_rope_frac_hbm"] = round(stitch_bytes / (rope_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4)
     bt, pl = ctx.tc_stitch_kv(ids, cu_t, sl, max_blocks, stream)
+    extra.update(frontend_extras(wl))
     if not args.no_graph:
         g = torch.cuda.CUDAGraph()
         layers(bt, pl)

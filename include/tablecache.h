@@ -239,6 +239,37 @@ int32_t tc_attn_kernel(const tc_ctx *ctx);
 tc_status tc_profile_enable(tc_ctx *ctx, int32_t on);
 tc_status tc_profile_read(tc_ctx *ctx, double *ms_out, int64_t *count_out);
 
+/*
+ * Front end (host only; upstream of the path): which tables does a prompt contain, and in which
+ * order should a batch's queries run.
+ *
+ * Table Trie and Alg. 1 (Sec. 4.1.2): the token content of every table is inserted into a trie
+ * whose terminal nodes hold the table id.  tc_trie_match scans a prompt's token sequence from
+ * position 0: at position p it takes the longest table whose whole content is a prefix of the
+ * rest of the prompt; if there is one, the table is reported and the scan continues behind it,
+ * otherwise at p + 1.  The reported ids, in order, are the table_ids of tc_stitch_kv.
+ *   tc_trie_insert   tokens HOST in [n_tokens] (n_tokens >= 1); TC_ERR_INVALID for a negative or
+ *                    repeated id, an empty content, or a content equal to an inserted table's
+ *   tc_trie_match    s HOST in [len]; table_ids_out / start_out HOST out [cap] (start_out may be
+ *                    NULL): the matched tables and the positions where they start.  Returns the
+ *                    number of matches (only the first cap are stored), or TC_ERR_INVALID.
+ *
+ * Query reranking (Sec. 4.2.1, Eq. 1-2): query i's tables as a bit set I_i over all n_tables
+ * tables; d_ij = popcount(I_i xor I_j).  From the anchor (the paper draws it at random: the caller
+ * passes it), the next query is always the remaining one nearest to the current one, lowest index
+ * on ties.
+ *   tc_rerank        table_ids / cu_tables HOST in, as for tc_stitch_kv (ids in [0, n_tables));
+ *                    order_out HOST out [n_queries], the visiting order.
+ */
+typedef struct tc_trie tc_trie;
+tc_trie *tc_trie_create(void);
+void tc_trie_destroy(tc_trie *trie);
+tc_status tc_trie_insert(tc_trie *trie, int32_t table_id, const int32_t *tokens, int32_t n_tokens);
+int32_t tc_trie_match(const tc_trie *trie, const int32_t *s, int32_t len, int32_t *table_ids_out,
+                      int32_t *start_out, int32_t cap);
+tc_status tc_rerank(const int32_t *table_ids, const int32_t *cu_tables, int32_t n_queries, int32_t n_tables,
+                    int32_t anchor, int32_t *order_out);
+
 /* Text for the most recent error on this context; library-owned, valid until the next call. */
 const char *tc_last_error(const tc_ctx *ctx);
 /* Library version string. */

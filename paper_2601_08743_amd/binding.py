@@ -33,7 +33,8 @@ TC_POLICY_LRU, TC_POLICY_FIFO, TC_POLICY_LFU = 0, 1, 2
 EXPORTS = ["tc_block_bytes", "tc_pool_bytes", "tc_first_seq_block", "tc_create", "tc_destroy",
            "tc_register_table_kv", "tc_load_async", "tc_load_trace", "tc_is_resident",
            "tc_stitch_kv", "tc_stitch_kv_rope", "tc_prefill_attn", "tc_release_seqs", "tc_read_seq_kv",
-           "tc_kv_splits", "tc_set_kv_splits", "tc_set_row_blocks", "tc_set_attn_kernel", "tc_attn_kernel", "tc_profile_enable", "tc_profile_read", "tc_last_error", "tc_version"]
+           "tc_kv_splits", "tc_set_kv_splits", "tc_set_row_blocks", "tc_set_attn_kernel", "tc_attn_kernel", "tc_profile_enable", "tc_profile_read", "tc_last_error", "tc_version",
+           "tc_trie_create", "tc_trie_destroy", "tc_trie_insert", "tc_trie_match", "tc_rerank"]
 
 
 class tc_config(ctypes.Structure):
@@ -72,6 +73,11 @@ _sig = {
     "tc_profile_read": (_i32, [_vp, _vp, _vp]),
     "tc_last_error": (ctypes.c_char_p, [_vp]),
     "tc_version": (ctypes.c_char_p, []),
+    "tc_trie_create": (_vp, []),
+    "tc_trie_destroy": (None, [_vp]),
+    "tc_trie_insert": (_i32, [_vp, _i32, _vp, _i32]),
+    "tc_trie_match": (_i32, [_vp, _vp, _i32, _vp, _vp, _i32]),
+    "tc_rerank": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp]),
 }
 for _n, (_r, _a) in _sig.items():
     getattr(_lib, _n).restype = _r
@@ -249,3 +255,52 @@ class Context:
 
     def tc_last_error(self) -> str:
         return _lib.tc_last_error(self._h).decode()
+
+
+class Trie:
+    """The Table Trie (same-named calls: tc_trie_insert, tc_trie_match)."""
+
+    def __init__(self):
+        self._h = _lib.tc_trie_create()
+        if not self._h:
+            raise MemoryError("tc_trie_create")
+
+    def tc_trie_insert(self, table_id: int, tokens):
+        t = _i32arr(tokens)
+        rc = _lib.tc_trie_insert(self._h, int(table_id), t.ctypes.data, t.size)
+        if rc != TC_OK:
+            raise TcError(rc, "tc_trie_insert(%d)" % table_id)
+
+    def tc_trie_match(self, s, cap: int = None):
+        """[(table id, start position)] in match order."""
+        s = _i32arr(s)
+        cap = s.size if cap is None else cap
+        ids = np.empty(max(cap, 1), dtype=np.int32)
+        st = np.empty(max(cap, 1), dtype=np.int32)
+        n = _lib.tc_trie_match(self._h, s.ctypes.data, s.size, ids.ctypes.data, st.ctypes.data, cap)
+        if n < 0:
+            raise TcError(n, "tc_trie_match")
+        k = min(n, cap)
+        return list(zip(ids[:k].tolist(), st[:k].tolist())), n
+
+    def tc_trie_destroy(self):
+        if self._h:
+            _lib.tc_trie_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.tc_trie_destroy()
+        except Exception:
+            pass
+
+
+def tc_rerank(table_ids, cu_tables, n_tables: int, anchor: int) -> np.ndarray:
+    ids, cu = _i32arr(table_ids), _i32arr(cu_tables)
+    n = cu.size - 1
+    order = np.full(max(n, 1), -1, dtype=np.int32)
+    rc = _lib.tc_rerank(ids.ctypes.data if ids.size else None, cu.ctypes.data, n, int(n_tables), int(anchor),
+                        order.ctypes.data)
+    if rc != TC_OK:
+        raise TcError(rc, "tc_rerank")
+    return order[:n]

@@ -158,6 +158,20 @@ class Workload:
         v = _draw(rng, (n, c.n_kv_heads, c.head_dim), c.dtype)
         return q, k, v
 
+    def table_tokens(self, t: int, vocab: int = 32000) -> np.ndarray:
+        """Token ids of table ``t``'s schema text (what the Table Trie is built from): one id per
+        schema token, drawn uniformly from the vocabulary."""
+        rng = np.random.default_rng(np.random.SeedSequence([self.cfg.seed, 3, int(t)]))
+        return rng.integers(0, vocab, size=int(self.table_len[t])).astype(np.int32)
+
+    def prompt_tokens(self, i: int, vocab: int = 32000) -> np.ndarray:
+        """Token ids of query ``i``'s prompt: its tables' schema texts in prompt order, then the
+        suffix (instructions and question)."""
+        rng = np.random.default_rng(np.random.SeedSequence([self.cfg.seed, 4, int(i)]))
+        parts = [self.table_tokens(int(t), vocab) for t in self.queries[i]]
+        parts.append(rng.integers(0, vocab, size=int(self.suffix_len[i])).astype(np.int32))
+        return np.concatenate(parts) if parts else np.zeros(0, np.int32)
+
     @property
     def sm_scale(self) -> float:
         return 1.0 / float(np.sqrt(self.cfg.head_dim))
