@@ -199,3 +199,38 @@ def test_every_key_counted_once(H, P, S, splits):
         assert dev < 0.5 * max(1.0, want.max() * 2.0 ** -7)      # a whole count cannot hide in the output rounding
         assert dev <= want.max() * 2.0 ** -8 + 1e-6               # and what is left is that rounding
         dw.close()
+
+
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_random_batches_through_both_kernels(H, seed):
+    """Seeded random batches - 1..5 queries of 1..4 tables with 1..400 tokens each, suffixes of
+    1..200 tokens, 0 (automatic) to 5 key partitions - through both kernels.  Rows that see fewer
+    than 64 keys get the few-key tolerance of the degenerate-shape test."""
+    rng = np.random.default_rng(9000 + seed)
+    n_tables = 6
+    B = int(rng.integers(1, 6))
+    base = W.CONFIGS["c2"]
+    cfg = W.scaled(base, name="rand%d" % seed, n_layers=1, n_tables=n_tables, batch=B, capacity=n_tables,
+                   seed=9000 + seed)
+    table_len = rng.integers(1, 401, size=n_tables).astype(np.int32)
+    queries = [rng.choice(n_tables, size=int(rng.integers(1, 5)), replace=False).astype(np.int32) for _ in range(B)]
+    suffix = rng.integers(1, 201, size=B).astype(np.int32)
+    wl = W.Workload(cfg, table_len, queries, suffix)
+    splits = int(rng.choice([0, 1, 2, 3, 5]))
+    outs = {}
+    for kind in (1, 2):
+        dw = H.DeviceWorkload(wl)
+        dw.ctx.tc_set_attn_kernel(kind)
+        dw.ctx.tc_set_kv_splits(splits)
+        bt, pl = dw.stitch()
+        res, out, qkv = _errs(H, dw, bt, pl, 0)
+        vmax = float(np.abs(W.bf16_bits_to_f32(qkv[2])).max())
+        for i, (e, _) in res.items():
+            tol = TOL if int(pl[i]) >= 64 else max(TOL, 2.0 ** -7 * 4.7)
+            assert e <= tol, "seed %d kernel %d query %d (P %d, S %d, %d partitions): %.3e" % (
+                seed, kind, i, int(pl[i]), int(suffix[i]), splits, e)
+        outs[kind] = H.out_to_f64(out, dw.cfg)
+        dw.close()
+    print("seed %d: B %d P %s S %s partitions %d: kernels differ by %.3e" % (
+        seed, B, [int(table_len[q].sum()) for q in queries], suffix.tolist(), splits,
+        float(np.abs(outs[1] - outs[2]).max())))
