@@ -14,6 +14,7 @@ Pieces and the passages they follow:
 * ``SeqBlockModel``     the paged-pool bookkeeping the library documents: lowest
                         free block first, queries in batch order
 * ``LRUModel`` / ``FIFOModel`` / ``LFUModel``   App. A, the three replacement rules
+* ``plan_pipeline`` / ``simulate_pipeline``      Sec. 4.2.2, micro-batches b_c / b_m
 
 Parity status: every function here is pinned by ``tests/test_oracle_*.py``
 (library causal attention, closed forms, brute-force masks, position-coded
@@ -190,20 +191,26 @@ def prefix_lengths(table_len: Sequence[int], table_ids: Sequence[int], cu_tables
 
 class LRUModel:
     """App. A, LRU: hit -> move to the front; miss -> evict the end if |cache| >= C,
-    insert at the front.  ``access`` returns (hit, evicted or None)."""
+    insert at the front.  ``access`` returns (hit, evicted or None).
+
+    `pinned` (all three models): tables that may not be evicted now, because a query that is
+    about to be stitched uses them (Sec. 4.2.2 loads a micro-batch ahead of its computation;
+    all its tables must still be there).  The victim is then the rule's first choice among the
+    other tables; with nothing pinned the rule is App. A's as printed."""
 
     def __init__(self, capacity: int):
         self.C = capacity
         self.items: List[int] = []          # index 0 = front
 
-    def access(self, t: int) -> Tuple[bool, Optional[int]]:
+    def access(self, t: int, pinned=()) -> Tuple[bool, Optional[int]]:
         if t in self.items:
             self.items.remove(t)
             self.items.insert(0, t)
             return True, None
         ev = None
         if len(self.items) >= self.C:
-            ev = self.items.pop()
+            ev = [x for x in self.items if x not in pinned][-1]     # IndexError: everything is pinned
+            self.items.remove(ev)
         self.items.insert(0, t)
         return False, ev
 
@@ -215,12 +222,13 @@ class FIFOModel:
         self.C = capacity
         self.items: List[int] = []          # index 0 = head
 
-    def access(self, t: int) -> Tuple[bool, Optional[int]]:
+    def access(self, t: int, pinned=()) -> Tuple[bool, Optional[int]]:
         if t in self.items:
             return True, None
         ev = None
         if len(self.items) >= self.C:
-            ev = self.items.pop(0)
+            ev = [x for x in self.items if x not in pinned][0]
+            self.items.remove(ev)
         self.items.append(t)
         return False, ev
 
@@ -235,7 +243,7 @@ class LFUModel:
         self.items: Dict[int, Tuple[int, int]] = {}
         self.now = 0
 
-    def access(self, t: int) -> Tuple[bool, Optional[int]]:
+    def access(self, t: int, pinned=()) -> Tuple[bool, Optional[int]]:
         self.now += 1
         if t in self.items:
             f, _ = self.items[t]
@@ -243,7 +251,7 @@ class LFUModel:
             return True, None
         ev = None
         if len(self.items) >= self.C:
-            ev = min(self.items, key=lambda x: self.items[x])
+            ev = min((x for x in self.items if x not in pinned), key=lambda x: self.items[x])
             del self.items[ev]
         self.items[t] = (1, self.now)
         return False, ev
@@ -255,6 +263,58 @@ def replay(model, accesses: Sequence[int]) -> List[Tuple[int, int, int]]:
     for t in accesses:
         hit, ev = model.access(int(t))
         out.append((int(t), int(hit), -1 if ev is None else int(ev)))
+    return out
+
+
+# ----------------------------------------------------------------------------- Sec. 4.2.2: pipeline schedule
+
+def plan_pipeline(table_sets: Sequence[Sequence[int]], capacity: int, b_c: int, b_m: int):
+    """Sec. 4.2.2, computation-loading pipeline over an ordered batch: the requests are computed
+    b_c at a time, and while a micro-batch is computed the tables of the next b_m requests are
+    copied in.  Returns one tuple per micro-batch,
+        (compute_begin, compute_end, demand_begin, demand_end, prefetch_begin, prefetch_end):
+    `demand` are the requests of this micro-batch nobody has asked for yet (asked for right
+    before its stitch), `prefetch` those asked for right after its stitch.  Requests asked for
+    but not yet stitched keep their tables pinned, so a prefetch stops early where the union of
+    their tables would outgrow the cache."""
+    N, steps, asked = len(table_sets), [], 0
+    uni = lambda a, b: set().union(*[set(map(int, x)) for x in table_sets[a:b]]) if b > a else set()
+    for c0 in range(0, N, b_c):
+        c1 = min(N, c0 + b_c)
+        if len(uni(c0, c1)) > capacity:
+            raise ValueError("micro-batch [%d,%d) needs more than %d tables at once" % (c0, c1, capacity))
+        d0, d1 = asked, max(asked, c1)
+        asked = d1
+        p0 = asked
+        while asked < N and asked < c1 + b_m and len(uni(c1, asked + 1)) <= capacity:
+            asked += 1
+        steps.append((c0, c1, d0, d1, p0, asked))
+    return steps
+
+
+def simulate_pipeline(model, table_sets: Sequence[Sequence[int]], steps) -> List[Tuple[int, int, int]]:
+    """Access trace (table, hit, evicted or -1) of the replacement model when the schedule of
+    `plan_pipeline` is carried out: a range of requests is asked for by pinning all its tables
+    and then requesting them in order; a micro-batch is unpinned once it is stitched."""
+    pins: Dict[int, int] = {}
+    out = []
+
+    def ask(a, b):
+        ids = [int(t) for q in table_sets[a:b] for t in q]
+        for t in ids:
+            pins[t] = pins.get(t, 0) + 1
+        for t in ids:
+            hit, ev = model.access(t, pinned=pins)
+            out.append((t, int(hit), -1 if ev is None else int(ev)))
+
+    for c0, c1, d0, d1, p0, p1 in steps:
+        ask(d0, d1)
+        for q in table_sets[c0:c1]:
+            for t in q:
+                pins[int(t)] -= 1
+                if pins[int(t)] == 0:
+                    del pins[int(t)]
+        ask(p0, p1)
     return out
 
 
