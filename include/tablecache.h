@@ -124,10 +124,28 @@ tc_status tc_register_table_kv(tc_ctx *ctx, int32_t table_id, int32_t n_tokens,
  * Ordering against other streams is the library's job: a stitch that reads a slot
  * waits for that slot's copies; a copy into a reused slot waits for the last stitch
  * that read it.  The (table, hit, evicted) trace is kept for tc_load_trace.
- * Errors: TC_ERR_UNKNOWN_TABLE, TC_ERR_INVALID (layer range), TC_ERR_HIP.
+ * A pinned table (tc_pin_tables) is never the victim: the rule's first choice among
+ * the unpinned tables goes instead; TC_ERR_CAPACITY if a miss finds every cached table
+ * pinned (ids before it in the list stay requested).
+ * Errors: TC_ERR_UNKNOWN_TABLE, TC_ERR_INVALID (layer range), TC_ERR_CAPACITY, TC_ERR_HIP.
  */
 tc_status tc_load_async(tc_ctx *ctx, const int32_t *table_ids, int32_t n,
                         int32_t l0, int32_t l1, void *stream);
+
+/*
+ * Pin / unpin tables in the device cache (reference counted, by table id; a table need
+ * not be cached yet).  App. A states each rule for one request at a time; the tables of
+ * one query, and of a micro-batch whose copies were issued ahead of its computation
+ * (Sec. 4.2.2), must all still be cached when the stitch runs, which the literal rules
+ * do not guarantee (FIFO can drop a table that was a hit a moment ago, LFU drops the
+ * table it has just inserted).  A caller pins a request's tables before requesting them
+ * and unpins them once its stitch is enqueued.  With nothing pinned the rules are
+ * exactly App. A's.   table_ids  HOST, n entries.
+ * Errors: TC_ERR_UNKNOWN_TABLE; TC_ERR_INVALID (unpin of a table that is not pinned:
+ * nothing is changed).
+ */
+tc_status tc_pin_tables(tc_ctx *ctx, const int32_t *table_ids, int32_t n);
+tc_status tc_unpin_tables(tc_ctx *ctx, const int32_t *table_ids, int32_t n);
 
 /* Copy out up to `cap` entries of the access trace since the last call: triples
  * (table, hit 0/1, evicted table or -1).  HOST out[3*cap].  Returns the count (>= 0). */
@@ -271,6 +289,31 @@ tc_status tc_rerank(const int32_t *table_ids, const int32_t *cu_tables, int32_t 
                     int32_t anchor, int32_t *order_out);
 
 /* Text for the most recent error on this context; library-owned, valid until the next call. */
+/*
+ * Computation-loading pipeline schedule (Sec. 4.2.2): the ordered requests are computed
+ * in micro-batches of b_c while the tables of up to the next b_m requests are copied in.
+ * Host only.  Step k computes requests [compute_begin, compute_end) = the k-th run of b_c.
+ * Before its stitch the caller requests the tables of [demand_begin, demand_end) (those
+ * of its requests that no earlier step prefetched: copies the computation has to wait
+ * for); after its stitch is enqueued the caller unpins the step's tables and requests
+ * those of [prefetch_begin, prefetch_end), which overlap the step's attention layers.
+ * The prefetch range ends at compute_end + b_m, or earlier where the distinct tables of
+ * the requests loaded but not yet computed would exceed `capacity` (they are pinned until
+ * their stitch).  b_m = 0 gives the schedule without overlap.
+ *   table_ids, cu_tables   HOST, request i uses table_ids[cu_tables[i] .. cu_tables[i+1]).
+ *   steps_out              HOST, room for `cap` steps; ceil(n_queries / b_c) are written.
+ * Returns the number of steps, or a negative tc_status: TC_ERR_INVALID (null pointers,
+ * b_c < 1, b_m < 0, cap too small), TC_ERR_CAPACITY (one micro-batch of b_c requests names
+ * more than `capacity` distinct tables).
+ */
+typedef struct tc_pipe_step {
+    int32_t compute_begin, compute_end;
+    int32_t demand_begin, demand_end;
+    int32_t prefetch_begin, prefetch_end;
+} tc_pipe_step;
+int32_t tc_plan_pipeline(const int32_t *table_ids, const int32_t *cu_tables, int32_t n_queries,
+                         int32_t capacity, int32_t b_c, int32_t b_m, tc_pipe_step *steps_out, int32_t cap);
+
 const char *tc_last_error(const tc_ctx *ctx);
 /* Library version string. */
 const char *tc_version(void);

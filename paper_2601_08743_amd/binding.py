@@ -13,6 +13,10 @@ import os
 from typing import Optional, Sequence, Tuple
 
 import numpy as np
+# torch first, always: the library needs libamdhip64.so.7 and must bind to the copy torch ships and
+# has initialised.  Loaded before torch, it would pull in the system's copy instead, the process
+# would hold two HIP runtimes, and the second one finds no device.
+import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtablecache.so")
@@ -34,7 +38,8 @@ EXPORTS = ["tc_block_bytes", "tc_pool_bytes", "tc_first_seq_block", "tc_create",
            "tc_register_table_kv", "tc_load_async", "tc_load_trace", "tc_is_resident",
            "tc_stitch_kv", "tc_stitch_kv_rope", "tc_prefill_attn", "tc_release_seqs", "tc_read_seq_kv",
            "tc_kv_splits", "tc_set_kv_splits", "tc_set_row_blocks", "tc_set_attn_kernel", "tc_attn_kernel", "tc_profile_enable", "tc_profile_read", "tc_last_error", "tc_version",
-           "tc_trie_create", "tc_trie_destroy", "tc_trie_insert", "tc_trie_match", "tc_rerank"]
+           "tc_trie_create", "tc_trie_destroy", "tc_trie_insert", "tc_trie_match", "tc_rerank",
+           "tc_pin_tables", "tc_unpin_tables", "tc_plan_pipeline"]
 
 
 class tc_config(ctypes.Structure):
@@ -78,6 +83,9 @@ _sig = {
     "tc_trie_insert": (_i32, [_vp, _i32, _vp, _i32]),
     "tc_trie_match": (_i32, [_vp, _vp, _i32, _vp, _vp, _i32]),
     "tc_rerank": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp]),
+    "tc_pin_tables": (_i32, [_vp, _vp, _i32]),
+    "tc_unpin_tables": (_i32, [_vp, _vp, _i32]),
+    "tc_plan_pipeline": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32]),
 }
 for _n, (_r, _a) in _sig.items():
     getattr(_lib, _n).restype = _r
@@ -170,6 +178,14 @@ class Context:
     def tc_load_async(self, table_ids, l0: int, l1: int, stream=None):
         ids = _i32arr(table_ids)
         self._check(_lib.tc_load_async(self._h, ids.ctypes.data, ids.size, l0, l1, _stream(stream)))
+
+    def tc_pin_tables(self, table_ids):
+        ids = _i32arr(table_ids)
+        self._check(_lib.tc_pin_tables(self._h, ids.ctypes.data, ids.size))
+
+    def tc_unpin_tables(self, table_ids):
+        ids = _i32arr(table_ids)
+        self._check(_lib.tc_unpin_tables(self._h, ids.ctypes.data, ids.size))
 
     def tc_load_trace(self, cap: int = 1 << 16) -> np.ndarray:
         out = np.zeros((cap, 3), dtype=np.int32)
@@ -304,3 +320,16 @@ def tc_rerank(table_ids, cu_tables, n_tables: int, anchor: int) -> np.ndarray:
     if rc != TC_OK:
         raise TcError(rc, "tc_rerank")
     return order[:n]
+
+
+def tc_plan_pipeline(table_ids, cu_tables, capacity: int, b_c: int, b_m: int) -> np.ndarray:
+    """Steps as an int32 array [n_steps, 6]: compute, demand and prefetch ranges (begin, end)."""
+    ids, cu = _i32arr(table_ids), _i32arr(cu_tables)
+    n = cu.size - 1
+    cap = max(1, -(-n // max(int(b_c), 1)))
+    steps = np.zeros((cap, 6), dtype=np.int32)
+    rc = _lib.tc_plan_pipeline(ids.ctypes.data if ids.size else None, cu.ctypes.data, n, int(capacity), int(b_c),
+                               int(b_m), steps.ctypes.data, cap)
+    if rc < 0:
+        raise TcError(rc, "tc_plan_pipeline")
+    return steps[:rc]

@@ -131,4 +131,58 @@ tc_status tc_rerank(const int32_t *table_ids, const int32_t *cu_tables, int32_t 
     return TC_OK;
 }
 
+// Sec. 4.2.2.  The window of requests whose tables are on the device (or on their way) but
+// whose stitch has not been issued slides over the ordered batch; `held` counts, per table, the
+// window's requests that use it, so its size is the number of slots the window pins.
+int32_t tc_plan_pipeline(const int32_t *table_ids, const int32_t *cu_tables, int32_t n_queries,
+                         int32_t capacity, int32_t b_c, int32_t b_m, tc_pipe_step *steps_out, int32_t cap)
+{
+    if (n_queries < 0 || capacity < 0 || b_c < 1 || b_m < 0 || cap < 0) return TC_ERR_INVALID;
+    if (n_queries == 0) return 0;
+    if (!cu_tables || cu_tables[0] != 0) return TC_ERR_INVALID;
+    for (int32_t i = 0; i < n_queries; ++i)
+        if (cu_tables[i + 1] < cu_tables[i]) return TC_ERR_INVALID;
+    if (cu_tables[n_queries] > 0 && !table_ids) return TC_ERR_INVALID;
+    const int32_t n_steps = (n_queries + b_c - 1) / b_c;
+    if (n_steps > cap || !steps_out) return TC_ERR_INVALID;
+
+    std::unordered_map<int32_t, int32_t> held;
+    auto add = [&](int32_t i) { for (int32_t k = cu_tables[i]; k < cu_tables[i + 1]; ++k) ++held[table_ids[k]]; };
+    auto drop = [&](int32_t i) {
+        for (int32_t k = cu_tables[i]; k < cu_tables[i + 1]; ++k) {
+            auto it = held.find(table_ids[k]);
+            if (--it->second == 0) held.erase(it);
+        }
+    };
+    auto fresh = [&](int32_t i) {      // tables of request i the window does not hold yet
+        int32_t n = 0;
+        for (int32_t k = cu_tables[i]; k < cu_tables[i + 1]; ++k) {
+            bool seen = held.count(table_ids[k]) != 0;
+            for (int32_t j = cu_tables[i]; j < k && !seen; ++j) seen = table_ids[j] == table_ids[k];
+            n += seen ? 0 : 1;
+        }
+        return n;
+    };
+
+    int32_t frontier = 0;              // requests [0, frontier) have been asked for
+    for (int32_t s = 0; s < n_steps; ++s) {
+        tc_pipe_step &st = steps_out[s];
+        st.compute_begin = s * b_c;
+        st.compute_end = st.compute_begin + b_c < n_queries ? st.compute_begin + b_c : n_queries;
+        st.demand_begin = frontier;
+        while (frontier < st.compute_end) {
+            if ((int64_t)held.size() + fresh(frontier) > capacity) return TC_ERR_CAPACITY;
+            add(frontier++);
+        }
+        st.demand_end = frontier;
+        for (int32_t i = st.compute_begin; i < st.compute_end; ++i) drop(i);   // stitched: no longer held
+        st.prefetch_begin = frontier;
+        const int64_t want = (int64_t)st.compute_end + b_m;
+        while (frontier < n_queries && frontier < want && (int64_t)held.size() + fresh(frontier) <= capacity)
+            add(frontier++);
+        st.prefetch_end = frontier;
+    }
+    return n_steps;
+}
+
 }  // extern "C"

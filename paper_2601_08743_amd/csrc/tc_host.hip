@@ -24,13 +24,16 @@ namespace {
 
 // ------------------------------------------------------------------ replacement rules (App. A)
 // Each rule answers three questions about the set of cached tables: is the request cached,
-// what happens on a hit, and who goes when a miss finds the cache full.
+// what happens on a hit, and who goes when a miss finds the cache full.  Tables a caller has
+// pinned are passed over: the victim is the rule's first choice among the others (-1: none left).
+using PinMap = std::unordered_map<int32_t, int32_t>;
+
 class Replacement {
 public:
     virtual ~Replacement() {}
     virtual bool cached(int32_t id) const = 0;
     virtual void on_hit(int32_t id) = 0;
-    virtual int32_t pick_victim() const = 0;       // cache is non-empty
+    virtual int32_t pick_victim(const PinMap &pins) const = 0;
     virtual void remove(int32_t id) = 0;
     virtual void insert(int32_t id) = 0;
     virtual size_t size() const = 0;
@@ -44,7 +47,10 @@ class LruRule : public Replacement {
 public:
     bool cached(int32_t id) const override { return pos_.count(id) != 0; }
     void on_hit(int32_t id) override { order_.splice(order_.begin(), order_, pos_[id]); }
-    int32_t pick_victim() const override { return order_.back(); }
+    int32_t pick_victim(const PinMap &pins) const override {
+        for (auto it = order_.rbegin(); it != order_.rend(); ++it) if (!pins.count(*it)) return *it;
+        return -1;
+    }
     void remove(int32_t id) override { order_.erase(pos_[id]); pos_.erase(id); }
     void insert(int32_t id) override { order_.push_front(id); pos_[id] = order_.begin(); }
     size_t size() const override { return pos_.size(); }
@@ -57,7 +63,10 @@ class FifoRule : public Replacement {
 public:
     bool cached(int32_t id) const override { return pos_.count(id) != 0; }
     void on_hit(int32_t) override {}
-    int32_t pick_victim() const override { return queue_.front(); }
+    int32_t pick_victim(const PinMap &pins) const override {
+        for (int32_t id : queue_) if (!pins.count(id)) return id;
+        return -1;
+    }
     void remove(int32_t id) override { queue_.erase(pos_[id]); pos_.erase(id); }
     void insert(int32_t id) override { queue_.push_back(id); pos_[id] = std::prev(queue_.end()); }
     size_t size() const override { return pos_.size(); }
@@ -72,10 +81,11 @@ public:
     void tick() override { ++clock_; }
     bool cached(int32_t id) const override { return stat_.count(id) != 0; }
     void on_hit(int32_t id) override { Stat &s = stat_[id]; s.freq += 1; s.stamp = clock_; }
-    int32_t pick_victim() const override {
+    int32_t pick_victim(const PinMap &pins) const override {
         int32_t best = -1; Stat bs{0, 0};
         for (const auto &kv : stat_)
-            if (best < 0 || kv.second.freq < bs.freq ||
+            if (pins.count(kv.first)) continue;
+            else if (best < 0 || kv.second.freq < bs.freq ||
                 (kv.second.freq == bs.freq && kv.second.stamp < bs.stamp)) { best = kv.first; bs = kv.second; }
         return best;
     }
@@ -124,6 +134,7 @@ struct tc_ctx {
     int64_t first_seq = 0;
     std::unordered_map<int32_t, Table> tables;
     std::unique_ptr<Replacement> rule;
+    PinMap pins;                           // table -> pin count (> 0)
     std::vector<Slot> slots;
     std::set<int32_t> free_slots;
     std::set<int32_t> free_seq;            // free sequence blocks, ordered
@@ -587,7 +598,10 @@ tc_status tc_load_async(tc_ctx *ctx, const int32_t *table_ids, int32_t n, int32_
             ctx->rule->on_hit(id);
         } else {
             if ((int64_t)ctx->rule->size() >= ctx->cfg.table_capacity) {
-                evicted = ctx->rule->pick_victim();
+                evicted = ctx->rule->pick_victim(ctx->pins);
+                if (evicted < 0)
+                    return fail(ctx, TC_ERR_CAPACITY, "load: table %d needs a slot and all %d cached tables are pinned",
+                                id, (int)ctx->cfg.table_capacity);
                 ctx->rule->remove(evicted);
                 Table &v = ctx->tables[evicted];
                 ctx->free_slots.insert(v.slot);
@@ -631,6 +645,30 @@ tc_status tc_load_async(tc_ctx *ctx, const int32_t *table_ids, int32_t n, int32_
         sl.ready_stream = stream;
         sl.ready_pending = true;
     }
+    return TC_OK;
+}
+
+tc_status tc_pin_tables(tc_ctx *ctx, const int32_t *table_ids, int32_t n)
+{
+    if (!ctx) return TC_ERR_INVALID;
+    if (n < 0 || (n > 0 && !table_ids)) return fail(ctx, TC_ERR_INVALID, "pin: bad id list");
+    for (int k = 0; k < n; ++k)
+        if (!ctx->tables.count(table_ids[k])) return fail(ctx, TC_ERR_UNKNOWN_TABLE, "pin: table %d not registered", table_ids[k]);
+    for (int k = 0; k < n; ++k) ctx->pins[table_ids[k]] += 1;
+    return TC_OK;
+}
+
+tc_status tc_unpin_tables(tc_ctx *ctx, const int32_t *table_ids, int32_t n)
+{
+    if (!ctx) return TC_ERR_INVALID;
+    if (n < 0 || (n > 0 && !table_ids)) return fail(ctx, TC_ERR_INVALID, "unpin: bad id list");
+    PinMap left = ctx->pins;           // all or nothing: check the whole list on a copy first
+    for (int k = 0; k < n; ++k) {
+        auto it = left.find(table_ids[k]);
+        if (it == left.end()) return fail(ctx, TC_ERR_INVALID, "unpin: table %d is not pinned (that often)", table_ids[k]);
+        if (--it->second == 0) left.erase(it);
+    }
+    ctx->pins.swap(left);
     return TC_OK;
 }
 

@@ -1,0 +1,45 @@
+"""Host loop of the computation-loading pipeline (Sec. 4.2.2) over the C ABI.
+
+The schedule comes from ``tc_plan_pipeline``; this module only carries it out: which library call
+is made when.  A range of requests is "asked for" by pinning all its tables and then requesting
+them, in batch order, on the load stream; a micro-batch is unpinned as soon as its stitch is
+enqueued (the library orders later copies into its slots behind that stitch).
+"""
+from __future__ import annotations
+
+from typing import Callable, Sequence
+
+import numpy as np
+
+from . import binding as B
+
+
+def flat_tables(queries: Sequence[np.ndarray], a: int, b: int) -> np.ndarray:
+    if b <= a:
+        return np.zeros(0, dtype=np.int32)
+    return np.concatenate([np.asarray(q, dtype=np.int32) for q in queries[a:b]]).astype(np.int32)
+
+
+def plan(queries: Sequence[np.ndarray], capacity: int, b_c: int, b_m: int) -> np.ndarray:
+    ids = flat_tables(queries, 0, len(queries))
+    cu = np.concatenate([[0], np.cumsum([len(q) for q in queries])]).astype(np.int32)
+    return B.tc_plan_pipeline(ids, cu, capacity, b_c, b_m)
+
+
+def run(ctx: "B.Context", queries: Sequence[np.ndarray], steps: np.ndarray, l0: int, l1: int, load_stream,
+        stitch: Callable[[int, int], object], layers: Callable[[int, int, object], None]) -> None:
+    """Carry out `steps`.  `stitch(c0, c1)` must enqueue the stitch of requests [c0, c1) and return
+    whatever `layers(c0, c1, handle)` needs to run their attention layers and release them."""
+
+    def ask(a: int, b: int) -> None:
+        ids = flat_tables(queries, a, b)
+        if ids.size:
+            ctx.tc_pin_tables(ids)
+            ctx.tc_load_async(ids, l0, l1, load_stream)
+
+    for c0, c1, d0, d1, p0, p1 in np.asarray(steps).tolist():
+        ask(d0, d1)
+        handle = stitch(c0, c1)
+        ctx.tc_unpin_tables(flat_tables(queries, c0, c1))
+        ask(p0, p1)
+        layers(c0, c1, handle)

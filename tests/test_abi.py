@@ -60,3 +60,18 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode == 2 and "one GPU" in r.stderr
+
+
+def test_binding_shares_the_hip_runtime_with_torch():
+    """Importing the binding in a fresh interpreter, before anything else, must leave exactly one
+    HIP runtime mapped into the process: the one torch ships.  (Loaded ahead of torch, the library
+    would bring in the system's copy, and with two runtimes the second sees no device.)"""
+    import subprocess
+    import sys
+    code = ("import paper_2601_08743_amd.binding, torch, os\n"
+            "maps = {l.split()[-1] for l in open('/proc/self/maps') if 'libamdhip64' in l}\n"
+            "print(sorted(maps))\n"
+            "assert len(maps) == 1, maps\n"
+            "assert os.path.dirname(torch.__file__) in next(iter(maps)), maps\n")
+    r = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout + r.stderr

@@ -115,3 +115,47 @@ def test_workload_prompts_resolve_to_their_tables():
         assert [p for _, p in m][:len(ids)] == starts
         assert m == oracle.trie_match({t: wl.table_tokens(t).tolist() for t in range(wl.cfg.n_tables)},
                                       wl.prompt_tokens(i).tolist())
+
+
+# ------------------------------------------------------------------------------------ pipeline schedule
+
+def _flat(sets):
+    ids = np.asarray([t for q in sets for t in q], dtype=np.int32)
+    cu = np.concatenate([[0], np.cumsum([len(q) for q in sets])]).astype(np.int32)
+    return ids, cu
+
+
+def test_pipeline_plan_equals_the_checker():
+    """Sec. 4.2.2: the library's schedule (incremental window bookkeeping) against the checker's
+    (set unions written out), on random batches including empty requests, repeated tables inside a
+    request, b_m = 0 and windows cut short by the cache size."""
+    rng = np.random.default_rng(21)
+    n_err = 0
+    for trial in range(300):
+        n = int(rng.integers(0, 50))
+        sets = [rng.integers(0, 14, size=int(rng.integers(0, 5))).tolist() for _ in range(n)]
+        b_c, b_m, C = int(rng.integers(1, 7)), int(rng.integers(0, 12)), int(rng.integers(3, 15))
+        ids, cu = _flat(sets)
+        try:
+            want = oracle.plan_pipeline(sets, C, b_c, b_m)
+        except ValueError:
+            with pytest.raises(B.TcError) as e:
+                B.tc_plan_pipeline(ids, cu, C, b_c, b_m)
+            assert e.value.code == B.TC_ERR_CAPACITY
+            n_err += 1
+            continue
+        got = B.tc_plan_pipeline(ids, cu, C, b_c, b_m)
+        assert [tuple(r) for r in got.tolist()] == want, (trial, sets, C, b_c, b_m)
+    assert 10 < n_err < 200          # both outcomes were exercised
+
+
+def test_pipeline_plan_rejects_bad_arguments():
+    ids, cu = _flat([[0, 1], [2]])
+    for C, b_c, b_m in ((4, 0, 1), (4, 1, -1), (-1, 1, 1)):
+        with pytest.raises(B.TcError) as e:
+            B.tc_plan_pipeline(ids, cu, C, b_c, b_m)
+        assert e.value.code == B.TC_ERR_INVALID
+    with pytest.raises(B.TcError):
+        B.tc_plan_pipeline(ids, [1, 2, 3], 4, 1, 1)            # offsets must start at 0
+    with pytest.raises(B.TcError):
+        B.tc_plan_pipeline(ids, [0, 2, 1], 4, 1, 1)            # and not decrease

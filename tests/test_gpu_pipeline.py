@@ -1,0 +1,157 @@
+"""GPU: the computation-loading pipeline of Sec. 4.2.2 carried out through the C ABI under the
+three replacement rules of App. A, with and without the reranking of Sec. 4.2.1.  Checked against
+the CPU checker: the schedule, the (table, hit, evicted) trace with pinned tables, every stitched
+sequence bit for bit (tables arrive from pinned host memory while earlier micro-batches are being
+computed, in slots that are being reused), and the attention outputs of one layer."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2601_08743_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import harness
+    assert torch.cuda.is_available()
+    return harness
+
+
+def _cfg(**kw):
+    base = dict(name="p", n_layers=2, n_q_heads=8, n_kv_heads=2, head_dim=128, dtype="bf16", n_tables=16,
+                table_len=(5, 70), batch=20, tables_per_query=(1, 2), choice="uniform", suffix_len=(1, 20),
+                capacity=6, seed=31)
+    base.update(kw)
+    return W.WorkloadConfig(**base)
+
+
+POLICIES = [("lru", 0, oracle.LRUModel), ("fifo", 1, oracle.FIFOModel), ("lfu", 2, oracle.LFUModel)]
+
+
+@pytest.mark.parametrize("name,policy,Model", POLICIES)
+@pytest.mark.parametrize("b_c,b_m", [(2, 2), (2, 0), (1, 4), (3, 1)])
+@pytest.mark.parametrize("rerank", [False, True])
+def test_pipeline_trace_and_stitches(H, name, policy, Model, b_c, b_m, rerank):
+    from paper_2601_08743_amd import binding as B
+    from paper_2601_08743_amd import pipeline as PL
+    wl = W.make_workload(_cfg())
+    c = wl.cfg
+    order = list(range(c.batch))
+    if rerank:
+        order = B.tc_rerank(wl.table_ids, wl.cu_tables, c.n_tables, 0).tolist()
+        assert order == oracle.rerank([q.tolist() for q in wl.queries], 0)
+    queries = [wl.queries[i] for i in order]
+    sets = [q.tolist() for q in queries]
+    steps = PL.plan(queries, c.capacity, b_c, b_m)
+    want_steps = oracle.plan_pipeline(sets, c.capacity, b_c, b_m)
+    assert [tuple(r) for r in steps.tolist()] == want_steps
+
+    dw = H.DeviceWorkload(wl, load_all=False, capacity=c.capacity, policy=policy)
+    s_load = torch.cuda.Stream()
+    q_l, k_l, v_l = wl.suffix_qkv(1)
+    dq, dk, dv = (H.to_dev(x, c) for x in (q_l, k_l, v_l))
+    cu = wl.cu_seqlens
+    worst = 0.0
+
+    def stitch(c0, c1):
+        mb = order[c0:c1]
+        ids = PL.flat_tables(queries, c0, c1)
+        cu_t = np.concatenate([[0], np.cumsum([len(q) for q in queries[c0:c1]])]).astype(np.int32)
+        sl = wl.suffix_len[mb].astype(np.int32)
+        bt, pl = dw.ctx.tc_stitch_kv(ids, cu_t, sl, 16, None)
+        return mb, bt, pl, sl
+
+    def layers(c0, c1, h):
+        nonlocal worst
+        mb, bt, pl, sl = h
+        # gather the micro-batch's suffix rows (the requests are not contiguous after reranking)
+        rows = np.concatenate([np.arange(cu[i], cu[i + 1]) for i in mb]).astype(np.int64)
+        ridx = torch.from_numpy(rows).cuda()
+        q_mb, k_mb, v_mb = dq[ridx].contiguous(), dk[ridx].contiguous(), dv[ridx].contiguous()
+        out = torch.full_like(q_mb, float("nan"))
+        cs = np.concatenate([[0], np.cumsum(sl)]).astype(np.int32)
+        for layer in (0, 1):
+            dw.ctx.tc_prefill_attn(layer, q_mb, k_mb, v_mb, out, cs, bt, pl, sl, wl.sm_scale, None)
+        torch.cuda.synchronize()
+        got = H.out_to_f64(out, c)
+        ref = H.oracle_attn_layer(wl, dw.tables_np, 1, (q_l, k_l, v_l), mb)
+        for j, i in enumerate(mb):
+            P, S = int(pl[j]), int(sl[j])
+            assert P == int(wl.table_len[wl.queries[i]].sum())
+            for layer in (0, 1):
+                k, v = dw.ctx.tc_read_seq_kv(layer, bt[j, :-(-(P + S) // 16)], P + S, H.np_dtype(c))
+                ks, vs = H.oracle_sequences(wl, dw.tables_np, layer, i)
+                np.testing.assert_array_equal(k[:P].view(np.uint8), ks.view(np.uint8))
+                np.testing.assert_array_equal(v[:P].view(np.uint8), vs.view(np.uint8))
+            worst = max(worst, float(np.abs(got[cs[j]:cs[j + 1]] - ref[i]).max()))
+        dw.ctx.tc_release_seqs(bt)
+
+    PL.run(dw.ctx, queries, steps, 0, c.n_layers, s_load, stitch, layers)
+    torch.cuda.synchronize()
+    got = [tuple(r) for r in dw.ctx.tc_load_trace().tolist()]
+    assert got == oracle.simulate_pipeline(Model(c.capacity), sets, want_steps)
+    assert worst <= 1e-2, worst
+    # everything was unpinned again: a full sweep over other tables can evict every slot
+    dw.ctx.tc_load_async(list(range(c.n_tables)), 0, c.n_layers, s_load)
+    torch.cuda.synchronize()
+    dw.close()
+
+
+def test_reranking_lowers_misses_in_the_pipeline(H):
+    """Sec. 4.2.1 with Sec. 4.2.2: on a batch drawn from a few groups of tables, visited in
+    reranked order the pipeline misses less than in arrival order, under each rule."""
+    from paper_2601_08743_amd import binding as B
+    from paper_2601_08743_amd import pipeline as PL
+    rng = np.random.default_rng(4)
+    groups = [rng.choice(16, size=3, replace=False) for _ in range(4)]
+    wl = W.make_workload(_cfg(batch=24, tables_per_query=(3, 3), capacity=4))
+    for i in range(24):
+        wl.queries[i] = groups[int(rng.integers(0, 4))].astype(np.int32)
+    ids = np.concatenate(wl.queries).astype(np.int32)
+    cu_t = np.arange(0, 3 * 24 + 1, 3, dtype=np.int32)
+    for name, policy, Model in POLICIES:
+        misses = {}
+        for rerank in (False, True):
+            order = B.tc_rerank(ids, cu_t, 16, 0).tolist() if rerank else list(range(24))
+            queries = [wl.queries[i] for i in order]
+            steps = PL.plan(queries, 4, 1, 1)
+            dw = H.DeviceWorkload(wl, load_all=False, capacity=4, policy=policy)
+            PL.run(dw.ctx, queries, steps, 0, 2, None,
+                   lambda c0, c1: None, lambda c0, c1, h: None)
+            tr = dw.ctx.tc_load_trace()
+            misses[rerank] = int((tr[:, 1] == 0).sum())
+            want = oracle.simulate_pipeline(Model(4), [q.tolist() for q in queries],
+                                            oracle.plan_pipeline([q.tolist() for q in queries], 4, 1, 1))
+            assert [tuple(r) for r in tr.tolist()] == want
+            dw.close()
+        assert misses[True] < misses[False], (name, misses)
+
+
+def test_pins_are_counted_and_errors_change_nothing(H):
+    from paper_2601_08743_amd import binding as B
+    wl = W.make_workload(_cfg(batch=1))
+    dw = H.DeviceWorkload(wl, load_all=False, capacity=2, policy=2)
+    ctx = dw.ctx
+    ctx.tc_pin_tables([0, 1, 0])
+    ctx.tc_load_async([0, 1], 0, 2)
+    with pytest.raises(B.TcError) as e:
+        ctx.tc_load_async([2], 0, 2)                   # both cached tables are pinned
+    assert e.value.code == B.TC_ERR_CAPACITY
+    assert ctx.tc_is_resident(0, 0, 2) and ctx.tc_is_resident(1, 0, 2) and not ctx.tc_is_resident(2, 0, 2)
+    ctx.tc_unpin_tables([0])
+    with pytest.raises(B.TcError):
+        ctx.tc_load_async([2], 0, 2)                   # 0 is still pinned once
+    with pytest.raises(B.TcError) as e:
+        ctx.tc_unpin_tables([1, 1])                    # pinned once only: nothing is unpinned
+    assert e.value.code == B.TC_ERR_INVALID
+    ctx.tc_unpin_tables([0])
+    ctx.tc_load_async([2], 0, 2)                       # 0 (older, same frequency) goes, 1 is pinned
+    assert not ctx.tc_is_resident(0, 0, 2) and ctx.tc_is_resident(1, 0, 2) and ctx.tc_is_resident(2, 0, 2)
+    with pytest.raises(B.TcError) as e:
+        ctx.tc_pin_tables([99])
+    assert e.value.code == B.TC_ERR_UNKNOWN_TABLE
+    ctx.tc_unpin_tables([1])
+    dw.close()
