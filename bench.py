@@ -46,69 +46,43 @@ def read_traffic(workload):
 
 
 def bench_pipeline(args):
-    """Cold-cache loading pipeline (Sec. 4.2.2): micro-batches of queries; while the attention of
-    micro-batch k runs on the compute stream, the tables micro-batch k+1 misses are copied from
-    pinned host memory on a side stream.  Three timings from the same warm start (tables 0..C-1
-    resident): compute only (tables made resident beforehand, untimed), loads only, pipeline."""
+    """Cold-cache loading pipeline (Sec. 4.2.2): the ordered requests are computed b_c at a time on
+    the compute stream while the tables of the next b_m requests are copied from pinned host memory
+    on a side stream, following the schedule of tc_plan_pipeline.  Three timings from the same warm
+    start (tables 0..C-1 resident): the pipeline; the loads alone; the compute alone (same batches,
+    every copy finished before the clock starts).  With --ablation the same measurement is repeated
+    over the replacement rules of App. A, with and without the reranking of Sec. 4.2.1, with and
+    without overlap (b_m = 0), which gives the shape of the paper's ablation tables on a synthetic
+    trace: misses, pipeline time, and the load time the computation could not hide."""
     import torch
     from paper_2601_08743_amd import binding as B
+    from paper_2601_08743_amd import pipeline as PL
     from paper_2601_08743_amd import workloads as W
     wl = W.get(args.workload)
     c = wl.cfg
-    bc = args.micro_batch
+    b_c = args.micro_batch
+    b_m = b_c if args.prefetch < 0 else args.prefetch
     t_setup = time.time()
-    mbs = [list(range(i, min(i + bc, c.batch))) for i in range(0, c.batch, bc)]
-    P = np.array([int(wl.table_len[q].sum()) for q in wl.queries])
-    S = wl.suffix_len.astype(int)
-    need_mb = [sum(-(-(int(P[i]) + int(S[i])) // 16) for i in mb) for mb in mbs]
-    for mb in mbs:
-        assert len(set(np.concatenate([wl.queries[i] for i in mb]).tolist())) <= c.capacity, \
-            "a micro-batch must fit the table cache"
+    P_all = np.array([int(wl.table_len[q].sum()) for q in wl.queries])
+    S_all = wl.suffix_len.astype(int)
+    need = [-(-(int(p) + int(s)) // 16) for p, s in zip(P_all, S_all)]
     max_tok = int(wl.table_len.max())
-    n_blocks = c.capacity * (-(-max_tok // 16)) + 2 * max(need_mb) + 16
-    max_blocks = max(-(-(int(p) + int(s)) // 16) for p, s in zip(P, S)) + 1
-    cfg = B.make_config(c.n_layers, c.n_q_heads, c.n_kv_heads, c.head_dim, B.TC_BF16, n_blocks,
-                        c.capacity, max_tok)
-    pool = torch.empty(B.tc_pool_bytes(cfg), dtype=torch.uint8, device="cuda")
-    ctx = B.Context(cfg, pool)
-    s_main, s_load = torch.cuda.Stream(), torch.cuda.Stream()
+    n_blocks = c.capacity * (-(-max_tok // 16)) + 2 * b_c * max(need) + 16
+    max_blocks = max(need) + 1
+    pool, host_kv = None, []
     for t in range(c.n_tables):
         k, v = wl.table_kv(t)
-        ctx.tc_register_table_kv(t, int(wl.table_len[t]), torch.from_numpy(k).pin_memory(),
-                                 torch.from_numpy(v).pin_memory())
-    # suffix activations: two layers' worth of random q/k/v, reused cyclically by the 48 layers
+        host_kv.append((torch.from_numpy(k).pin_memory(), torch.from_numpy(v).pin_memory()))
+    s_main, s_load = torch.cuda.Stream(), torch.cuda.Stream()
+    # suffix activations: two layers' worth of random q/k/v, reused cyclically by the layers
     # (their values do not change what is timed)
     qkv = []
     for l in range(2):
         q, k, v = wl.suffix_qkv(l)
         qkv.append(tuple(torch.from_numpy(x).view(torch.bfloat16).cuda() for x in (q, k, v)))
     out = torch.empty_like(qkv[0][0])
-    cu = wl.cu_seqlens
-    setup_s = time.time() - t_setup
     L = c.n_layers
-
-    def warm():
-        ctx.tc_load_async(list(range(c.capacity - 1, -1, -1)), 0, L, s_load)   # table 0 most recent
-        torch.cuda.synchronize()
-        ctx.tc_load_trace()
-
-    def mb_args(mb):
-        ids = np.concatenate([wl.queries[i] for i in mb]).astype(np.int32)
-        cu_t = np.concatenate([[0], np.cumsum([len(wl.queries[i]) for i in mb])]).astype(np.int32)
-        sl = wl.suffix_len[mb].astype(np.int32)
-        cs = np.concatenate([[0], np.cumsum(sl)]).astype(np.int32)
-        return ids, cu_t, sl, cs, int(cu[mb[0]]), int(cu[mb[-1] + 1])
-
-    def compute(mb):
-        ids, cu_t, sl, cs, r0, r1 = mb_args(mb)
-        bt, pl = ctx.tc_stitch_kv(ids, cu_t, sl, max_blocks, s_main)
-        for l in range(L):
-            q, k, v = qkv[l & 1]
-            ctx.tc_prefill_attn(l, q[r0:r1], k[r0:r1], v[r0:r1], out[r0:r1], cs, bt, pl, sl, wl.sm_scale, s_main)
-        ctx.tc_release_seqs(bt)
-
-    def load(mb):
-        ctx.tc_load_async(np.concatenate([wl.queries[i] for i in mb]), 0, L, s_load)
+    setup_s = time.time() - t_setup
 
     def timed(fn):
         torch.cuda.synchronize()
@@ -117,57 +91,109 @@ def bench_pipeline(args):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3
 
-    # the pipeline proper: stitch(k) needs load(k) done; load(k+1) is enqueued right after stitch(k)
-    def run_pipeline():
-        load(mbs[0])
-        for k, mb in enumerate(mbs):
-            ids, cu_t, sl, cs, r0, r1 = mb_args(mb)
+    def case(policy, rerank, bc, bm, reps, warmup):
+        nonlocal pool
+        cfg = B.make_config(c.n_layers, c.n_q_heads, c.n_kv_heads, c.head_dim, B.TC_BF16, n_blocks,
+                            c.capacity, max_tok, policy)
+        if pool is None:
+            pool = torch.empty(B.tc_pool_bytes(cfg), dtype=torch.uint8, device="cuda")
+        ctx = None
+
+        def fresh():
+            """A new context over the same pool, tables 0..C-1 resident (table 0 most recent): every
+            phase of every repetition starts from the same cache and the same rule state."""
+            nonlocal ctx
+            if ctx is not None:
+                torch.cuda.synchronize()
+                ctx.tc_destroy()
+            ctx = B.Context(cfg, pool)
+            for t in range(c.n_tables):
+                ctx.tc_register_table_kv(t, int(wl.table_len[t]), host_kv[t][0], host_kv[t][1])
+            ctx.tc_load_async(list(range(c.capacity - 1, -1, -1)), 0, L, s_load)
+            torch.cuda.synchronize()
+            ctx.tc_load_trace()
+
+        order = list(range(c.batch))
+        if rerank:
+            order = B.tc_rerank(wl.table_ids, wl.cu_tables, c.n_tables, 0).tolist()
+        queries = [wl.queries[i] for i in order]
+        sl_all = wl.suffix_len[order].astype(np.int32)
+        cu_r = np.concatenate([[0], np.cumsum(sl_all)]).astype(np.int64)     # rows of the reordered batch
+        steps = PL.plan(queries, c.capacity, bc, bm)
+        steps_serial = PL.plan(queries, c.capacity, bc, 0)
+
+        def stitch(c0, c1):
+            ids = PL.flat_tables(queries, c0, c1)
+            cu_t = np.concatenate([[0], np.cumsum([len(q) for q in queries[c0:c1]])]).astype(np.int32)
+            sl = sl_all[c0:c1]
             bt, pl = ctx.tc_stitch_kv(ids, cu_t, sl, max_blocks, s_main)
-            if k + 1 < len(mbs):
-                load(mbs[k + 1])
+            return bt, pl, sl
+
+        def layers(c0, c1, h):
+            bt, pl, sl = h
+            cs = np.concatenate([[0], np.cumsum(sl)]).astype(np.int32)
+            r0, r1 = int(cu_r[c0]), int(cu_r[c1])
             for l in range(L):
                 q, kk, v = qkv[l & 1]
                 ctx.tc_prefill_attn(l, q[r0:r1], kk[r0:r1], v[r0:r1], out[r0:r1], cs, bt, pl, sl,
                                     wl.sm_scale, s_main)
             ctx.tc_release_seqs(bt)
 
-    def run_loads():
-        for mb in mbs:
-            load(mb)
+        t_compute = [0.0]
 
-    def run_compute():
-        tot = 0.0
-        for mb in mbs:
-            load(mb)
-            tot += timed(lambda: compute(mb))
-        return tot
+        def stitch_clocked(c0, c1):          # serial schedule: every copy is done before the clock starts
+            torch.cuda.synchronize()
+            t_compute.append(time.perf_counter())
+            return stitch(c0, c1)
 
-    res_p, res_l, res_c, misses, nbytes = [], [], [], 0, 0
-    for rep in range(args.steps + args.warmup):
-        warm(); tp = timed(run_pipeline)
-        tr = ctx.tc_load_trace()
-        warm(); tl = timed(run_loads); ctx.tc_load_trace()
-        warm(); tc_ = run_compute(); ctx.tc_load_trace()
-        if rep >= args.warmup:
-            res_p.append(tp); res_l.append(tl); res_c.append(tc_)
-            miss_ids = tr[tr[:, 1] == 0][:, 0]
-            misses = int(miss_ids.size)
-            nbytes = int(sum(int(wl.table_len[t]) for t in miss_ids)) * 2 * c.kv_row_bytes * L
-    T_p, T_l, T_c = float(np.median(res_p)), float(np.median(res_l)), float(np.median(res_c))
-    flops = attn_flops_per_layer(c, P, S) * L
+        def layers_clocked(c0, c1, h):
+            layers(c0, c1, h)
+            torch.cuda.synchronize()
+            t_compute[0] += (time.perf_counter() - t_compute.pop()) * 1e3
+
+        res_p, res_l, res_c, misses, nbytes = [], [], [], 0, 0
+        for rep in range(reps + warmup):
+            fresh()
+            tp = timed(lambda: PL.run(ctx, queries, steps, 0, L, s_load, stitch, layers))
+            tr = ctx.tc_load_trace()
+            fresh()
+            tl = timed(lambda: PL.run(ctx, queries, steps, 0, L, s_load, lambda a, b: None, lambda a, b, h: None))
+            fresh()
+            t_compute[0] = 0.0
+            PL.run(ctx, queries, steps_serial, 0, L, s_load, stitch_clocked, layers_clocked)
+            if rep >= warmup:
+                res_p.append(tp); res_l.append(tl); res_c.append(t_compute[0])
+                miss_ids = tr[tr[:, 1] == 0][:, 0]
+                misses = int(miss_ids.size)
+                nbytes = int(sum(int(wl.table_len[t]) for t in miss_ids)) * 2 * c.kv_row_bytes * L
+        torch.cuda.synchronize()
+        ctx.tc_destroy()
+        T_p, T_l, T_c = float(np.median(res_p)), float(np.median(res_l)), float(np.median(res_c))
+        return {"policy": ["lru", "fifo", "lfu"][policy], "rerank": bool(rerank), "b_c": bc, "b_m": bm,
+                "misses": misses, "h2d_bytes": nbytes, "t_pipeline_ms": round(T_p, 3), "t_loads_ms": round(T_l, 3),
+                "t_compute_ms": round(T_c, 3), "exposed_load_ms": round(T_p - T_c, 3)}
+
+    policy = {"lru": 0, "fifo": 1, "lfu": 2}[args.policy]
+    r = case(policy, args.rerank, b_c, b_m, args.steps, args.warmup)
+    T_p, T_l, T_c, nbytes = r["t_pipeline_ms"], r["t_loads_ms"], r["t_compute_ms"], r["h2d_bytes"]
+    ablation = None
+    if args.ablation:
+        ablation = [case(pol, rr, b_c, bm, 1, 1) for pol in (0, 1, 2) for rr in (False, True) for bm in (0, b_c)]
+    flops = attn_flops_per_layer(c, P_all, S_all) * L
     res = {
         "metric": "suffix prefill attn TFLOP/s (cold-cache pipeline: loads + stitch + per-layer attention)",
         "value": round(flops / (T_p * 1e-3) / 1e12, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(T_p, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s: L=%d Hq=%d Hkv=%d D=128, %d tables in pinned host memory, device cache C=%d (LRU, "
-                               "warm 0..%d), B=%d in micro-batches of %d, sum P=%d, S=%d" % (
-                                   c.name, L, c.n_q_heads, c.n_kv_heads, c.n_tables, c.capacity, c.capacity - 1,
-                                   c.batch, bc, int(P.sum()), int(S[0]))},
+        "config": {"workload": "%s: L=%d Hq=%d Hkv=%d D=128, %d tables in pinned host memory, device cache C=%d (%s, "
+                               "warm 0..%d), B=%d, b_c=%d, b_m=%d, reranking %s, sum P=%d, S=%d" % (
+                                   c.name, L, c.n_q_heads, c.n_kv_heads, c.n_tables, c.capacity, args.policy.upper(),
+                                   c.capacity - 1, c.batch, b_c, b_m, "on" if args.rerank else "off",
+                                   int(P_all.sum()), int(S_all[0]))},
         "prefill_ms_per_query": round(T_p / c.batch, 4),
         "t_compute_ms": round(T_c, 3), "t_loads_ms": round(T_l, 3), "t_pipeline_ms": round(T_p, 3),
-        "pipeline_over_max": round(T_p / max(T_c, T_l), 4), "exposed_compute_ms": round(T_p - T_l, 3),
-        "misses": misses, "h2d_bytes": nbytes,
+        "pipeline_over_max": round(T_p / max(T_c, T_l), 4), "exposed_load_ms": r["exposed_load_ms"],
+        "misses": r["misses"], "h2d_bytes": nbytes,
         "h2d_gbps_loads_only": round(nbytes / (T_l * 1e-3) / 1e9, 2),
         "h2d_gbps_in_pipeline": round(nbytes / (T_p * 1e-3) / 1e9, 2),
         "compute_tflops_no_loads": round(flops / (T_c * 1e-3) / 1e12, 2),
@@ -176,6 +202,8 @@ def bench_pipeline(args):
                      "note": "link-bound: the copies of a batch take longer than its compute"},
         "cpu_baseline": None, "setup_s": round(setup_s, 1),
     }
+    if ablation is not None:
+        res["ablation"] = ablation
     print(json.dumps(res))
 
 
@@ -215,7 +243,11 @@ def main():
     ap.add_argument("--row-blocks", type=int, default=0, help="force 128 (1) or 256 (2) rows per work-group")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the extra timing of the layer loop replayed as a HIP graph")
-    ap.add_argument("--micro-batch", type=int, default=8, help="queries per micro-batch (c5 pipeline)")
+    ap.add_argument("--micro-batch", type=int, default=8, help="b_c: requests computed per micro-batch (c5 pipeline)")
+    ap.add_argument("--prefetch", type=int, default=-1, help="b_m: requests loaded ahead (c5 pipeline; default b_c, 0 = no overlap)")
+    ap.add_argument("--policy", default="lru", choices=["lru", "fifo", "lfu"], help="replacement rule (c5 pipeline)")
+    ap.add_argument("--rerank", action="store_true", help="visit the batch in reranked order (c5 pipeline)")
+    ap.add_argument("--ablation", action="store_true", help="c5 pipeline: also run rules x reranking x overlap")
     ap.add_argument("--calibrate", action="store_true",
                     help="run one plain elementwise kernel of known size (reads 1 GiB, writes 1 GiB) before the "
                          "timed region, as the reference for scaling HBM counters of a --pmc run")

@@ -292,8 +292,11 @@ tc_status tc_rerank(const int32_t *table_ids, const int32_t *cu_tables, int32_t 
 /*
  * Computation-loading pipeline schedule (Sec. 4.2.2): the ordered requests are computed
  * in micro-batches of b_c while the tables of up to the next b_m requests are copied in.
- * Host only.  Step k computes requests [compute_begin, compute_end) = the k-th run of b_c.
- * Before its stitch the caller requests the tables of [demand_begin, demand_end) (those
+ * Host only.  The steps' compute ranges [compute_begin, compute_end) follow one another and
+ * cover the batch; each holds b_c requests, fewer at the end of the batch or where the
+ * distinct tables of b_c requests would not fit the cache together (the step is cut short
+ * and the next one starts there).
+ * Before a step's stitch the caller requests the tables of [demand_begin, demand_end) (those
  * of its requests that no earlier step prefetched: copies the computation has to wait
  * for); after its stitch is enqueued the caller unpins the step's tables and requests
  * those of [prefetch_begin, prefetch_end), which overlap the step's attention layers.
@@ -301,10 +304,10 @@ tc_status tc_rerank(const int32_t *table_ids, const int32_t *cu_tables, int32_t 
  * the requests loaded but not yet computed would exceed `capacity` (they are pinned until
  * their stitch).  b_m = 0 gives the schedule without overlap.
  *   table_ids, cu_tables   HOST, request i uses table_ids[cu_tables[i] .. cu_tables[i+1]).
- *   steps_out              HOST, room for `cap` steps; ceil(n_queries / b_c) are written.
+ *   steps_out              HOST, room for `cap` steps; n_queries always suffice.
  * Returns the number of steps, or a negative tc_status: TC_ERR_INVALID (null pointers,
- * b_c < 1, b_m < 0, cap too small), TC_ERR_CAPACITY (one micro-batch of b_c requests names
- * more than `capacity` distinct tables).
+ * b_c < 1, b_m < 0, cap too small), TC_ERR_CAPACITY (a single request names more than
+ * `capacity` distinct tables).
  */
 typedef struct tc_pipe_step {
     int32_t compute_begin, compute_end;

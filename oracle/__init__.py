@@ -276,19 +276,24 @@ def plan_pipeline(table_sets: Sequence[Sequence[int]], capacity: int, b_c: int, 
     `demand` are the requests of this micro-batch nobody has asked for yet (asked for right
     before its stitch), `prefetch` those asked for right after its stitch.  Requests asked for
     but not yet stitched keep their tables pinned, so a prefetch stops early where the union of
-    their tables would outgrow the cache."""
-    N, steps, asked = len(table_sets), [], 0
+    their tables would outgrow the cache; for the same reason a micro-batch holds fewer than b_c
+    requests where the tables of b_c would not fit together (the next one starts there)."""
+    N, steps, asked, c0 = len(table_sets), [], 0, 0
     uni = lambda a, b: set().union(*[set(map(int, x)) for x in table_sets[a:b]]) if b > a else set()
-    for c0 in range(0, N, b_c):
-        c1 = min(N, c0 + b_c)
-        if len(uni(c0, c1)) > capacity:
-            raise ValueError("micro-batch [%d,%d) needs more than %d tables at once" % (c0, c1, capacity))
-        d0, d1 = asked, max(asked, c1)
-        asked = d1
-        p0 = asked
+    while c0 < N:
+        full = min(N, c0 + b_c)
+        d0 = asked
+        # requests c0..asked-1 are here already; ask for more of this micro-batch while they fit
+        while asked < full and len(uni(c0, asked + 1)) <= capacity:
+            asked += 1
+        c1 = min(asked, full)
+        if c1 == c0:
+            raise ValueError("request %d alone needs more than %d tables" % (c0, capacity))
+        d1 = p0 = asked
         while asked < N and asked < c1 + b_m and len(uni(c1, asked + 1)) <= capacity:
             asked += 1
         steps.append((c0, c1, d0, d1, p0, asked))
+        c0 = c1
     return steps
 
 

@@ -326,7 +326,7 @@ def tc_plan_pipeline(table_ids, cu_tables, capacity: int, b_c: int, b_m: int) ->
     """Steps as an int32 array [n_steps, 6]: compute, demand and prefetch ranges (begin, end)."""
     ids, cu = _i32arr(table_ids), _i32arr(cu_tables)
     n = cu.size - 1
-    cap = max(1, -(-n // max(int(b_c), 1)))
+    cap = max(1, n)
     steps = np.zeros((cap, 6), dtype=np.int32)
     rc = _lib.tc_plan_pipeline(ids.ctypes.data if ids.size else None, cu.ctypes.data, n, int(capacity), int(b_c),
                                int(b_m), steps.ctypes.data, cap)

@@ -143,8 +143,7 @@ int32_t tc_plan_pipeline(const int32_t *table_ids, const int32_t *cu_tables, int
     for (int32_t i = 0; i < n_queries; ++i)
         if (cu_tables[i + 1] < cu_tables[i]) return TC_ERR_INVALID;
     if (cu_tables[n_queries] > 0 && !table_ids) return TC_ERR_INVALID;
-    const int32_t n_steps = (n_queries + b_c - 1) / b_c;
-    if (n_steps > cap || !steps_out) return TC_ERR_INVALID;
+    if (!steps_out && cap > 0) return TC_ERR_INVALID;
 
     std::unordered_map<int32_t, int32_t> held;
     auto add = [&](int32_t i) { for (int32_t k = cu_tables[i]; k < cu_tables[i + 1]; ++k) ++held[table_ids[k]]; };
@@ -165,22 +164,26 @@ int32_t tc_plan_pipeline(const int32_t *table_ids, const int32_t *cu_tables, int
     };
 
     int32_t frontier = 0;              // requests [0, frontier) have been asked for
-    for (int32_t s = 0; s < n_steps; ++s) {
-        tc_pipe_step &st = steps_out[s];
-        st.compute_begin = s * b_c;
-        st.compute_end = st.compute_begin + b_c < n_queries ? st.compute_begin + b_c : n_queries;
+    int32_t n_steps = 0;
+    for (int32_t c0 = 0; c0 < n_queries; ++n_steps) {
+        if (n_steps >= cap) return TC_ERR_INVALID;
+        tc_pipe_step &st = steps_out[n_steps];
+        const int64_t full = (int64_t)c0 + b_c < n_queries ? c0 + b_c : n_queries;
+        st.compute_begin = c0;
         st.demand_begin = frontier;
-        while (frontier < st.compute_end) {
-            if ((int64_t)held.size() + fresh(frontier) > capacity) return TC_ERR_CAPACITY;
-            add(frontier++);
-        }
+        // the step takes what has been asked for already (at most b_c requests) and asks for more
+        // of its b_c requests while their tables still fit beside the ones held
+        while (frontier < full && (int64_t)held.size() + fresh(frontier) <= capacity) add(frontier++);
+        st.compute_end = frontier < full ? frontier : (int32_t)full;
+        if (st.compute_end == c0) return TC_ERR_CAPACITY;       // one request alone outgrows the cache
         st.demand_end = frontier;
-        for (int32_t i = st.compute_begin; i < st.compute_end; ++i) drop(i);   // stitched: no longer held
+        for (int32_t i = c0; i < st.compute_end; ++i) drop(i);  // stitched: no longer held
         st.prefetch_begin = frontier;
         const int64_t want = (int64_t)st.compute_end + b_m;
         while (frontier < n_queries && frontier < want && (int64_t)held.size() + fresh(frontier) <= capacity)
             add(frontier++);
         st.prefetch_end = frontier;
+        c0 = st.compute_end;
     }
     return n_steps;
 }

@@ -134,7 +134,7 @@ def test_pipeline_plan_equals_the_checker():
     for trial in range(300):
         n = int(rng.integers(0, 50))
         sets = [rng.integers(0, 14, size=int(rng.integers(0, 5))).tolist() for _ in range(n)]
-        b_c, b_m, C = int(rng.integers(1, 7)), int(rng.integers(0, 12)), int(rng.integers(3, 15))
+        b_c, b_m, C = int(rng.integers(1, 7)), int(rng.integers(0, 12)), int(rng.integers(2, 15))
         ids, cu = _flat(sets)
         try:
             want = oracle.plan_pipeline(sets, C, b_c, b_m)
@@ -146,7 +146,7 @@ def test_pipeline_plan_equals_the_checker():
             continue
         got = B.tc_plan_pipeline(ids, cu, C, b_c, b_m)
         assert [tuple(r) for r in got.tolist()] == want, (trial, sets, C, b_c, b_m)
-    assert 10 < n_err < 200          # both outcomes were exercised
+    assert 3 < n_err < 200           # both outcomes were exercised
 
 
 def test_pipeline_plan_rejects_bad_arguments():

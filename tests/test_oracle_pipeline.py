@@ -60,8 +60,17 @@ def test_plan_hand_worked():
     assert oracle.plan_pipeline(sets, 3, 2, 3) == [(0, 2, 0, 2, 2, 4), (2, 4, 4, 4, 4, 5), (4, 5, 5, 5, 5, 5)]
     # b_m smaller than b_c: the second half of each micro-batch is asked for on demand
     assert oracle.plan_pipeline(sets, 4, 2, 1) == [(0, 2, 0, 2, 2, 3), (2, 4, 3, 4, 4, 5), (4, 5, 5, 5, 5, 5)]
+    # C=2: requests 0,1 need three tables at once, so the first micro-batch is request 0 alone and
+    # only request 1 can be prefetched behind it ({1 2}; request 2 would add table 3).  Request 1 is
+    # then computed alone too (with request 2 it would need 1 2 3); behind it requests 2,3 (tables
+    # 3 0) are prefetched and computed together; request 4 (4 5) follows.
+    assert oracle.plan_pipeline(sets, 2, 2, 2) == [(0, 1, 0, 1, 1, 2), (1, 2, 2, 2, 2, 4), (2, 4, 4, 4, 4, 5),
+                                                   (4, 5, 5, 5, 5, 5)]
+    # C=3, b_c=3: requests 0,1 fit (0 1 2), request 2 (table 3) does not: cut short, and the prefetch
+    # of up to three requests stops after 2,3 (tables 3 0; request 4 would add two more)
+    assert oracle.plan_pipeline(sets, 3, 3, 3) == [(0, 2, 0, 2, 2, 4), (2, 4, 4, 4, 4, 5), (4, 5, 5, 5, 5, 5)]
     with pytest.raises(ValueError):
-        oracle.plan_pipeline(sets, 2, 2, 2)             # requests 0,1 need three tables at once
+        oracle.plan_pipeline(sets, 1, 2, 2)             # request 0 alone needs two tables
     assert oracle.plan_pipeline([], 4, 2, 2) == []
 
 
@@ -71,24 +80,29 @@ def _random_sets(rng, n, n_tables, kmax):
 
 def test_plan_properties():
     rng = np.random.default_rng(5)
-    for trial in range(200):
+    n_cut = 0
+    for trial in range(300):
         n = int(rng.integers(1, 40))
         sets = _random_sets(rng, n, 12, 4)
         b_c, b_m = int(rng.integers(1, 6)), int(rng.integers(0, 9))
-        C = int(rng.integers(4 * b_c if b_c < 3 else 12, 14))
+        C = int(rng.integers(4, 14))
         steps = oracle.plan_pipeline(sets, C, b_c, b_m)
-        asked = 0
-        for k, (c0, c1, d0, d1, p0, p1) in enumerate(steps):
-            assert (c0, c1) == (k * b_c, min(n, (k + 1) * b_c))
+        asked, nxt = 0, 0
+        uni = lambda a, b: set().union(*map(set, sets[a:b])) if b > a else set()
+        for c0, c1, d0, d1, p0, p1 in steps:
+            assert c0 == nxt and c0 < c1 <= min(n, c0 + b_c)   # in order, without gaps, at most b_c
+            assert len(uni(c0, c1)) <= C                       # the micro-batch fits the cache
+            if c1 < min(n, c0 + b_c):                          # cut short only for lack of room
+                assert len(uni(c0, c1 + 1)) > C
+                n_cut += 1
             assert d0 == asked and d1 == max(asked, c1) and p0 == d1 and p1 >= p0
             assert p1 <= max(c1 + b_m, p0)                     # never further ahead than b_m requests
-            held = set().union(*map(set, sets[c1:p1])) if p1 > c1 else set()
-            assert len(held) <= C                              # what stays pinned fits the cache
+            assert len(uni(c1, p1)) <= C                       # what stays pinned fits the cache
             if p1 < n and p1 < c1 + b_m:                       # stopped early only for lack of room
-                assert len(held | set(sets[p1])) > C
-            asked = p1
-        assert asked == n or steps[-1][1] == n
-        assert steps[-1][1] == n
+                assert len(uni(c1, p1 + 1)) > C
+            asked, nxt = p1, c1
+        assert nxt == n
+    assert n_cut > 20
 
 
 @pytest.mark.parametrize("cls", MODELS)
@@ -100,7 +114,7 @@ def test_simulated_pipeline_keeps_each_micro_batch_cached(cls):
         n = int(rng.integers(1, 30))
         sets = _random_sets(rng, n, 10, 3)
         b_c, b_m = int(rng.integers(1, 4)), int(rng.integers(0, 7))
-        C = int(rng.integers(3 * b_c, 11))
+        C = int(rng.integers(3, 11))
         steps = oracle.plan_pipeline(sets, C, b_c, b_m)
         for k, (c0, c1, d0, d1, p0, p1) in enumerate(steps):
             # the schedule up to step k's demand loads, with its stitch and prefetch cut off
