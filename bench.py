@@ -91,7 +91,7 @@ def bench_pipeline(args):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3
 
-    def case(policy, rerank, bc, bm, reps, warmup):
+    def case(policy, rerank, bc, bm, reps, warmup, serial=False):
         nonlocal pool
         cfg = B.make_config(c.n_layers, c.n_q_heads, c.n_kv_heads, c.head_dim, B.TC_BF16, n_blocks,
                             c.capacity, max_tok, policy)
@@ -154,7 +154,8 @@ def bench_pipeline(args):
         res_p, res_l, res_c, misses, nbytes = [], [], [], 0, 0
         for rep in range(reps + warmup):
             fresh()
-            tp = timed(lambda: PL.run(ctx, queries, steps, 0, L, s_load, stitch, layers))
+            tp = timed(lambda: PL.run(ctx, queries, steps, 0, L, s_load, stitch, layers,
+                                      torch.cuda.synchronize if serial else None))
             tr = ctx.tc_load_trace()
             fresh()
             tl = timed(lambda: PL.run(ctx, queries, steps, 0, L, s_load, lambda a, b: None, lambda a, b, h: None))
@@ -170,6 +171,7 @@ def bench_pipeline(args):
         ctx.tc_destroy()
         T_p, T_l, T_c = float(np.median(res_p)), float(np.median(res_l)), float(np.median(res_c))
         return {"policy": ["lru", "fifo", "lfu"][policy], "rerank": bool(rerank), "b_c": bc, "b_m": bm,
+                "overlap": not serial,
                 "misses": misses, "h2d_bytes": nbytes, "t_pipeline_ms": round(T_p, 3), "t_loads_ms": round(T_l, 3),
                 "t_compute_ms": round(T_c, 3), "exposed_load_ms": round(T_p - T_c, 3)}
 
@@ -178,7 +180,9 @@ def bench_pipeline(args):
     T_p, T_l, T_c, nbytes = r["t_pipeline_ms"], r["t_loads_ms"], r["t_compute_ms"], r["h2d_bytes"]
     ablation = None
     if args.ablation:
-        ablation = [case(pol, rr, b_c, bm, 1, 1) for pol in (0, 1, 2) for rr in (False, True) for bm in (0, b_c)]
+        # without overlap: b_m = 0 and the device idle before each micro-batch's loads are issued
+        ablation = [case(pol, rr, b_c, 0 if serial else b_m, 1, 1, serial)
+                    for pol in (0, 1, 2) for rr in (False, True) for serial in (True, False)]
     flops = attn_flops_per_layer(c, P_all, S_all) * L
     res = {
         "metric": "suffix prefill attn TFLOP/s (cold-cache pipeline: loads + stitch + per-layer attention)",
@@ -268,7 +272,7 @@ def main():
         torch.add(x, 1, out=y)
         torch.cuda.synchronize()
         del x, y
-    if args.workload == "c5":
+    if args.workload in ("c5", "c5db"):
         if args.steps == 50:
             args.steps, args.warmup = 3, 1
         return bench_pipeline(args)

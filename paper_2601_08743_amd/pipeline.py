@@ -27,9 +27,13 @@ def plan(queries: Sequence[np.ndarray], capacity: int, b_c: int, b_m: int) -> np
 
 
 def run(ctx: "B.Context", queries: Sequence[np.ndarray], steps: np.ndarray, l0: int, l1: int, load_stream,
-        stitch: Callable[[int, int], object], layers: Callable[[int, int, object], None]) -> None:
+        stitch: Callable[[int, int], object], layers: Callable[[int, int, object], None],
+        before_demand: Callable[[], None] = None) -> None:
     """Carry out `steps`.  `stitch(c0, c1)` must enqueue the stitch of requests [c0, c1) and return
-    whatever `layers(c0, c1, handle)` needs to run their attention layers and release them."""
+    whatever `layers(c0, c1, handle)` needs to run their attention layers and release them.
+    `before_demand()` is called ahead of each step's demand loads: a baseline without any overlap
+    waits there for the device to go idle (the host otherwise runs ahead, and even demand loads
+    overlap the previous step's layers)."""
 
     def ask(a: int, b: int) -> None:
         ids = flat_tables(queries, a, b)
@@ -38,6 +42,8 @@ def run(ctx: "B.Context", queries: Sequence[np.ndarray], steps: np.ndarray, l0: 
             ctx.tc_load_async(ids, l0, l1, load_stream)
 
     for c0, c1, d0, d1, p0, p1 in np.asarray(steps).tolist():
+        if before_demand is not None:
+            before_demand()
         ask(d0, d1)
         handle = stitch(c0, c1)
         ctx.tc_unpin_tables(flat_tables(queries, c0, c1))

@@ -41,12 +41,13 @@ class WorkloadConfig:
     table_len: Tuple[int, int]    # inclusive range, tokens
     batch: int
     tables_per_query: Tuple[int, int]   # inclusive range
-    choice: str                   # "uniform" | "zipf" | "all"
+    choice: str                   # "uniform" | "zipf" | "all" | "db"
     suffix_len: Tuple[int, int]   # inclusive range, tokens
     capacity: int                 # device table-cache capacity C, in tables
     seed: int
     block_size: int = BLOCK_SIZE
     zipf_s: float = 1.1
+    db_size: int = 0              # choice "db": tables per database (consecutive ids)
 
     @property
     def group(self) -> int:
@@ -78,6 +79,10 @@ CONFIGS = {
     # cold-cache loading pipeline: half of the tables fit on the device
     "c5": WorkloadConfig("c5", 48, 40, 8, 128, "bf16", 80, (150, 600), 64, (4, 12), "zipf",
                          (128, 128), 40, 1005),
+    # c5 with the structure of a Text-to-SQL service: the 80 tables belong to 8 databases of 10, a
+    # request names tables of one database only; 4 databases fit on the device
+    "c5db": WorkloadConfig("c5db", 48, 40, 8, 128, "bf16", 80, (150, 600), 64, (4, 10), "db",
+                           (128, 128), 40, 1006, db_size=10),
 }
 
 
@@ -201,6 +206,10 @@ def make_workload(cfg: WorkloadConfig) -> Workload:
             rng.shuffle(ids)
         elif cfg.choice == "zipf":
             ids = _zipf_pick(rng, cfg.n_tables, m, cfg.zipf_s)
+        elif cfg.choice == "db":
+            n_db = cfg.n_tables // cfg.db_size
+            db = int(_zipf_pick(rng, n_db, 1, cfg.zipf_s)[0])
+            ids = (db * cfg.db_size + rng.choice(cfg.db_size, size=min(m, cfg.db_size), replace=False)).astype(np.int32)
         else:
             raise ValueError(cfg.choice)
         queries.append(ids)
