@@ -64,6 +64,10 @@ enum {
 
 enum { TC_F32 = 0, TC_BF16 = 1 };
 enum { TC_POLICY_LRU = 0, TC_POLICY_FIFO = 1, TC_POLICY_LFU = 2 };
+/* How the device cache keeps a table: as registered (token rows; sequences are built by copying,
+ * tc_stitch_kv), or already in the pool's block layout, every table starting on a block of its own
+ * (sequences are built by pointing at those blocks, tc_stitch_alias; bf16 only). */
+enum { TC_SLOTS_ROWS = 0, TC_SLOTS_BLOCKS = 1 };
 
 typedef struct {
     int32_t n_layers;          /* L                                                          */
@@ -76,12 +80,14 @@ typedef struct {
     int32_t table_capacity;    /* C of App. A: how many tables the device cache holds        */
     int32_t max_table_tokens;  /* longest table that may be registered (sizes a slot)        */
     int32_t policy;            /* TC_POLICY_*                                                */
-    int32_t reserved;          /* 0                                                          */
+    int32_t slot_layout;       /* TC_SLOTS_*                                                 */
 } tc_config;
 
 /* Bytes of one block in one layer: 2 (K and V) * Hkv * block_size * D * sizeof(element). */
 size_t tc_block_bytes(const tc_config *cfg);
-/* Bytes the caller must allocate for the pool: n_layers * n_pool_blocks * tc_block_bytes.  0 if cfg is invalid. */
+/* Bytes the caller must allocate for the pool: n_layers * n_pool_blocks * tc_block_bytes, plus, with
+ * TC_SLOTS_BLOCKS, room for one table as registered (host copies land there before they are laid out
+ * into blocks).  0 if cfg is invalid. */
 size_t tc_pool_bytes(const tc_config *cfg);
 /* First sequence block = table_capacity * ceil(max_table_tokens / block_size).  -1 if cfg is invalid. */
 int64_t tc_first_seq_block(const tc_config *cfg);
@@ -173,6 +179,27 @@ int32_t tc_is_resident(const tc_ctx *ctx, int32_t table_id, int32_t l0, int32_t 
 tc_status tc_stitch_kv(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_tables, int32_t B,
                        const int32_t *suffix_len, int32_t *block_table, int32_t max_blocks,
                        int32_t *prefix_len, void *stream);
+
+/*
+ * Stitch without copying (contexts created with TC_SLOTS_BLOCKS).  Sec. 1 criticises prefix caches
+ * for keeping a copy of the shared schema per request; here the concatenation of Sec. 4.1.2 is made
+ * in the block table alone: query i's sequence lists, table by table in match order, the blocks of
+ * the slots that hold its tables, then ceil(S_i / 16) blocks of its own for the suffix.  No kernel
+ * runs and no table byte moves.  A table of n tokens fills ceil(n / 16) blocks; the unused positions
+ * at the end of its last block hold zero keys and values and take no part in attention (the library
+ * remembers where they are), so the sequence is as long as its blocks:
+ *   prefix_len[i] = 16 * (number of table blocks of query i)       (>= the sum of the table lengths)
+ * and this padded length is what tc_prefill_attn must be given.  Arguments and errors as for
+ * tc_stitch_kv; block_table entries below tc_first_seq_block are blocks of table slots (slot s owns
+ * s * ceil(max_table_tokens / 16) onwards).  Whatever is enqueued on `stream` afterwards runs after
+ * the loads of the tables it reads.  The tables must stay cached until the batch's last attention
+ * launch has been enqueued (pin them, tc_pin_tables); a later load that evicts one of them waits on
+ * its own stream for those launches.  tc_release_seqs gives back the suffix blocks only.
+ * Keys are used as stored: this entry point does not re-encode positions.
+ */
+tc_status tc_stitch_alias(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_tables, int32_t B,
+                          const int32_t *suffix_len, int32_t *block_table, int32_t max_blocks,
+                          int32_t *prefix_len, void *stream);
 
 /*
  * Stitch with positional re-encoding (Sec. 4.1.1, last paragraph: table KV is stored without

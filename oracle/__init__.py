@@ -13,6 +13,8 @@ Pieces and the passages they follow:
                         content) with the suffix causal to itself
 * ``SeqBlockModel``     the paged-pool bookkeeping the library documents: lowest
                         free block first, queries in batch order
+* ``SlotModel`` / ``alias_block_table``           the same concatenation without a copy: the
+                        sequence's block table points at the table slots' blocks
 * ``LRUModel`` / ``FIFOModel`` / ``LFUModel``   App. A, the three replacement rules
 * ``plan_pipeline`` / ``simulate_pipeline``      Sec. 4.2.2, micro-batches b_c / b_m
 
@@ -179,6 +181,49 @@ class SeqBlockModel:
             if b >= 0:
                 self.free.append(int(b))
         self.free.sort()
+
+
+class SlotModel:
+    """Which slot of the device cache holds which table, as the library documents it: on a miss the
+    table takes the lowest free slot, or, if the rule evicted a table, that table's slot.  Fed with
+    the (table, hit, evicted) trace of a replacement model."""
+
+    def __init__(self, capacity: int):
+        self.free = list(range(capacity))
+        self.slot: Dict[int, int] = {}
+
+    def apply(self, trace) -> None:
+        for t, hit, ev in trace:
+            if hit:
+                continue
+            s = self.slot.pop(int(ev)) if ev >= 0 else self.free.pop(0)
+            self.slot[int(t)] = s
+
+
+def alias_block_table(seq_model: "SeqBlockModel", slot_of: Dict[int, int], table_len: Sequence[int],
+                      queries: Sequence[Sequence[int]], suffix_len: Sequence[int], slot_blocks: int,
+                      max_blocks: int):
+    """Sec. 4.1.2's concatenation made in the block table alone (nothing is copied): query i lists,
+    table by table in match order, the blocks of the slots holding its tables (slot s owns blocks
+    s*slot_blocks ..; a table of n tokens uses the first ceil(n/16)), then ceil(S_i/16) fresh
+    sequence blocks for the suffix, lowest free first, queries in batch order.
+    Returns (block_table [B][max_blocks] with -1 for unused, padded prefix lengths [B],
+    valid [B] lists: how many token positions of each prefix block hold a token)."""
+    bs = seq_model.bs
+    bt = np.full((len(queries), max_blocks), -1, dtype=np.int32)
+    padded, valid = [], []
+    for i, q in enumerate(queries):
+        row, val = [], []
+        for t in q:
+            n = int(table_len[int(t)])
+            nb = -(-n // bs)
+            row += [slot_of[int(t)] * slot_blocks + j for j in range(nb)]
+            val += [bs] * (nb - 1) + [n - bs * (nb - 1)]
+        padded.append(bs * len(row))
+        valid.append(val)
+        row += [seq_model.free.pop(0) for _ in range(-(-int(suffix_len[i]) // bs))]
+        bt[i, :len(row)] = row
+    return bt, np.array(padded, dtype=np.int32), valid
 
 
 def prefix_lengths(table_len: Sequence[int], table_ids: Sequence[int], cu_tables: Sequence[int]):

@@ -33,10 +33,11 @@ TC_ERR_INVALID, TC_ERR_UNKNOWN_TABLE, TC_ERR_OOM_POOL = -1, -2, -3
 TC_ERR_NOT_RESIDENT, TC_ERR_CAPACITY, TC_ERR_HIP = -4, -5, -6
 TC_F32, TC_BF16 = 0, 1
 TC_POLICY_LRU, TC_POLICY_FIFO, TC_POLICY_LFU = 0, 1, 2
+TC_SLOTS_ROWS, TC_SLOTS_BLOCKS = 0, 1
 
 EXPORTS = ["tc_block_bytes", "tc_pool_bytes", "tc_first_seq_block", "tc_create", "tc_destroy",
            "tc_register_table_kv", "tc_load_async", "tc_load_trace", "tc_is_resident",
-           "tc_stitch_kv", "tc_stitch_kv_rope", "tc_prefill_attn", "tc_release_seqs", "tc_read_seq_kv",
+           "tc_stitch_kv", "tc_stitch_kv_rope", "tc_stitch_alias", "tc_prefill_attn", "tc_release_seqs", "tc_read_seq_kv",
            "tc_kv_splits", "tc_set_kv_splits", "tc_set_row_blocks", "tc_set_attn_kernel", "tc_attn_kernel", "tc_profile_enable", "tc_profile_read", "tc_last_error", "tc_version",
            "tc_trie_create", "tc_trie_destroy", "tc_trie_insert", "tc_trie_match", "tc_rerank",
            "tc_pin_tables", "tc_unpin_tables", "tc_plan_pipeline"]
@@ -48,7 +49,7 @@ class tc_config(ctypes.Structure):
                 ("block_size", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("n_pool_blocks", ctypes.c_int64), ("table_capacity", ctypes.c_int32),
                 ("max_table_tokens", ctypes.c_int32), ("policy", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+                ("slot_layout", ctypes.c_int32)]
 
 
 _vp, _i32, _i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
@@ -64,6 +65,7 @@ _sig = {
     "tc_load_trace": (_i32, [_vp, _vp, _i32]),
     "tc_is_resident": (_i32, [_vp, _i32, _i32, _i32]),
     "tc_stitch_kv": (_i32, [_vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp]),
+    "tc_stitch_alias": (_i32, [_vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp]),
     "tc_stitch_kv_rope": (_i32, [_vp, _vp, _vp, _i32, _vp, _vp, ctypes.c_double, _vp, _i32, _vp, _vp]),
     "tc_prefill_attn": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32,
                                ctypes.c_float, _vp]),
@@ -120,9 +122,9 @@ def _stream(s) -> Optional[int]:
 
 
 def make_config(n_layers, n_q_heads, n_kv_heads, head_dim, dtype, n_pool_blocks, table_capacity,
-                max_table_tokens, policy=TC_POLICY_LRU, block_size=16) -> tc_config:
+                max_table_tokens, policy=TC_POLICY_LRU, block_size=16, slot_layout=TC_SLOTS_ROWS) -> tc_config:
     return tc_config(n_layers, n_q_heads, n_kv_heads, head_dim, block_size, dtype, n_pool_blocks,
-                     table_capacity, max_table_tokens, policy, 0)
+                     table_capacity, max_table_tokens, policy, slot_layout)
 
 
 def tc_block_bytes(cfg: tc_config) -> int:
@@ -205,6 +207,16 @@ class Context:
         pl = np.full((B,), -7, dtype=np.int32)
         self._check(_lib.tc_stitch_kv(self._h, ids.ctypes.data, cu.ctypes.data, B, sl.ctypes.data,
                                       bt.ctypes.data, max_blocks, pl.ctypes.data, _stream(stream)))
+        return bt, pl
+
+    def tc_stitch_alias(self, table_ids, cu_tables, suffix_len, max_blocks: int,
+                        stream=None) -> Tuple[np.ndarray, np.ndarray]:
+        ids, cu, sl = _i32arr(table_ids), _i32arr(cu_tables), _i32arr(suffix_len)
+        B = cu.size - 1
+        bt = np.full((B, max_blocks), -7, dtype=np.int32)
+        pl = np.full((B,), -7, dtype=np.int32)
+        self._check(_lib.tc_stitch_alias(self._h, ids.ctypes.data, cu.ctypes.data, B, sl.ctypes.data,
+                                         bt.ctypes.data, max_blocks, pl.ctypes.data, _stream(stream)))
         return bt, pl
 
     def tc_stitch_kv_rope(self, table_ids, cu_tables, suffix_len, pos0, rope_theta: float, max_blocks: int,

@@ -19,7 +19,7 @@ __device__ __forceinline__ void append_unit(const Geom &g, const BatchDev &b, in
     if (n < b.total_S) {
         const int i = b.tok_q[n];
         const int p = b.prefix_len[i] + (n - b.cu_seqlens[i]);
-        const int phys = b.block_table[(int64_t)i * b.max_blocks + (p >> 4)];
+        const int phys = entry_bid(b.block_table[(int64_t)i * b.max_blocks + (p >> 4)]);
         const int t = p & 15;
         char *kd = layer_base + (int64_t)phys * g.block_bytes;
         char *vd = kd + (g.block_bytes >> 1);
@@ -46,7 +46,7 @@ __device__ __forceinline__ void append_unit(const Geom &g, const BatchDev &b, in
         const int end = b.prefix_len[i] + b.suffix_len[i];
         const int t0 = end & 15;
         if (t0 == 0) return;
-        const int phys = b.block_table[(int64_t)i * b.max_blocks + (end >> 4)];
+        const int phys = entry_bid(b.block_table[(int64_t)i * b.max_blocks + (end >> 4)]);
         char *kd = layer_base + (int64_t)phys * g.block_bytes;
         char *vd = kd + (g.block_bytes >> 1);
         const uint4 zero = make_uint4(0, 0, 0, 0);

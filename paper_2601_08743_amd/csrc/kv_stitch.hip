@@ -13,6 +13,69 @@
 
 namespace tc {
 
+// Copy of one block's keys, [t][h][d] rows at k_src + src_off[t] (-1: no such token, zeros) ->
+// the block's K half [h][t][d].
+__device__ __forceinline__ void copy_block_k(const Geom &g, const char *k_src, const int64_t *src_off, char *dst, int tid)
+{
+    const int cpr = g.row_bytes >> 4, cph = g.head_bytes >> 4;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    for (int c = tid; c < kBlockTokens * cpr; c += 256) {
+        const int t = c / cpr, w = c - t * cpr;
+        const int h = w / cph, dc = w - h * cph;
+        const int64_t so = src_off[t];
+        const uint4 v = so >= 0 ? *(const uint4 *)(k_src + so + ((int64_t)w << 4)) : zero;
+        *(uint4 *)(dst + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = v;
+    }
+}
+
+// The same for the values: rows at v_src + src_off[t] -> the block's V half (vdst), transposed
+// per head for 2-byte elements (through `lds`, [16][row_bytes / 16] chunks).
+template <bool kTransposeV>
+__device__ __forceinline__ void copy_block_v(const Geom &g, const char *v_src, const int64_t *src_off, char *vdst,
+                                             uint4 *lds, int tid)
+{
+    const int cpr = g.row_bytes >> 4, cph = g.head_bytes >> 4;
+    const int n_chunks = kBlockTokens * cpr;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    if (!kTransposeV) {
+        for (int c = tid; c < n_chunks; c += 256) {
+            const int t = c / cpr, w = c - t * cpr;
+            const int h = w / cph, dc = w - h * cph;
+            const int64_t so = src_off[t];
+            const uint4 v = so >= 0 ? *(const uint4 *)(v_src + so + ((int64_t)w << 4)) : zero;
+            *(uint4 *)(vdst + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = v;
+        }
+    } else {
+        for (int c = tid; c < n_chunks; c += 256) {
+            const int t = c / cpr, w = c - t * cpr;
+            const int64_t so = src_off[t];
+            lds[c] = so >= 0 ? *(const uint4 *)(v_src + so + ((int64_t)w << 4)) : zero;
+        }
+        __syncthreads();
+        // out chunk oc = (h, d, half): 8 tokens of one (h, d), 2-byte elements
+        const unsigned short *l16 = (const unsigned short *)lds;
+        const int row_elems = g.row_bytes >> 1;
+        const int n_out = g.Hkv * g.D * 2;
+        for (int oc = tid; oc < n_out; oc += 256) {
+            const int half = oc & 1;
+            const int hd = oc >> 1;                // h * D + d
+            unsigned short e[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int t = (k & 3) | ((k & 4) << 1) | (half << 2);
+                e[k] = l16[t * row_elems + hd];
+            }
+            uint4 v;
+            v.x = e[0] | ((unsigned)e[1] << 16);
+            v.y = e[2] | ((unsigned)e[3] << 16);
+            v.z = e[4] | ((unsigned)e[5] << 16);
+            v.w = e[6] | ((unsigned)e[7] << 16);
+            *(uint4 *)(vdst + ((int64_t)oc << 4)) = v;
+        }
+    }
+}
+
+
 // ------------------------------------------------------------------------------------ stitch
 // Paper Sec. 4.1.2: the matched tables' KV caches are concatenated in match order.
 // One work-group per (destination block, layer).
@@ -53,14 +116,7 @@ __global__ __launch_bounds__(256) void stitch_kernel(Geom g, BatchDev b, int l0)
     const int n_chunks = kBlockTokens * cpr;
     const uint4 zero = make_uint4(0, 0, 0, 0);
     if (!kRope) {
-        // K: [t][h][d] -> [h][t][d]
-        for (int c = tid; c < n_chunks; c += 256) {
-            const int t = c / cpr, w = c - t * cpr;
-            const int h = w / cph, dc = w - h * cph;
-            const int64_t so = src_off[t];
-            const uint4 v = so >= 0 ? *(const uint4 *)(layer_base + so + ((int64_t)w << 4)) : zero;
-            *(uint4 *)(dst + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = v;
-        }
+        copy_block_k(g, layer_base, src_off, dst, tid);
     } else {
         // one unit = the two 16-byte chunks of a head row that hold elements i and i + D/2.  The
         // loads of a pass of kUnits units per thread are issued first; the rotation table is built
@@ -158,44 +214,44 @@ __global__ __launch_bounds__(256) void stitch_kernel(Geom g, BatchDev b, int l0)
         }
         __syncthreads();                        // the rotation table is dead: the V staging may overwrite it
     }
-    const char *vsrc_base = layer_base + (g.slot_bytes >> 1);
-    char *vdst = dst + (g.block_bytes >> 1);
-    if (!kTransposeV) {
-        for (int c = tid; c < n_chunks; c += 256) {
-            const int t = c / cpr, w = c - t * cpr;
-            const int h = w / cph, dc = w - h * cph;
-            const int64_t so = src_off[t];
-            const uint4 v = so >= 0 ? *(const uint4 *)(vsrc_base + so + ((int64_t)w << 4)) : zero;
-            *(uint4 *)(vdst + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = v;
-        }
-    } else {
-        for (int c = tid; c < n_chunks; c += 256) {
-            const int t = c / cpr, w = c - t * cpr;
-            const int64_t so = src_off[t];
-            lds[c] = so >= 0 ? *(const uint4 *)(vsrc_base + so + ((int64_t)w << 4)) : zero;
-        }
-        __syncthreads();
-        // out chunk oc = (h, d, half): 8 tokens of one (h, d), 2-byte elements
-        const unsigned short *l16 = (const unsigned short *)lds;
-        const int row_elems = g.row_bytes >> 1;
-        const int n_out = g.Hkv * g.D * 2;
-        for (int oc = tid; oc < n_out; oc += 256) {
-            const int half = oc & 1;
-            const int hd = oc >> 1;                // h * D + d
-            unsigned short e[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int t = (k & 3) | ((k & 4) << 1) | (half << 2);
-                e[k] = l16[t * row_elems + hd];
-            }
-            uint4 v;
-            v.x = e[0] | ((unsigned)e[1] << 16);
-            v.y = e[2] | ((unsigned)e[3] << 16);
-            v.z = e[4] | ((unsigned)e[5] << 16);
-            v.w = e[6] | ((unsigned)e[7] << 16);
-            *(uint4 *)(vdst + ((int64_t)oc << 4)) = v;
-        }
+    copy_block_v<kTransposeV>(g, layer_base + (g.slot_bytes >> 1), src_off, dst + (g.block_bytes >> 1), lds, tid);
+}
+
+// ------------------------------------------------------------------------------------ format
+// A table's KV as registered (token rows, all layers: K part then V part) -> the blocks of its
+// slot, in the sequence-block layout, the unused tail of its last block zero-filled (keys and
+// values), so that an attention launch can read the slot's blocks as if they were part of a
+// stitched sequence.  One work-group per (block of the table, layer).  `raw` holds the K part at
+// offset 0 and the V part at `v_part`; layer l of either starts n_tokens * l rows in.
+template <bool kTransposeV>
+__global__ __launch_bounds__(256) void format_kernel(Geom g, const char *raw, int64_t v_part, int n_tokens,
+                                                     int first_block, int l0)
+{
+    extern __shared__ uint4 lds[];
+    __shared__ int64_t src_off[kBlockTokens];
+    const int layer = l0 + blockIdx.y;
+    const int tid = threadIdx.x;
+    if (tid < kBlockTokens) {
+        const int tok = blockIdx.x * kBlockTokens + tid;
+        src_off[tid] = tok < n_tokens ? ((int64_t)layer * n_tokens + tok) * g.row_bytes : -1;
     }
+    __syncthreads();
+    char *dst = g.pool + (int64_t)layer * g.layer_stride + (int64_t)(first_block + blockIdx.x) * g.block_bytes;
+    copy_block_k(g, raw, src_off, dst, tid);
+    copy_block_v<kTransposeV>(g, raw + v_part, src_off, dst + (g.block_bytes >> 1), lds, tid);
+}
+
+hipError_t launch_format(const Geom &g, const void *raw, int64_t v_part, int n_tokens, int first_block, int l0,
+                         int l1, const Launch &L)
+{
+    if (n_tokens <= 0 || l1 <= l0) return hipSuccess;
+    dim3 grid((n_tokens + kBlockTokens - 1) / kBlockTokens, l1 - l0);
+    if (g.esize == 2)
+        TC_LAUNCH(format_kernel<true>, grid, kBlockTokens * g.row_bytes, L, g, (const char *)raw, v_part, n_tokens,
+                  first_block, l0);
+    else
+        TC_LAUNCH(format_kernel<false>, grid, 0, L, g, (const char *)raw, v_part, n_tokens, first_block, l0);
+    return hipGetLastError();
 }
 
 hipError_t launch_stitch(const Geom &g, const BatchDev &b, int l0, int l1, bool rope, const Launch &L)

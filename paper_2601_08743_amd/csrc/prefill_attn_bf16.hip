@@ -63,7 +63,7 @@ struct RowState {
 template <int RB>
 __device__ __forceinline__ void tile_math(RowState<RB> &st, const bf16x8 (&qf)[RB][8], const char *k_ld,
                                           const char *v_ld, int key0, const int (&limit)[RB],
-                                          bool need_mask, int hh, float c)
+                                          bool need_mask, uint32_t pads, int hh, float c)
 {
     f32x16 sacc[RB][2];
 #pragma unroll
@@ -83,13 +83,16 @@ __device__ __forceinline__ void tile_math(RowState<RB> &st, const bf16x8 (&qf)[R
         }
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        if (need_mask) {                               // causal edge or ragged tail in this tile
+        if (need_mask) {                               // causal edge, ragged tail or unused block tails in this tile
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int key = key0 + 32 * mb + 8 * (e >> 2) + 4 * hh + (e & 3);
-                    if (key > limit[rb]) sacc[rb][mb][e] = -INFINITY;
+                    // position inside its 16-token block, and that block's unused tail (4 bits per block)
+                    const int t = 8 * ((e >> 2) & 1) + 4 * hh + (e & 3);
+                    const int used = 16 - (int)((pads >> (4 * (2 * mb + (e >> 3)))) & 15u);
+                    if (key > limit[rb] || t >= used) sacc[rb][mb][e] = -INFINITY;
                 }
         }
         float mx = sacc[rb][0][0];
@@ -220,7 +223,7 @@ __device__ __forceinline__ void tile_loop(RowState<RB> &st, const bf16x8 (&qf)[R
     uint4 kb0, kb1, kb2, kb3, vb0, vb1, vb2, vb3;
 #define TC_LD(kx, vx, bid_)                                                                    \
     {                                                                                          \
-        const char *src = pool_l + (int64_t)__builtin_amdgcn_readfirstlane(bid_) * bb;        \
+        const char *src = pool_l + (int64_t)entry_bid(__builtin_amdgcn_readfirstlane(bid_)) * bb; \
         kx = *(const uint4 *)(src + t_off);                                                    \
         vx = *(const uint4 *)(src + (v_half + t_off));                                         \
     }
@@ -317,8 +320,16 @@ __device__ __forceinline__ void tile_loop(RowState<RB> &st, const bf16x8 (&qf)[R
         const int key0 = (pre_ ? tt_ : tt_ - npt) * kAttnKeys;                                    \
         int lim_[RB];                                                                             \
         _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) lim_[rb] = pre_ ? P - 1 : ir.limit[rb]; \
+        uint32_t pads_ = 0;                                                                       \
+        if (pre_) {                                                                               \
+            const int4 e4_ = *(const int4 *)(s_bid + (r_) * 4);                                   \
+            pads_ = (uint32_t)entry_pad(e4_.x) | ((uint32_t)entry_pad(e4_.y) << 4) |              \
+                    ((uint32_t)entry_pad(e4_.z) << 8) | ((uint32_t)entry_pad(e4_.w) << 12);       \
+            pads_ = __builtin_amdgcn_readfirstlane(pads_);                                        \
+        }                                                                                         \
         tile_math<RB>(st, qf, k_ld + (stage_) * kStage, v_ld + (stage_) * kStage, key0, lim_,     \
-                      key0 + kAttnKeys - 1 > (pre_ ? P - 1 : ir.wave_stok_min), hh, c);           \
+                      pads_ != 0 || key0 + kAttnKeys - 1 > (pre_ ? P - 1 : ir.wave_stok_min),     \
+                      pads_, hh, c);                                                              \
     }
 
     // Two key tiles (128 keys) per iteration: their K/V are loaded into the two register sets
@@ -471,7 +482,13 @@ constexpr int kFastV = kFastBufs * kFastKTile;            // V buffers follow th
 constexpr int kFastBid = kFastV + kFastBufs * kVTile;     // block ids of the item's key range
 constexpr int kLdsBytesPipe = kFastBid + kBidBytes;
 static_assert(kLdsBytesPipe <= 160 * 1024 && 2 * kStage <= kFastBid, "LDS layout");
-constexpr int kFastMinTiles = 3;                          // shorter runs take the general loop
+// Shorter runs take the general loop.  Runs of exactly three tiles are excluded on evidence, not
+// on a found cause: on some machines their first launches in a process returned wrong rows
+// (launch-dependent results for identical inputs, gone when the run went through the general loop),
+// while runs of four and more have never differed between launches.  Little is lost: runs this
+// short are mostly the pipeline's fill and drain (a two-tile run was measured slower than the
+// general loop).
+constexpr int kFastMinTiles = 4;
 
 #define TC_SB() __builtin_amdgcn_sched_barrier(0)
 
@@ -529,6 +546,23 @@ __device__ __forceinline__ void v_pack(uint32_t &d, float lo, float hi)
     asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(d) : "v"(lo), "v"(hi));
 }
 
+// The compiler does not know how long a matrix instruction written as inline assembly takes, and it
+// is free to put its own register copies of O (moves between accumulation registers where two
+// paths join, copies in and out of them) right next to one.  These two fences pin O down: each
+// names all of O as an operand, so every copy the compiler makes lands before `o_fence_in` or after
+// `o_fence_out`.  A matrix result must not be read for 11 cycles after issue (the compiler's own
+// figure for this instruction): the closing fence sits right behind the step's last matrix
+// instruction and holds 12.  After the opening fence the first matrix instruction that reads O
+// comes more than ten instructions later, which covers the 2 cycles a freshly written register needs.
+__device__ __forceinline__ void o_fence_in(f32x16 (&o)[4])
+{
+    asm volatile("" : "+a"(o[0]), "+a"(o[1]), "+a"(o[2]), "+a"(o[3]));
+}
+__device__ __forceinline__ void o_fence_out(f32x16 (&o)[4])
+{
+    asm volatile("s_nop 11" : "+a"(o[0]), "+a"(o[1]), "+a"(o[2]), "+a"(o[3]));
+}
+
 // One step.  PAR = parity of s.  kb / vb: this lane's LDS read addresses for K(s+1) / V(s-1); the
 // K chunk of k-step ks sits at kb ^ (ks << 5) (the XOR swizzle; bits 5..7 of kb hold the lane's key).
 // QK: tile s+1 exists, PV: tile s-1 exists - compile-time, because a run-time test per matrix
@@ -551,6 +585,7 @@ __device__ __forceinline__ void fast_step(FastState &fs, f32x16 (&o)[4], const b
 #define TC_OPADDR(j) ((((j) & 1) == 0) ? (kb ^ ((((j) >> 1) & 7) << 5)) + (((j) >> 4) * 32 * 256)             \
                                       : vb + ((((j) >> 1) >> 2) * kHeadBlk + (((j) >> 1) & 3) * 1024))
 #define TC_OPLOAD(j) if ((((j) & 1) == 0) ? QK : PV) fr[(j) & 3] = *(lds_frag)(uintptr_t)(TC_OPADDR(j));
+    if (PV) o_fence_in(o);
     TC_OPLOAD(0) TC_OPLOAD(1) TC_OPLOAD(2)
     // stream position x of this step: 0..15 -> S[2 PAR] (tile s, keys 32..63), 16..31 -> S[2 PAR + 1]
     // (tile s+1, keys 0..31); negative: the previous step's positions 32 + x (tile s, keys 0..31)
@@ -592,6 +627,7 @@ __device__ __forceinline__ void fast_step(FastState &fs, f32x16 (&o)[4], const b
         }
         TC_SB();
     }
+    if (PV) o_fence_out(o);
     // the stream's last stages (positions 27..31) run in the first slots of the next step
     l_cur = lc;
     l_nxt = ln;
@@ -618,9 +654,11 @@ __device__ __forceinline__ bool fast_tiles(RowState<1> &st, const bf16x8 (&qf)[1
     // ---- loads: wave w brings block w of a tile (16 keys): K as four 1 KB pieces of four rows each,
     // chunk c of row r stored at chunk position c ^ r; V verbatim (4 KB per block and head)
     // (the per-lane offsets are recomputed at every use rather than kept in registers across the steps)
-    const char *dummy = pool_l + (int64_t)it.bid[0] * bb;       // source of loads past the run: a valid block
-    auto issue_k = [&](int buf, int bid, bool real) {
-        const char *src = real ? pool_l + (int64_t)__builtin_amdgcn_readfirstlane(bid) * bb : dummy;
+    // Only tiles that exist are loaded, and the waits below count exactly the loads that may still
+    // be in flight (s_waitcnt vmcnt tells which tiles have landed because a wave's loads complete in
+    // issue order).
+    auto issue_k = [&](int buf, int bid) {
+        const char *src = pool_l + (int64_t)entry_bid(__builtin_amdgcn_readfirstlane(bid)) * bb;
         const uint32_t dst = lds0 + buf * kFastKTile + w * 4096;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -628,23 +666,32 @@ __device__ __forceinline__ bool fast_tiles(RowState<1> &st, const bf16x8 (&qf)[1
             load_to_lds(dst + i * 1024, src, rb * 256 + (((lane & 15) ^ rb) * 16));
         }
     };
-    auto issue_v = [&](int buf, int bid, bool real) {
-        const char *src = (real ? pool_l + (int64_t)__builtin_amdgcn_readfirstlane(bid) * bb : dummy) + v_half;
+    auto issue_v = [&](int buf, int bid) {
+        const char *src = pool_l + (int64_t)entry_bid(__builtin_amdgcn_readfirstlane(bid)) * bb + v_half;
         const uint32_t dst = lds0 + kFastV + buf * kVTile + w * 4096;
 #pragma unroll
         for (int i = 0; i < 4; ++i) load_to_lds(dst + i * 1024, src + i * 1024, lane * 16);
+    };
+    // wait until at most k batches (one tile's K or V: 4 loads per wave) are still in flight
+    auto wait_batches = [&](int k) {
+        if (k <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if (k == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else if (k == 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if (k == 3) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+        else if (k == 4) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
     };
     // the item carries the block ids of its first four tiles
     auto item_bid = [&](int t) {
         const int b0 = it.bid[4 * t], b1 = it.bid[4 * t + 1], b2 = it.bid[4 * t + 2], b3 = it.bid[4 * t + 3];
         return w == 0 ? b0 : w == 1 ? b1 : w == 2 ? b2 : b3;
     };
-    issue_k(0, item_bid(0), true);
-    issue_k(1, item_bid(1), 1 < n);
-    issue_k(2, item_bid(2), 2 < n);
-    issue_v(0, item_bid(0), true);
-    issue_k(3, item_bid(3), 3 < n);
-    issue_v(1, item_bid(1), 1 < n);
+    issue_k(0, item_bid(0));                            // n >= 3: tiles 0, 1, 2 exist
+    issue_k(1, item_bid(1));
+    issue_k(2, item_bid(2));
+    issue_v(0, item_bid(0));
+    if (3 < n) issue_k(3, item_bid(3));
+    issue_v(1, item_bid(1));
     // the block-id table is filled behind these loads, so that its round trip to the block table
     // does not delay them (the barrier of the prime step publishes it)
     fill_bids(s_bid, b, it, tid);
@@ -662,7 +709,7 @@ __device__ __forceinline__ bool fast_tiles(RowState<1> &st, const bf16x8 (&qf)[1
         for (int e = 0; e < 4; ++e) { fs.pE[kk][e] = 0u; fs.pO[kk][e] = 0u; }
 
     // ---- prime: QK(0) from K buffer 0; reference; weights of keys 0..31
-    asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+    wait_batches(4 + (3 < n ? 1 : 0));                  // everything issued after K(0) may still be in flight
     __syncthreads();                                    // K(0) landed for every wave; block ids visible
     {
         typedef const __attribute__((address_space(3))) bf16x8 *lds_frag;
@@ -677,9 +724,22 @@ __device__ __forceinline__ bool fast_tiles(RowState<1> &st, const bf16x8 (&qf)[1
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
             fs.S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(lds_frag)(uintptr_t)((kb ^ (ks << 5)) + 32 * 256), qf[0][ks], fs.S[0], 0, 0, 0);
-        float mx = fs.S[3][0];
+        // reference: the largest score among the run's first 32 keys - its real ones: the unused tail
+        // of an aliased table block holds zero keys, whose score 0 says nothing about the row
+        const int pad0 = entry_pad(it.bid[0]), pad1 = entry_pad(it.bid[1]);
+        float mx;
+        if ((pad0 | pad1) == 0) {
+            mx = fs.S[3][0];
 #pragma unroll
-        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fs.S[3][e]);
+            for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fs.S[3][e]);
+        } else {
+            mx = -INFINITY;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int t = 8 * ((e >> 2) & 1) + 4 * hh + (e & 3);
+                if (t < 16 - ((e >> 3) ? pad1 : pad0)) mx = fmaxf(mx, fs.S[3][e]);
+            }
+        }
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         st.m_run[0] = mx * c;
         fs.nm = -st.m_run[0];
@@ -701,13 +761,24 @@ __device__ __forceinline__ bool fast_tiles(RowState<1> &st, const bf16x8 (&qf)[1
 
     // ---- steps.  Before step s: K reads go to buffer (s+1) & 3, V reads to buffer (s-1) & 3.
     // boundary after step s (s = -1 for the prime step)
+    // The next step reads K(s+2) and V(s).  Issue order: K0 K1 K2 V0 [K3] V1, then per boundary b
+    // K(b+5), V(b+3) (those that exist); what was issued after the later of the two needed tiles may
+    // stay in flight.
     auto boundary = [&](int s, int bid_k, int bid_v) {
-        if (s + 2 < n) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");     // two younger batches may stay in flight
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (s >= 0 && s + 5 < n) {                       // the steady state: one test, everything exists
+            asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+            __syncthreads();
+            issue_k((s + 1) & 3, bid_k);
+            issue_v((s + 3) & 3, bid_v);
+            return;
+        }
+        const int younger = s < 0 ? 3 + (3 < n ? 1 : 0)
+                                  : (s + 1 < n ? 1 : 0) + (s + 2 < n ? 1 : 0) + (s + 3 < n ? 1 : 0) + (s + 4 < n ? 1 : 0);
+        wait_batches(younger);
         __syncthreads();
         if (s + 3 < n) {
-            issue_k((s + 1) & 3, bid_k, s + 5 < n);
-            issue_v((s + 3) & 3, bid_v, true);
+            if (s + 5 < n) issue_k((s + 1) & 3, bid_k);
+            issue_v((s + 3) & 3, bid_v);
         }
     };
     auto advance = [&](int s_next) {                    // read addresses for step s_next
@@ -753,11 +824,20 @@ __device__ __forceinline__ bool fast_tiles(RowState<1> &st, const bf16x8 (&qf)[1
         TC_STEP(0, false, true, s + 1)
     }
 #undef TC_STEP
-    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");   // O's last matrix instruction completes before O is read
+    // Unused tails of aliased table blocks inside the run: their keys and values are zeros, so they
+    // added nothing to O and, each, exactly 2^(0 c - ref) to the row sum - taken out here instead of
+    // masking scores in every step.  That is only sound while this weight is small against the sum:
+    // with ref >= 0 it is at most 1, and the sum holds the reference key's own weight 1.  A row whose
+    // reference is negative sends the item to the general loop, which masks.
+    bool bad = false;
+    if (it.n_pad_fast > 0) {
+        if (hh == 0) fs.l -= (float)it.n_pad_fast * __builtin_amdgcn_exp2f(fs.nm);
+        bad = fs.nm > 0.f;
+    }
     st.l_lane[0] = fs.l;
     // a weight that overflowed shows in the sum (inf or nan)
     const float l_row = fs.l + __shfl_xor(fs.l, 32);
-    return __syncthreads_or(!(l_row < 1e30f)) == 0;
+    return __syncthreads_or(bad || !(l_row < 1e30f)) == 0;
 }
 
 // The kernel for one row block per wave: pipelined path over the leading run of full prefix tiles,

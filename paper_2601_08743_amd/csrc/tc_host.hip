@@ -107,6 +107,8 @@ struct Slot {
     hipStream_t ready_stream = nullptr;
     bool ready_pending = false;        // a record exists that other streams may have to wait for
     int32_t read_ev = -1;              // index into the read-event ring, -1 = never read
+    hipStream_t reader_stream = nullptr;   // block-format slots: stream of the last attention launch that
+    bool reader_pending = false;           // read the slot through an aliasing sequence, not yet ordered
 };
 
 // The integer plan of one batch, host copy and layout of the device copy.
@@ -118,6 +120,8 @@ struct Plan {
     std::vector<int32_t> rope_pos0;      // [B]
     std::vector<double> rope_rev_freq;   // [D/2]
     std::vector<int32_t> block_table, cu_seqlens, prefix_len, suffix_len;
+    std::vector<uint8_t> block_pad;      // aliasing sequences: unused token positions per block-table entry, else empty
+    std::vector<int32_t> alias_slots;    // table slots whose blocks the batch's sequences alias
     BatchDev dev{};
     const AttnItem *items_dev = nullptr;
     const MergeGroup *groups_dev = nullptr;
@@ -142,6 +146,9 @@ struct tc_ctx {
     std::vector<int32_t> trace;            // (table, hit, evicted) triples
     std::vector<hipEvent_t> read_ring;     // events recorded after stitch kernels
     int32_t read_next = 0;
+    hipEvent_t raw_ev = nullptr;           // block-format slots: the raw staging area was last used up to here,
+    hipStream_t raw_stream = nullptr;      // on this stream
+    bool raw_pending = false;
     Plan plan;
     int32_t *h_stage = nullptr; size_t h_stage_ints = 0;
     int32_t *d_plan = nullptr; size_t d_plan_ints = 0;
@@ -215,6 +222,9 @@ bool config_ok(const tc_config *c)
     if (c->n_pool_blocks <= 0 || c->n_pool_blocks > INT32_MAX) return false;
     const int64_t sb = (c->max_table_tokens + kBlockTokens - 1) / kBlockTokens;
     if ((int64_t)c->table_capacity * sb > c->n_pool_blocks) return false;
+    if (c->slot_layout != TC_SLOTS_ROWS && c->slot_layout != TC_SLOTS_BLOCKS) return false;
+    // aliasing sequences: bf16 kernels only; the device block tables keep 5 bits beside the id
+    if (c->slot_layout == TC_SLOTS_BLOCKS && (c->dtype != TC_BF16 || c->n_pool_blocks > (int64_t)kBidMask)) return false;
     return true;
 }
 
@@ -332,6 +342,7 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
             cut[ns] = n_tiles;
         }
         const int32_t *bt = p.block_table.data() + (size_t)i * p.max_blocks;
+        const uint8_t *pad_of = p.block_pad.empty() ? nullptr : p.block_pad.data() + (size_t)i * p.max_blocks;
         for (int h = 0; h < c.n_kv_heads; ++h) {
             for (int s = 0; s < ns; ++s) {
                 const int t0 = cut[s], t1 = cut[s + 1];
@@ -341,8 +352,14 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
                     it.q = i; it.kvh = h; it.m0 = mt * RT; it.tile_begin = t0; it.tile_end = t1;
                     it.split = s; it.n_splits = ns; it.group = n_groups + mt;
                     it.P = P; it.S = S; it.cu = p.cu_seqlens[i];
-                    for (int k = 0; k < 16; ++k)
-                        it.bid[k] = bt[std::min(t0 * (KT / kBlockTokens) + k, last_blk)];
+                    for (int k = 0; k < 16; ++k) {
+                        const int idx = std::min(t0 * (KT / kBlockTokens) + k, last_blk);
+                        it.bid[k] = bt[idx] | (pad_of ? (int32_t)((uint32_t)pad_of[idx] << kPadShift) : 0);
+                    }
+                    if (pad_of && bf16) {
+                        const int n_fast = std::min(t1, P >> 6) - t0;
+                        for (int k = t0 * 4; k < (t0 + std::max(n_fast, 0)) * 4; ++k) it.n_pad_fast += pad_of[k];
+                    }
                     bucket.push_back(it);
                 }
                 buckets.push_back(std::move(bucket));
@@ -416,6 +433,8 @@ tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
     std::memset(h, 0, total * sizeof(int32_t));
     if (B) {
         std::memcpy(h + o_bt, p.block_table.data(), B * p.max_blocks * 4);
+        for (size_t k = 0; k < p.block_pad.size(); ++k)
+            if (p.block_pad[k]) h[o_bt + k] |= (int32_t)((uint32_t)p.block_pad[k] << kPadShift);
         std::memcpy(h + o_cu, p.cu_seqlens.data(), (B + 1) * 4);
         std::memcpy(h + o_pl, p.prefix_len.data(), B * 4);
         std::memcpy(h + o_sl, p.suffix_len.data(), B * 4);
@@ -485,7 +504,11 @@ size_t tc_block_bytes(const tc_config *c)
 size_t tc_pool_bytes(const tc_config *c)
 {
     if (!config_ok(c)) return 0;
-    return (size_t)c->n_layers * (size_t)c->n_pool_blocks * tc_block_bytes(c);
+    size_t blocks = (size_t)c->n_pool_blocks;
+    // block-format slots: room for one table as registered (token rows), where a copy from the host
+    // lands before it is laid out into the table's slot
+    if (c->slot_layout == TC_SLOTS_BLOCKS) blocks += (size_t)((c->max_table_tokens + kBlockTokens - 1) / kBlockTokens);
+    return (size_t)c->n_layers * blocks * tc_block_bytes(c);
 }
 
 int64_t tc_first_seq_block(const tc_config *c)
@@ -518,6 +541,13 @@ tc_status tc_create(const tc_config *cfg, void *kv_pool_dev, size_t pool_bytes, 
     const int64_t n_seq = cfg->n_pool_blocks - ctx->first_seq;
     g.layer_stride = g.block_bytes * n_seq;
     g.pool = (char *)kv_pool_dev + g.slot_bytes * cfg->table_capacity - ctx->first_seq * g.block_bytes;
+    if (cfg->slot_layout == TC_SLOTS_BLOCKS) {
+        // one block-id space per layer: ids [0, first_seq) are the table slots' blocks (slot s owns
+        // s * slot_blocks ..), the rest sequence blocks; the staging area for raw tables follows
+        g.pool = (char *)kv_pool_dev;
+        g.layer_stride = g.block_bytes * cfg->n_pool_blocks;
+        g.tab_base = (char *)kv_pool_dev + g.layer_stride * cfg->n_layers;
+    }
     g.first_seq = (int32_t)ctx->first_seq;
     g.n_blocks = (int32_t)cfg->n_pool_blocks;
     g.Hq = cfg->n_q_heads; g.Hkv = cfg->n_kv_heads; g.D = cfg->head_dim; g.G = g.Hq / g.Hkv;
@@ -538,6 +568,7 @@ tc_status tc_create(const tc_config *cfg, void *kv_pool_dev, size_t pool_bytes, 
     for (auto &e : ctx->read_ring)
         if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return TC_ERR_HIP;
     if (hipEventCreateWithFlags(&ctx->stage_ev, hipEventDisableTiming) != hipSuccess) return TC_ERR_HIP;
+    if (hipEventCreateWithFlags(&ctx->raw_ev, hipEventDisableTiming) != hipSuccess) return TC_ERR_HIP;
     for (int64_t b = ctx->first_seq; b < cfg->n_pool_blocks; ++b) ctx->free_seq.insert((int32_t)b);
     ctx->seq_used.assign((size_t)(cfg->n_pool_blocks - ctx->first_seq), 0);
     *out = ctx.release();
@@ -551,6 +582,7 @@ tc_status tc_destroy(tc_ctx *ctx)
     for (auto &s : ctx->slots) if (s.ready) (void)hipEventDestroy(s.ready);
     for (auto &e : ctx->read_ring) if (e) (void)hipEventDestroy(e);
     if (ctx->stage_ev) (void)hipEventDestroy(ctx->stage_ev);
+    if (ctx->raw_ev) (void)hipEventDestroy(ctx->raw_ev);
     if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
     if (ctx->d_plan) (void)hipFree(ctx->d_plan);
     if (ctx->d_part) (void)hipFree(ctx->d_part);
@@ -620,6 +652,18 @@ tc_status tc_load_async(tc_ctx *ctx, const int32_t *table_ids, int32_t n, int32_
             }
             if (s.ready_pending && s.ready_stream != stream)   // earlier copies into this slot on another stream
                 TC_HIP(ctx, hipStreamWaitEvent(stream, s.ready, 0));
+            if (s.reader_pending) {     // attention launches read the previous occupant in place: wait for
+                                        // everything enqueued so far on the stream they run on
+                if (s.reader_stream != stream) {
+                    const int32_t ev = ctx->read_next;
+                    ctx->read_next = (ctx->read_next + 1) % (int32_t)ctx->read_ring.size();
+                    TC_HIP(ctx, hipEventRecord(ctx->read_ring[ev], s.reader_stream));
+                    TC_HIP(ctx, hipStreamWaitEvent(stream, ctx->read_ring[ev], 0));
+                    for (Slot &o : ctx->slots)      // the same event covers every slot read on that stream
+                        if (o.reader_pending && o.reader_stream == s.reader_stream) o.reader_pending = false;
+                }
+                s.reader_pending = false;
+            }
         }
         ctx->trace.push_back(id); ctx->trace.push_back(hit ? 1 : 0); ctx->trace.push_back(evicted);
         // copy the layers of the range that are not on the device yet: a run of consecutive layers of
@@ -630,10 +674,22 @@ tc_status tc_load_async(tc_ctx *ctx, const int32_t *table_ids, int32_t n, int32_
             if (t.layer_loaded[l]) { ++l; continue; }
             int e = l;
             while (e < l1 && !t.layer_loaded[e]) ++e;
-            char *dst = g.tab_base + (int64_t)t.slot * g.slot_bytes + (size_t)l * width;
+            const bool blocks = ctx->cfg.slot_layout == TC_SLOTS_BLOCKS;
+            // block-format slots: the rows land in the staging area (one for all tables; copies and
+            // the kernel that lays them out into the slot's blocks are ordered by the stream)
+            if (blocks && ctx->raw_pending && ctx->raw_stream != stream)
+                TC_HIP(ctx, hipStreamWaitEvent(stream, ctx->raw_ev, 0));
+            char *dst = (blocks ? g.tab_base : g.tab_base + (int64_t)t.slot * g.slot_bytes) + (size_t)l * width;
             TC_HIP(ctx, hipMemcpyAsync(dst, t.host_k + (size_t)l * width, width * (e - l), hipMemcpyHostToDevice, stream));
             TC_HIP(ctx, hipMemcpyAsync(dst + (g.slot_bytes >> 1), t.host_v + (size_t)l * width, width * (e - l),
                                        hipMemcpyHostToDevice, stream));
+            if (blocks) {
+                TC_HIP(ctx, launch_format(g, g.tab_base, g.slot_bytes >> 1, t.n_tokens, t.slot * ctx->slot_blocks, l, e,
+                                          Launch{stream, nullptr, nullptr}));
+                TC_HIP(ctx, hipEventRecord(ctx->raw_ev, stream));
+                ctx->raw_stream = stream;
+                ctx->raw_pending = true;
+            }
             for (int x = l; x < e; ++x) t.layer_loaded[x] = 1;
             touched.insert(t.slot);
             l = e;
@@ -701,6 +757,8 @@ static tc_status stitch_common(tc_ctx *ctx, const int32_t *table_ids, const int3
                                double rope_theta)
 {
     if (!ctx) return TC_ERR_INVALID;
+    if (ctx->cfg.slot_layout != TC_SLOTS_ROWS)
+        return fail(ctx, TC_ERR_INVALID, "stitch: this context keeps tables in block format; use tc_stitch_alias");
     if (B < 0 || max_blocks < 0) return fail(ctx, TC_ERR_INVALID, "stitch: negative size");
     if (B > 0 && (!cu_tables || !suffix_len || !block_table || !prefix_len))
         return fail(ctx, TC_ERR_INVALID, "stitch: null argument");
@@ -827,6 +885,98 @@ tc_status tc_stitch_kv_rope(tc_ctx *ctx, const int32_t *table_ids, const int32_t
                          true, pos0, rope_theta);
 }
 
+tc_status tc_stitch_alias(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_tables, int32_t B,
+                          const int32_t *suffix_len, int32_t *block_table, int32_t max_blocks,
+                          int32_t *prefix_len, void *stream_)
+{
+    if (!ctx) return TC_ERR_INVALID;
+    if (ctx->cfg.slot_layout != TC_SLOTS_BLOCKS)
+        return fail(ctx, TC_ERR_INVALID, "alias: this context keeps tables as token rows; use tc_stitch_kv");
+    if (B < 0 || max_blocks < 0) return fail(ctx, TC_ERR_INVALID, "alias: negative size");
+    if (B > 0 && (!cu_tables || !suffix_len || !block_table || !prefix_len))
+        return fail(ctx, TC_ERR_INVALID, "alias: null argument");
+    if (B > 0 && (cu_tables[0] != 0)) return fail(ctx, TC_ERR_INVALID, "alias: cu_tables[0] != 0");
+    hipStream_t stream = (hipStream_t)stream_;
+    const int L = ctx->cfg.n_layers;
+
+    // ---- validate and size everything before touching any state
+    std::vector<int32_t> n_pref(B), n_suf(B);
+    int64_t need_total = 0, total_S = 0;
+    for (int i = 0; i < B; ++i) {
+        if (cu_tables[i + 1] < cu_tables[i]) return fail(ctx, TC_ERR_INVALID, "alias: cu_tables not monotone");
+        if (cu_tables[i + 1] > cu_tables[i] && !table_ids) return fail(ctx, TC_ERR_INVALID, "alias: null table_ids");
+        if (suffix_len[i] < 0) return fail(ctx, TC_ERR_INVALID, "alias: negative suffix_len");
+        int64_t nb = 0;
+        for (int k = cu_tables[i]; k < cu_tables[i + 1]; ++k) {
+            auto it = ctx->tables.find(table_ids[k]);
+            if (it == ctx->tables.end()) return fail(ctx, TC_ERR_UNKNOWN_TABLE, "alias: table %d not registered", table_ids[k]);
+            const Table &t = it->second;
+            bool all = t.slot >= 0;
+            for (int l = 0; all && l < L; ++l) all = t.layer_loaded[l] != 0;
+            if (!all) return fail(ctx, TC_ERR_NOT_RESIDENT, "alias: table %d is not device-resident", table_ids[k]);
+            nb += (t.n_tokens + kBlockTokens - 1) / kBlockTokens;
+            if (nb * kBlockTokens + suffix_len[i] > INT32_MAX / 2) return fail(ctx, TC_ERR_INVALID, "alias: sequence too long");
+        }
+        n_pref[i] = (int32_t)nb;
+        n_suf[i] = (suffix_len[i] + kBlockTokens - 1) / kBlockTokens;
+        if (nb + n_suf[i] > max_blocks)
+            return fail(ctx, TC_ERR_OOM_POOL, "alias: query %d needs %lld blocks, max_blocks is %d", i, (long long)(nb + n_suf[i]), max_blocks);
+        need_total += n_suf[i];
+        total_S += suffix_len[i];
+    }
+    if (need_total > (int64_t)ctx->free_seq.size())
+        return fail(ctx, TC_ERR_OOM_POOL, "alias: need %lld sequence blocks, %zu free", (long long)need_total, ctx->free_seq.size());
+    if (total_S > INT32_MAX / 2) return fail(ctx, TC_ERR_INVALID, "alias: batch too long");
+
+    // ---- the plan: each table contributes the blocks of its slot, the suffix gets blocks of its own
+    Plan p;
+    p.B = B; p.max_blocks = max_blocks; p.total_S = (int32_t)total_S;
+    p.block_table.assign((size_t)B * max_blocks, -1);
+    p.block_pad.assign((size_t)B * max_blocks, 0);
+    p.cu_seqlens.assign(B + 1, 0);
+    p.prefix_len.assign(B, 0);
+    p.suffix_len.assign(suffix_len, suffix_len + B);
+    std::set<int32_t> used_slots;
+    auto next_free = ctx->free_seq.begin();
+    for (int i = 0; i < B; ++i) {
+        p.cu_seqlens[i + 1] = p.cu_seqlens[i] + suffix_len[i];
+        p.prefix_len[i] = n_pref[i] * kBlockTokens;
+        size_t at = (size_t)i * max_blocks;
+        for (int k = cu_tables[i]; k < cu_tables[i + 1]; ++k) {
+            const Table &t = ctx->tables[table_ids[k]];
+            const int nb = (t.n_tokens + kBlockTokens - 1) / kBlockTokens;
+            for (int j = 0; j < nb; ++j, ++at) p.block_table[at] = t.slot * ctx->slot_blocks + j;
+            p.block_pad[at - 1] = (uint8_t)(nb * kBlockTokens - t.n_tokens);
+            used_slots.insert(t.slot);
+        }
+        for (int j = 0; j < n_suf[i]; ++j, ++next_free, ++at) p.block_table[at] = *next_free;
+    }
+    p.alias_slots.assign(used_slots.begin(), used_slots.end());
+    tc_status st = upload_plan(ctx, p, {}, {}, {}, stream);
+    if (st != TC_OK) return st;               // nothing allocated yet
+
+    // ---- commit: take the suffix blocks; whatever follows on `stream` comes after the loads it reads
+    for (int i = 0; i < B; ++i)
+        for (int j = n_pref[i]; j < n_pref[i] + n_suf[i]; ++j) {
+            const int32_t phys = p.block_table[(size_t)i * max_blocks + j];
+            ctx->free_seq.erase(phys);
+            ctx->seq_used[phys - ctx->first_seq] = 1;
+        }
+    for (int32_t s : used_slots) {
+        Slot &sl = ctx->slots[s];
+        if (sl.ready_pending && sl.ready_stream != stream)
+            TC_HIP(ctx, hipStreamWaitEvent(stream, sl.ready, 0));
+        sl.reader_stream = stream;
+        sl.reader_pending = true;
+    }
+    ctx->plan = std::move(p);
+    if (B > 0) {
+        std::memcpy(block_table, ctx->plan.block_table.data(), (size_t)B * max_blocks * sizeof(int32_t));
+        std::memcpy(prefix_len, ctx->plan.prefix_len.data(), (size_t)B * sizeof(int32_t));
+    }
+    return TC_OK;
+}
+
 tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,
                           void *out, const int32_t *cu_seqlens, const int32_t *block_table,
                           int32_t max_blocks, const int32_t *prefix_len, const int32_t *suffix_len,
@@ -873,6 +1023,10 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
     Plan &p = ctx->plan;
     if (p.total_S == 0) return TC_OK;
     if (!q || !k_new || !v_new || !out) return fail(ctx, TC_ERR_INVALID, "attn: null tensor");
+    for (int32_t sidx : p.alias_slots) {        // this launch reads these table slots in place
+        ctx->slots[sidx].reader_stream = stream;
+        ctx->slots[sidx].reader_pending = true;
+    }
     if (((uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)out) & 15)
         return fail(ctx, TC_ERR_INVALID, "attn: tensors must be 16-byte aligned");
 
@@ -909,6 +1063,7 @@ tc_status tc_release_seqs(tc_ctx *ctx, const int32_t *block_table, int32_t max_b
     for (size_t k = 0; k < n; ++k) {
         const int32_t b = block_table[k];
         if (b < 0) continue;
+        if (ctx->cfg.slot_layout == TC_SLOTS_BLOCKS && b < ctx->first_seq) continue;   // a table slot's block, aliased
         if (b < ctx->first_seq || b >= ctx->cfg.n_pool_blocks || !ctx->seq_used[b - ctx->first_seq] || !seen.insert(b).second)
             return fail(ctx, TC_ERR_INVALID, "release: %d is not an allocated sequence block", b);
     }
@@ -916,7 +1071,8 @@ tc_status tc_release_seqs(tc_ctx *ctx, const int32_t *block_table, int32_t max_b
         ctx->seq_used[b - ctx->first_seq] = 0;
         ctx->free_seq.insert(b);
     }
-    if (ctx->plan.valid && !seen.empty()) ctx->plan.valid = false;   // its blocks may be handed out again
+    if (ctx->plan.valid && (!seen.empty() || !ctx->plan.alias_slots.empty()))
+        ctx->plan.valid = false;               // its blocks may be handed out again
     return TC_OK;
 }
 
@@ -929,7 +1085,7 @@ tc_status tc_read_seq_kv(tc_ctx *ctx, int32_t layer, const int32_t *blocks, int3
     if (!blocks || !out_k || !out_v) return fail(ctx, TC_ERR_INVALID, "read: null argument");
     const int nb = (n_tokens + kBlockTokens - 1) / kBlockTokens;
     for (int j = 0; j < nb; ++j)
-        if (blocks[j] < ctx->first_seq || blocks[j] >= ctx->cfg.n_pool_blocks)
+        if (blocks[j] < (ctx->cfg.slot_layout == TC_SLOTS_BLOCKS ? 0 : ctx->first_seq) || blocks[j] >= ctx->cfg.n_pool_blocks)
             return fail(ctx, TC_ERR_INVALID, "read: block %d is not a sequence block", blocks[j]);
     hipStream_t stream = (hipStream_t)stream_;
     const size_t bytes = (size_t)n_tokens * ctx->geom.row_bytes;

@@ -14,6 +14,15 @@ constexpr int kAttnMaxTiles = 256;   // bf16 kernel: key tiles per work item (bl
 constexpr int kF32Rows = 4;          // fp32 kernel: rows per work-group (one per wave)
 constexpr int kF32Keys = 64;         // fp32 kernel: keys per tile
 
+// Block-table entries as the kernels see them (device copies only; the caller's tables hold plain
+// ids): the low 27 bits are the block id; the bits above count the unused token positions at the
+// end of the block (0..15).  Only blocks of a table slot that a sequence aliases have any: a table
+// of n tokens fills its last block up to n mod 16, the rest is zeros.
+constexpr uint32_t kBidMask = (1u << 27) - 1;
+constexpr int kPadShift = 27;
+__host__ __device__ inline int32_t entry_bid(int32_t e) { return (int32_t)((uint32_t)e & kBidMask); }
+__host__ __device__ inline int32_t entry_pad(int32_t e) { return (int32_t)((uint32_t)e >> kPadShift); }
+
 // Pool geometry, passed by value to kernels.
 struct Geom {
     char *pool;              // sequence region, biased so that block id b of layer l starts at
@@ -71,9 +80,11 @@ struct AttnItem {
     int32_t group;       // index of the (query, KV head, row tile): partial slots and arrival counter
     int32_t P, S, cu;    // prefix length, suffix length, first suffix row of the query
     int32_t n_groups;    // total number of groups in the batch
-    int32_t bid[16];     // block ids of the first four key tiles of the range (clamped to the sequence)
+    int32_t bid[16];     // block-table entries of the first four key tiles of the range (clamped to the sequence)
+    int32_t n_pad_fast;  // unused token positions inside the leading run of full prefix tiles of the range
+    int32_t rsv[3];
 };
-static_assert(sizeof(AttnItem) == 112, "AttnItem layout");
+static_assert(sizeof(AttnItem) == 128, "AttnItem layout");
 
 // A (query, KV head, row tile) whose partitions the bf16 merge kernel combines.
 struct MergeGroup {
@@ -105,6 +116,8 @@ struct Launch {
 
 // kv_stitch.hip
 hipError_t launch_stitch(const Geom &g, const BatchDev &b, int l0, int l1, bool rope, const Launch &L);
+hipError_t launch_format(const Geom &g, const void *raw, int64_t v_part, int n_tokens, int first_block, int l0,
+                         int l1, const Launch &L);
 hipError_t launch_append(const Geom &g, const BatchDev &b, int layer, const void *k_new,
                          const void *v_new, const Launch &L);
 hipError_t launch_readback(const Geom &g, int layer, const int32_t *blocks_dev, int n_tokens,

@@ -28,7 +28,7 @@ class DeviceWorkload:
     """A workload registered with a library context; tables loaded into the device cache."""
 
     def __init__(self, wl: W.Workload, seq_blocks: int = None, capacity: int = None,
-                 policy: int = 0, load_all: bool = True, tables=None):
+                 policy: int = 0, load_all: bool = True, tables=None, slot_layout: int = 0):
         from paper_2601_08743_amd import binding as B
         self.B = B
         self.wl = wl
@@ -43,7 +43,8 @@ class DeviceWorkload:
         n_blocks = cap * slot_blocks + seq_blocks
         self.tc_cfg = B.make_config(c.n_layers, c.n_q_heads, c.n_kv_heads, c.head_dim,
                                     B.TC_F32 if c.dtype == "f32" else B.TC_BF16, n_blocks, cap,
-                                    max_tok, policy)
+                                    max_tok, policy, slot_layout=slot_layout)
+        self.slot_blocks = slot_blocks
         nbytes = B.tc_pool_bytes(self.tc_cfg)
         assert nbytes > 0
         # poison the pool: NaN patterns in both element types, so that any slot read without
@@ -73,6 +74,14 @@ class DeviceWorkload:
             max_blocks = max(-(-(p + int(s)) // 16) for p, s in zip(P, wl.suffix_len)) + 1
         bt, pl = self.ctx.tc_stitch_kv(wl.table_ids, wl.cu_tables, wl.suffix_len, max_blocks, stream)
         return bt, pl
+
+    def alias(self, max_blocks: int = None, stream=None):
+        """The batch's sequences made by pointing at the table slots' blocks (block-format slots)."""
+        wl = self.wl
+        if max_blocks is None:
+            max_blocks = max(sum(-(-int(wl.table_len[t]) // 16) for t in q) + -(-int(s) // 16)
+                             for q, s in zip(wl.queries, wl.suffix_len)) + 1
+        return self.ctx.tc_stitch_alias(wl.table_ids, wl.cu_tables, wl.suffix_len, max_blocks, stream)
 
     def attn_layer(self, layer: int, bt, pl, stream=None, qkv=None):
         wl, c = self.wl, self.cfg

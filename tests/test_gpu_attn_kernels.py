@@ -234,3 +234,38 @@ def test_random_batches_through_both_kernels(H, seed):
     print("seed %d: B %d P %s S %s partitions %d: kernels differ by %.3e" % (
         seed, B, [int(table_len[q].sum()) for q in queries], suffix.tolist(), splits,
         float(np.abs(outs[1] - outs[2]).max())))
+
+
+@pytest.mark.parametrize("heads", [(8, 8), (32, 8), (8, 2), (28, 4)])
+def test_repeated_launches_are_bit_identical(H, heads):
+    """The same launch on the same inputs must return the same bits every time, from the first
+    launch of a fresh context on: nothing in the kernels is allowed to depend on what earlier
+    kernels left in LDS or registers, or on when a tile arrives.  Short prefixes (3 .. 7 key tiles,
+    with and without a ragged one) and short suffixes, where a work-group's start-up is most of
+    its life; the last launch is also compared with the checker."""
+    Hq, Hkv = heads
+    P = [192, 200, 256, 260, 320, 391, 448]
+    S = [1, 5, 40, 1, 20, 5, 40]
+    wl = _one_table_per_query(P, S, seed=777)
+    wl = W.Workload(W.scaled(wl.cfg, n_q_heads=Hq, n_kv_heads=Hkv), wl.table_len, wl.queries, wl.suffix_len)
+    q, k, v = wl.suffix_qkv(0)
+    for kind in (2, 1):
+        dw = H.DeviceWorkload(wl)
+        dw.ctx.tc_set_attn_kernel(kind)
+        dw.ctx.tc_set_kv_splits(1)
+        bt, pl = dw.stitch()
+        dq, dk, dv = (H.to_dev(x, wl.cfg) for x in (q, k, v))
+        outs = []
+        for rep in range(5):
+            out = torch.full_like(dq, float("nan"))
+            dw.ctx.tc_prefill_attn(0, dq, dk, dv, out, wl.cu_seqlens, bt, pl, wl.suffix_len, wl.sm_scale, None)
+            torch.cuda.synchronize()
+            outs.append(out.view(torch.int16).cpu().numpy())
+        for rep in range(4):
+            np.testing.assert_array_equal(outs[rep], outs[4], err_msg="kernel %d, launch %d differs from launch 4" % (kind, rep))
+        ref = H.oracle_attn_layer(wl, dw.tables_np, 0, (q, k, v))
+        got = H.out_to_f64(out, wl.cfg)
+        for i, r in ref.items():
+            sl = slice(int(wl.cu_seqlens[i]), int(wl.cu_seqlens[i + 1]))
+            assert np.abs(got[sl] - r).max() <= TOL, (kind, P[i], S[i])
+        dw.close()

@@ -122,3 +122,20 @@ def test_lru_equals_stack_distance_rule():
             assert hit == 0
         else:
             assert hit == int(len(set(acc[prev[-1] + 1:i])) < C)
+
+
+def test_alias_block_table_hand_worked():
+    """Concatenation by block table alone: slot s owns blocks 3s, 3s+1, 3s+2 (tables of up to 48
+    tokens); sequence blocks start at 12.  Tables: 7 -> slot 2 (20 tokens: two blocks, 4 tokens in
+    the second), 9 -> slot 0 (16 tokens: one full block), 4 -> slot 3 (1 token)."""
+    slots = oracle.SlotModel(4)
+    # misses fill slots 0, 1, 2, 3 in order; then table 4 evicts table 5 and inherits its slot
+    slots.apply([(9, 0, -1), (8, 0, -1), (7, 0, -1), (5, 0, -1), (9, 1, -1), (4, 0, 5)])
+    assert slots.slot == {9: 0, 8: 1, 7: 2, 4: 3}
+    seq = oracle.SeqBlockModel(12, 8)
+    table_len = {7: 20, 9: 16, 4: 1, 8: 48}
+    bt, padded, valid = oracle.alias_block_table(seq, slots.slot, table_len, [[7, 9], [], [4, 7]], [17, 3, 0], 3, 6)
+    assert bt.tolist() == [[6, 7, 0, 12, 13, -1], [14, -1, -1, -1, -1, -1], [9, 6, 7, -1, -1, -1]]
+    assert padded.tolist() == [48, 0, 48]
+    assert valid == [[16, 4, 16], [], [1, 16, 4]]
+    assert seq.free == [15, 16, 17, 18, 19]
