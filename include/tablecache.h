@@ -330,6 +330,9 @@ tc_status tc_rerank(const int32_t *table_ids, const int32_t *cu_tables, int32_t 
  * The prefetch range ends at compute_end + b_m, or earlier where the distinct tables of
  * the requests loaded but not yet computed would exceed `capacity` (they are pinned until
  * their stitch).  b_m = 0 gives the schedule without overlap.
+ * keep_pinned != 0: the step's own tables stay pinned until its attention layers are enqueued
+ * (tc_stitch_alias: the layers read the table slots in place), so they count against the cache
+ * while the prefetch range is sized; the caller then unpins after the layers, not after the stitch.
  *   table_ids, cu_tables   HOST, request i uses table_ids[cu_tables[i] .. cu_tables[i+1]).
  *   steps_out              HOST, room for `cap` steps; n_queries always suffice.
  * Returns the number of steps, or a negative tc_status: TC_ERR_INVALID (null pointers,
@@ -342,7 +345,8 @@ typedef struct tc_pipe_step {
     int32_t prefetch_begin, prefetch_end;
 } tc_pipe_step;
 int32_t tc_plan_pipeline(const int32_t *table_ids, const int32_t *cu_tables, int32_t n_queries,
-                         int32_t capacity, int32_t b_c, int32_t b_m, tc_pipe_step *steps_out, int32_t cap);
+                         int32_t capacity, int32_t b_c, int32_t b_m, int32_t keep_pinned,
+                         tc_pipe_step *steps_out, int32_t cap);
 
 const char *tc_last_error(const tc_ctx *ctx);
 /* Library version string. */

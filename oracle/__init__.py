@@ -313,7 +313,8 @@ def replay(model, accesses: Sequence[int]) -> List[Tuple[int, int, int]]:
 
 # ----------------------------------------------------------------------------- Sec. 4.2.2: pipeline schedule
 
-def plan_pipeline(table_sets: Sequence[Sequence[int]], capacity: int, b_c: int, b_m: int):
+def plan_pipeline(table_sets: Sequence[Sequence[int]], capacity: int, b_c: int, b_m: int,
+                  keep_pinned: bool = False):
     """Sec. 4.2.2, computation-loading pipeline over an ordered batch: the requests are computed
     b_c at a time, and while a micro-batch is computed the tables of the next b_m requests are
     copied in.  Returns one tuple per micro-batch,
@@ -322,7 +323,9 @@ def plan_pipeline(table_sets: Sequence[Sequence[int]], capacity: int, b_c: int, 
     before its stitch), `prefetch` those asked for right after its stitch.  Requests asked for
     but not yet stitched keep their tables pinned, so a prefetch stops early where the union of
     their tables would outgrow the cache; for the same reason a micro-batch holds fewer than b_c
-    requests where the tables of b_c would not fit together (the next one starts there)."""
+    requests where the tables of b_c would not fit together (the next one starts there).
+    `keep_pinned`: the micro-batch being computed keeps its tables pinned as well (a stitch that
+    points at the cached tables instead of copying them), so they count while the prefetch is sized."""
     N, steps, asked, c0 = len(table_sets), [], 0, 0
     uni = lambda a, b: set().union(*[set(map(int, x)) for x in table_sets[a:b]]) if b > a else set()
     while c0 < N:
@@ -335,17 +338,19 @@ def plan_pipeline(table_sets: Sequence[Sequence[int]], capacity: int, b_c: int, 
         if c1 == c0:
             raise ValueError("request %d alone needs more than %d tables" % (c0, capacity))
         d1 = p0 = asked
-        while asked < N and asked < c1 + b_m and len(uni(c1, asked + 1)) <= capacity:
+        while asked < N and asked < c1 + b_m and len(uni(c0 if keep_pinned else c1, asked + 1)) <= capacity:
             asked += 1
         steps.append((c0, c1, d0, d1, p0, asked))
         c0 = c1
     return steps
 
 
-def simulate_pipeline(model, table_sets: Sequence[Sequence[int]], steps) -> List[Tuple[int, int, int]]:
+def simulate_pipeline(model, table_sets: Sequence[Sequence[int]], steps,
+                      keep_pinned: bool = False) -> List[Tuple[int, int, int]]:
     """Access trace (table, hit, evicted or -1) of the replacement model when the schedule of
     `plan_pipeline` is carried out: a range of requests is asked for by pinning all its tables
-    and then requesting them in order; a micro-batch is unpinned once it is stitched."""
+    and then requesting them in order; a micro-batch is unpinned once it is stitched (or, with
+    `keep_pinned`, after the prefetch behind it has been asked for)."""
     pins: Dict[int, int] = {}
     out = []
 
@@ -357,14 +362,20 @@ def simulate_pipeline(model, table_sets: Sequence[Sequence[int]], steps) -> List
             hit, ev = model.access(t, pinned=pins)
             out.append((t, int(hit), -1 if ev is None else int(ev)))
 
-    for c0, c1, d0, d1, p0, p1 in steps:
-        ask(d0, d1)
-        for q in table_sets[c0:c1]:
+    def unpin(a, b):
+        for q in table_sets[a:b]:
             for t in q:
                 pins[int(t)] -= 1
                 if pins[int(t)] == 0:
                     del pins[int(t)]
+
+    for c0, c1, d0, d1, p0, p1 in steps:
+        ask(d0, d1)
+        if not keep_pinned:
+            unpin(c0, c1)
         ask(p0, p1)
+        if keep_pinned:
+            unpin(c0, c1)
     return out
 
 

@@ -135,7 +135,8 @@ tc_status tc_rerank(const int32_t *table_ids, const int32_t *cu_tables, int32_t 
 // whose stitch has not been issued slides over the ordered batch; `held` counts, per table, the
 // window's requests that use it, so its size is the number of slots the window pins.
 int32_t tc_plan_pipeline(const int32_t *table_ids, const int32_t *cu_tables, int32_t n_queries,
-                         int32_t capacity, int32_t b_c, int32_t b_m, tc_pipe_step *steps_out, int32_t cap)
+                         int32_t capacity, int32_t b_c, int32_t b_m, int32_t keep_pinned, tc_pipe_step *steps_out,
+                         int32_t cap)
 {
     if (n_queries < 0 || capacity < 0 || b_c < 1 || b_m < 0 || cap < 0) return TC_ERR_INVALID;
     if (n_queries == 0) return 0;
@@ -177,12 +178,17 @@ int32_t tc_plan_pipeline(const int32_t *table_ids, const int32_t *cu_tables, int
         st.compute_end = frontier < full ? frontier : (int32_t)full;
         if (st.compute_end == c0) return TC_ERR_CAPACITY;       // one request alone outgrows the cache
         st.demand_end = frontier;
-        for (int32_t i = c0; i < st.compute_end; ++i) drop(i);  // stitched: no longer held
+        // a copying stitch is done with the tables once it is enqueued; an aliasing one leaves the
+        // attention layers reading them, so they stay held while the prefetch is sized
+        if (!keep_pinned)
+            for (int32_t i = c0; i < st.compute_end; ++i) drop(i);
         st.prefetch_begin = frontier;
         const int64_t want = (int64_t)st.compute_end + b_m;
         while (frontier < n_queries && frontier < want && (int64_t)held.size() + fresh(frontier) <= capacity)
             add(frontier++);
         st.prefetch_end = frontier;
+        if (keep_pinned)
+            for (int32_t i = c0; i < st.compute_end; ++i) drop(i);
         c0 = st.compute_end;
     }
     return n_steps;

@@ -3,7 +3,8 @@
 The schedule comes from ``tc_plan_pipeline``; this module only carries it out: which library call
 is made when.  A range of requests is "asked for" by pinning all its tables and then requesting
 them, in batch order, on the load stream; a micro-batch is unpinned as soon as its stitch is
-enqueued (the library orders later copies into its slots behind that stitch).
+enqueued (the library orders later copies into its slots behind that stitch), or, when the stitch
+aliases the table slots instead of copying them, as soon as its attention layers are.
 """
 from __future__ import annotations
 
@@ -20,20 +21,21 @@ def flat_tables(queries: Sequence[np.ndarray], a: int, b: int) -> np.ndarray:
     return np.concatenate([np.asarray(q, dtype=np.int32) for q in queries[a:b]]).astype(np.int32)
 
 
-def plan(queries: Sequence[np.ndarray], capacity: int, b_c: int, b_m: int) -> np.ndarray:
+def plan(queries: Sequence[np.ndarray], capacity: int, b_c: int, b_m: int, keep_pinned: bool = False) -> np.ndarray:
     ids = flat_tables(queries, 0, len(queries))
     cu = np.concatenate([[0], np.cumsum([len(q) for q in queries])]).astype(np.int32)
-    return B.tc_plan_pipeline(ids, cu, capacity, b_c, b_m)
+    return B.tc_plan_pipeline(ids, cu, capacity, b_c, b_m, keep_pinned)
 
 
 def run(ctx: "B.Context", queries: Sequence[np.ndarray], steps: np.ndarray, l0: int, l1: int, load_stream,
         stitch: Callable[[int, int], object], layers: Callable[[int, int, object], None],
-        before_demand: Callable[[], None] = None) -> None:
+        before_demand: Callable[[], None] = None, keep_pinned: bool = False) -> None:
     """Carry out `steps`.  `stitch(c0, c1)` must enqueue the stitch of requests [c0, c1) and return
     whatever `layers(c0, c1, handle)` needs to run their attention layers and release them.
     `before_demand()` is called ahead of each step's demand loads: a baseline without any overlap
     waits there for the device to go idle (the host otherwise runs ahead, and even demand loads
-    overlap the previous step's layers)."""
+    overlap the previous step's layers).  `keep_pinned` (schedules planned with it; aliasing
+    stitch): a micro-batch's tables are unpinned after its layers are enqueued, not after its stitch."""
 
     def ask(a: int, b: int) -> None:
         ids = flat_tables(queries, a, b)
@@ -46,6 +48,9 @@ def run(ctx: "B.Context", queries: Sequence[np.ndarray], steps: np.ndarray, l0: 
             before_demand()
         ask(d0, d1)
         handle = stitch(c0, c1)
-        ctx.tc_unpin_tables(flat_tables(queries, c0, c1))
+        if not keep_pinned:
+            ctx.tc_unpin_tables(flat_tables(queries, c0, c1))
         ask(p0, p1)
         layers(c0, c1, handle)
+        if keep_pinned:
+            ctx.tc_unpin_tables(flat_tables(queries, c0, c1))

@@ -135,3 +135,27 @@ def test_simulated_trace_visits_the_requests_in_order(cls):
     for b_c, b_m in ((1, 0), (2, 2), (3, 7), (4, 1)):
         steps = oracle.plan_pipeline(sets, 10, b_c, b_m)
         assert oracle.simulate_pipeline(cls(10), sets, steps) == oracle.replay(cls(10), flat)
+
+
+def test_plan_with_the_computing_batch_kept_pinned():
+    sets = [[0, 1], [1, 2], [3], [4], [5]]
+    # C=4, b_c=2, b_m=2: while requests 0,1 (tables 0 1 2) are computed they stay pinned, so only
+    # request 2 (table 3) can be prefetched; request 3 is then asked for on demand
+    assert oracle.plan_pipeline(sets, 4, 2, 2, keep_pinned=True) == [(0, 2, 0, 2, 2, 3), (2, 4, 3, 4, 4, 5),
+                                                                   (4, 5, 5, 5, 5, 5)]
+    # without, the cache has room for requests 2 and 3 behind the stitch of 0 and 1
+    assert oracle.plan_pipeline(sets, 4, 2, 2) == [(0, 2, 0, 2, 2, 4), (2, 4, 4, 4, 4, 5), (4, 5, 5, 5, 5, 5)]
+    rng = np.random.default_rng(8)
+    for trial in range(100):
+        n = int(rng.integers(1, 30))
+        s = _random_sets(rng, n, 10, 3)
+        b_c, b_m, C = int(rng.integers(1, 4)), int(rng.integers(0, 6)), int(rng.integers(3, 11))
+        steps = oracle.plan_pipeline(s, C, b_c, b_m, keep_pinned=True)
+        uni = lambda a, b: set().union(*map(set, s[a:b])) if b > a else set()
+        for c0, c1, d0, d1, p0, p1 in steps:
+            assert len(uni(c0, p1)) <= C                       # computing batch and prefetch window together
+            if p1 < n and p1 < c1 + b_m:
+                assert len(uni(c0, p1 + 1)) > C
+        for cls in MODELS:                                     # and the cache then really holds them all
+            m = cls(C)
+            oracle.simulate_pipeline(m, s, steps, keep_pinned=True)
