@@ -237,6 +237,69 @@ def frontend_extras(wl):
     return {"frontend_match_mtok_s": round(n_tok / dt / 1e6, 2), "frontend_rerank_1024q_ms": round(dt_r * 1e3, 3)}
 
 
+def zero_copy_extras(args, wl, qkv, outs_copy, flops_step, stream):
+    """The same step with the stitch that copies nothing (a second context whose table slots are
+    kept in block format; tc_stitch_alias builds the sequences by pointing at them): an extra
+    measurement beside the headline step, which keeps the gather it is named for.  The last
+    layer's output is compared with the copying path's (same inputs; the padded key tiles change
+    rounding only)."""
+    import torch
+    from paper_2601_08743_amd import binding as B
+    c = wl.cfg
+    max_tok = int(wl.table_len.max())
+    need = [sum(-(-int(wl.table_len[t]) // 16) for t in q) + -(-int(s) // 16) for q, s in zip(wl.queries, wl.suffix_len)]
+    n_blocks = c.capacity * (-(-max_tok // 16)) + sum(-(-int(s) // 16) for s in wl.suffix_len) + 8
+    cfg = B.make_config(c.n_layers, c.n_q_heads, c.n_kv_heads, c.head_dim, B.TC_BF16, n_blocks, c.capacity, max_tok,
+                        slot_layout=B.TC_SLOTS_BLOCKS)
+    pool = torch.empty(B.tc_pool_bytes(cfg), dtype=torch.uint8, device="cuda")
+    ctx = B.Context(cfg, pool)
+    keep = []
+    for t in range(c.n_tables):
+        k, v = wl.table_kv(t)
+        hk, hv = torch.from_numpy(k).pin_memory(), torch.from_numpy(v).pin_memory()
+        keep.append((hk, hv))
+        ctx.tc_register_table_kv(t, int(wl.table_len[t]), hk, hv)
+    ctx.tc_load_async(list(range(c.n_tables))[:c.capacity], 0, c.n_layers, stream)
+    torch.cuda.synchronize()
+    ids, cu_t, cu_s, sl = wl.table_ids, wl.cu_tables, wl.cu_seqlens, wl.suffix_len
+    max_blocks = max(need) + 1
+    outs = [torch.empty_like(o) for o in outs_copy]
+
+    def run(n):
+        for _ in range(n):
+            bt, pl = ctx.tc_stitch_alias(ids, cu_t, sl, max_blocks, stream)
+            for l in range(c.n_layers):
+                q, k, v = qkv[l]
+                ctx.tc_prefill_attn(l, q, k, v, outs[l], cu_s, bt, pl, sl, wl.sm_scale, stream)
+            ctx.tc_release_seqs(bt)
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    t0 = time.perf_counter()
+    for _ in range(20):
+        bt, pl = ctx.tc_stitch_alias(ids, cu_t, sl, max_blocks, stream)
+        ctx.tc_release_seqs(bt)
+    host_us = (time.perf_counter() - t0) * 1e6 / 20
+    torch.cuda.synchronize()
+    ctx.tc_profile_enable(True)
+    run(max(3, args.steps // 5))
+    torch.cuda.synchronize()
+    prof = ctx.tc_profile_read()
+    ctx.tc_profile_enable(False)
+    diff = float((outs[-1].float() - outs_copy[-1].float()).abs().max())
+    res = {"zero_copy_ms_per_step": round(ms, 4), "zero_copy_tflops": round(flops_step / (ms * 1e-3) / 1e12, 3),
+           "zero_copy_stitch_host_us": round(host_us, 1),
+           "zero_copy_attn_kernel_us": round(prof["attn"][0] * 1e3 / max(prof["attn"][1], 1), 2),
+           "zero_copy_max_abs_vs_copy": diff}
+    torch.cuda.synchronize()
+    ctx.tc_destroy()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -246,6 +309,9 @@ def main():
     ap.add_argument("--splits", type=int, default=0, help="force split-KV partitions (0 = automatic)")
     ap.add_argument("--row-blocks", type=int, default=0, help="force 128 (1) or 256 (2) rows per work-group")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the headline step: skip the extra measurements (re-encoding stitch, front end, "
+                         "stitch without copying, graph replay); used for profiler runs")
     ap.add_argument("--no-graph", action="store_true", help="skip the extra timing of the layer loop replayed as a HIP graph")
     ap.add_argument("--micro-batch", type=int, default=8, help="b_c: requests computed per micro-batch (c5 pipeline)")
     ap.add_argument("--prefetch", type=int, default=-1, help="b_m: requests loaded ahead (c5 pipeline; default b_c, 0 = no overlap)")
@@ -373,23 +439,28 @@ def main():
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
     extra = {}
+    if args.no_extras:
+        args.no_graph = True
     # the re-encoding stitch (keys rotary-encoded by position while they are copied): same bytes, an
     # extra measurement beside the step; the step itself uses the plain stitch
     ctx.tc_release_seqs(bt)
-    ctx.tc_profile_enable(True)
+    ctx.tc_profile_enable(not args.no_extras)
     ctx.tc_profile_read()
-    for _ in range(max(3, args.steps // 5)):
-        bt_r, _ = ctx.tc_stitch_kv_rope(ids, cu_t, sl, None, 1.0e6, max_blocks, stream)
-        ctx.tc_release_seqs(bt_r)
-    torch.cuda.synchronize()
-    prof_r = ctx.tc_profile_read()
-    ctx.tc_profile_enable(False)
-    rope_us = prof_r["stitch"][0] * 1e3 / max(prof_r["stitch"][1], 1)
-    extra["stitch_rope_kernel_us"] = round(rope_us, 2)
-    extra["stitch_rope_gbps"] = round(stitch_bytes / (rope_us * 1e-6) / 1e9, 1)
-    extra["stitch_rope_frac_hbm"] = round(stitch_bytes / (rope_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4)
+    if not args.no_extras:
+        for _ in range(max(3, args.steps // 5)):
+            bt_r, _ = ctx.tc_stitch_kv_rope(ids, cu_t, sl, None, 1.0e6, max_blocks, stream)
+            ctx.tc_release_seqs(bt_r)
+        torch.cuda.synchronize()
+        prof_r = ctx.tc_profile_read()
+        ctx.tc_profile_enable(False)
+        rope_us = prof_r["stitch"][0] * 1e3 / max(prof_r["stitch"][1], 1)
+        extra["stitch_rope_kernel_us"] = round(rope_us, 2)
+        extra["stitch_rope_gbps"] = round(stitch_bytes / (rope_us * 1e-6) / 1e9, 1)
+        extra["stitch_rope_frac_hbm"] = round(stitch_bytes / (rope_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4)
+        extra.update(frontend_extras(wl))
+        if c.dtype == "bf16":
+            extra.update(zero_copy_extras(args, wl, qkv, outs, flops_step, stream))
     bt, pl = ctx.tc_stitch_kv(ids, cu_t, sl, max_blocks, stream)
-    extra.update(frontend_extras(wl))
     if not args.no_graph:
         g = torch.cuda.CUDAGraph()
         layers(bt, pl)
