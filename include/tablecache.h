@@ -243,6 +243,19 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
                           const int32_t *prefix_len, const int32_t *suffix_len, int32_t B,
                           float sm_scale, void *stream);
 
+/*
+ * Grow sequences for decoding: make sure query i's row of block_table has a block for every
+ * position below new_len[i] (its current blocks are the leading entries that are not -1; more
+ * are taken lowest-free-first, queries in order).  A decode step is then tc_prefill_attn with
+ * suffix_len = 1 and prefix_len = everything already in the pool (the tables' tokens, the prompt's
+ * own suffix, the tokens generated so far): the call appends the new token's K/V at position
+ * prefix_len and attends to all of it.  Sequences made by tc_stitch_kv only (copied prefixes).
+ *   block_table  HOST in/out [B][max_blocks];  new_len  HOST in [B]
+ * Errors: TC_ERR_OOM_POOL (max_blocks too small or no free block; nothing is changed),
+ * TC_ERR_INVALID.
+ */
+tc_status tc_grow_seqs(tc_ctx *ctx, int32_t *block_table, int32_t max_blocks, int32_t B, const int32_t *new_len);
+
 /* Return the sequence blocks named in block_table (HOST [B][max_blocks], -1 ignored) to
  * the free set.  The caller must have ordered this after the kernels that use them.
  * Errors: TC_ERR_INVALID if an entry is not an allocated sequence block (nothing freed). */

@@ -550,7 +550,7 @@ __device__ __forceinline__ void v_pack(uint32_t &d, float lo, float hi)
 // is free to put its own register copies of O (moves between accumulation registers where two
 // paths join, copies in and out of them) right next to one.  These two fences pin O down: each
 // names all of O as an operand, so every copy the compiler makes lands before `o_fence_in` or after
-// `o_fence_out`.  A matrix result must not be read for 11 cycles after issue (the compiler's own
+// `step_fence_out`.  A matrix result must not be read for 11 cycles after issue (the compiler's own
 // figure for this instruction): the closing fence sits right behind the step's last matrix
 // instruction and holds 12.  After the opening fence the first matrix instruction that reads O
 // comes more than ten instructions later, which covers the 2 cycles a freshly written register needs.
@@ -558,9 +558,13 @@ __device__ __forceinline__ void o_fence_in(f32x16 (&o)[4])
 {
     asm volatile("" : "+a"(o[0]), "+a"(o[1]), "+a"(o[2]), "+a"(o[3]));
 }
-__device__ __forceinline__ void o_fence_out(f32x16 (&o)[4])
+// The closing fence also names the score registers (ordinary VGPRs, written by the QK matrix
+// instructions): no compiler-made copy of them may follow the step's last matrix instructions
+// closely either.
+__device__ __forceinline__ void step_fence_out(f32x16 (&o)[4], f32x16 (&S)[4])
 {
-    asm volatile("s_nop 11" : "+a"(o[0]), "+a"(o[1]), "+a"(o[2]), "+a"(o[3]));
+    asm volatile("s_nop 11" : "+a"(o[0]), "+a"(o[1]), "+a"(o[2]), "+a"(o[3]),
+                              "+v"(S[0]), "+v"(S[1]), "+v"(S[2]), "+v"(S[3]));
 }
 
 // One step.  PAR = parity of s.  kb / vb: this lane's LDS read addresses for K(s+1) / V(s-1); the
@@ -627,7 +631,7 @@ __device__ __forceinline__ void fast_step(FastState &fs, f32x16 (&o)[4], const b
         }
         TC_SB();
     }
-    if (PV) o_fence_out(o);
+    step_fence_out(o, fs.S);
     // the stream's last stages (positions 27..31) run in the first slots of the next step
     l_cur = lc;
     l_nxt = ln;

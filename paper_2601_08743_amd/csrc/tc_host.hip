@@ -1053,6 +1053,41 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
     return TC_OK;
 }
 
+tc_status tc_grow_seqs(tc_ctx *ctx, int32_t *block_table, int32_t max_blocks, int32_t B, const int32_t *new_len)
+{
+    if (!ctx) return TC_ERR_INVALID;
+    if (B < 0 || max_blocks < 0 || (B > 0 && (!block_table || !new_len)))
+        return fail(ctx, TC_ERR_INVALID, "grow: bad arguments");
+    // size first, change nothing on failure
+    std::vector<int32_t> have(B), want(B);
+    int64_t need_total = 0;
+    for (int i = 0; i < B; ++i) {
+        if (new_len[i] < 0) return fail(ctx, TC_ERR_INVALID, "grow: negative length");
+        const int32_t *row = block_table + (size_t)i * max_blocks;
+        int h = 0;
+        while (h < max_blocks && row[h] >= 0) {
+            if (row[h] < ctx->first_seq || row[h] >= ctx->cfg.n_pool_blocks || !ctx->seq_used[row[h] - ctx->first_seq])
+                return fail(ctx, TC_ERR_INVALID, "grow: %d is not an allocated sequence block", row[h]);
+            ++h;
+        }
+        have[i] = h;
+        want[i] = (int32_t)(((int64_t)new_len[i] + kBlockTokens - 1) / kBlockTokens);
+        if (want[i] > max_blocks)
+            return fail(ctx, TC_ERR_OOM_POOL, "grow: query %d needs %d blocks, max_blocks is %d", i, want[i], max_blocks);
+        if (want[i] > h) need_total += want[i] - h;
+    }
+    if (need_total > (int64_t)ctx->free_seq.size())
+        return fail(ctx, TC_ERR_OOM_POOL, "grow: need %lld sequence blocks, %zu free", (long long)need_total, ctx->free_seq.size());
+    for (int i = 0; i < B; ++i)
+        for (int j = have[i]; j < want[i]; ++j) {
+            const int32_t phys = *ctx->free_seq.begin();
+            ctx->free_seq.erase(ctx->free_seq.begin());
+            ctx->seq_used[phys - ctx->first_seq] = 1;
+            block_table[(size_t)i * max_blocks + j] = phys;
+        }
+    return TC_OK;
+}
+
 tc_status tc_release_seqs(tc_ctx *ctx, const int32_t *block_table, int32_t max_blocks, int32_t B)
 {
     if (!ctx) return TC_ERR_INVALID;

@@ -7,7 +7,7 @@ register, for 11 wait states after issue, and the hardware does not interlock th
 keeps every such pair three or more slots apart; this test compiles the kernel to assembly and
 verifies it on what the compiler actually emitted: between a matrix instruction and the first
 non-matrix instruction that reads (or overwrites) any register of its result there are at least
-`MIN_GAP` issued instructions (an `s_nop n` counts n + 1)."""
+`MIN_GAP` issued instructions (an `s_nop n` counts n + 1), along every path of the control flow."""
 import os
 import re
 import subprocess
@@ -37,17 +37,23 @@ def _regs(text):
 
 
 def _kernel_instructions(asm_text):
+    """(op, operands) list of the kernel, and a map label -> index of the instruction that follows it."""
     lines = asm_text.splitlines()
     start = next(i for i, l in enumerate(lines) if re.match(r"^_ZN2tc\d+%s\w*:" % KERNEL, l))
     end = next(i for i in range(start, len(lines)) if lines[i].startswith(".Lfunc_end"))
-    ins = []
+    ins, labels = [], {}
     for l in lines[start + 1:end]:
         l = l.split(";")[0].strip()
-        if not l or l.endswith(":") or l.startswith("."):
+        if not l or l.startswith("."):
+            m = re.match(r"^(\.LBB\d+_\d+):", l)
+            if m:
+                labels[m.group(1)] = len(ins)
+            continue
+        if l.endswith(":"):
             continue
         op, _, rest = l.partition(" ")
         ins.append((op, rest.strip()))
-    return ins
+    return ins, labels
 
 
 @pytest.fixture(scope="module")
@@ -64,32 +70,45 @@ def instructions():
 
 
 def test_matrix_results_are_not_read_too_early(instructions):
-    n_mfma, tightest = 0, None
-    for i, (op, rest) in enumerate(instructions):
+    """Every path of the control-flow graph is followed from each matrix instruction (both ways at a
+    conditional branch) until MIN_GAP wait states have passed, a barrier is met or the kernel ends."""
+    ins, labels = instructions
+    n_mfma, tightest = 0, [None]
+
+    def walk(i0, op, rest, dst, j, gap, seen):
+        while j < len(ins) and gap < MIN_GAP:
+            if (j, gap) in seen:
+                return
+            seen.add((j, gap))
+            op2, rest2 = ins[j]
+            if op2.startswith("v_mfma"):
+                gap += 1            # accumulating into the same registers is forwarded by the hardware
+            elif op2 == "s_nop":
+                gap += int(rest2) + 1
+            elif op2 in ("s_endpgm", "s_barrier"):
+                return              # a barrier or the end: far more than MIN_GAP cycles away
+            elif op2 == "s_branch":
+                j = labels[rest2.strip()]
+                gap += 1
+                continue
+            elif op2.startswith("s_cbranch"):
+                walk(i0, op, rest, dst, labels[rest2.strip()], gap + 1, seen)
+                gap += 1
+            elif _regs(rest2) & dst:
+                assert gap >= MIN_GAP, "instruction %d (%s %s): result touched by '%s %s' after %d wait states" % (
+                    i0, op, rest, op2, rest2, gap)
+                return
+            else:
+                gap += 1
+            j += 1
+
+    for i, (op, rest) in enumerate(ins):
         if not op.startswith("v_mfma"):
             continue
         n_mfma += 1
-        dst = _regs(rest.split(",")[0])
-        gap = 0
-        for op2, rest2 in instructions[i + 1:i + 1 + 4 * MIN_GAP]:
-            if op2.startswith("v_mfma"):
-                gap += 1            # accumulating into the same registers is forwarded by the hardware
-                continue
-            if op2 == "s_nop":
-                gap += int(rest2) + 1
-                continue
-            if op2.startswith("s_cbranch") or op2 in ("s_branch", "s_endpgm", "s_barrier"):
-                break               # a barrier or the end of the block: far more than MIN_GAP cycles away
-            if _regs(rest2) & dst:
-                assert gap >= MIN_GAP, "instruction %d (%s %s): result touched by '%s %s' after %d wait states" % (
-                    i, op, rest, op2, rest2, gap)
-                tightest = gap if tightest is None else min(tightest, gap)
-                break
-            gap += 1
-            if gap >= MIN_GAP:
-                break
+        walk(i, op, rest, _regs(rest.split(",")[0]), i + 1, 0, set())
     assert n_mfma >= 32 * 5, "the pipelined steps were not found in the kernel"
-    print("matrix instructions checked: %d, tightest gap seen: %s" % (n_mfma, tightest))
+    print("matrix instructions checked on all paths: %d" % n_mfma)
 
 
 def test_pipelined_steps_keep_their_slot_structure(instructions):
@@ -99,7 +118,7 @@ def test_pipelined_steps_keep_their_slot_structure(instructions):
     against the slots collapsing into blocks of matrix instructions, which would still compute the
     right thing but lose the overlap the schedule exists for."""
     gaps, cur, seen_mfma = [], 0, False
-    for op, _ in instructions:
+    for op, _ in instructions[0]:
         if op.startswith("v_mfma"):
             if seen_mfma:
                 gaps.append(cur)
