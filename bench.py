@@ -119,7 +119,7 @@ def bench_pipeline(args):
         queries = [wl.queries[i] for i in order]
         sl_all = wl.suffix_len[order].astype(np.int32)
         cu_r = np.concatenate([[0], np.cumsum(sl_all)]).astype(np.int64)     # rows of the reordered batch
-        steps = PL.plan(queries, c.capacity, bc, bm)
+        steps = PL.plan(queries, c.capacity, bc, bm, taper=not args.no_taper and bm > 0)
         steps_serial = PL.plan(queries, c.capacity, bc, 0)
 
         def stitch(c0, c1):
@@ -190,9 +190,10 @@ def bench_pipeline(args):
         "warmup": args.warmup, "ms_per_step": round(T_p, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: L=%d Hq=%d Hkv=%d D=128, %d tables in pinned host memory, device cache C=%d (%s, "
-                               "warm 0..%d), B=%d, b_c=%d, b_m=%d, reranking %s, sum P=%d, S=%d" % (
+                               "warm 0..%d), B=%d, b_c=%d%s, b_m=%d, reranking %s, sum P=%d, S=%d" % (
                                    c.name, L, c.n_q_heads, c.n_kv_heads, c.n_tables, c.capacity, args.policy.upper(),
-                                   c.capacity - 1, c.batch, b_c, b_m, "on" if args.rerank else "off",
+                                   c.capacity - 1, c.batch, b_c, "" if args.no_taper else " (tapering tail)", b_m,
+                                   "on" if args.rerank else "off",
                                    int(P_all.sum()), int(S_all[0]))},
         "prefill_ms_per_query": round(T_p / c.batch, 4),
         "t_compute_ms": round(T_c, 3), "t_loads_ms": round(T_l, 3), "t_pipeline_ms": round(T_p, 3),
@@ -317,6 +318,7 @@ def main():
     ap.add_argument("--prefetch", type=int, default=-1, help="b_m: requests loaded ahead (c5 pipeline; default b_c, 0 = no overlap)")
     ap.add_argument("--policy", default="lru", choices=["lru", "fifo", "lfu"], help="replacement rule (c5 pipeline)")
     ap.add_argument("--rerank", action="store_true", help="visit the batch in reranked order (c5 pipeline)")
+    ap.add_argument("--no-taper", action="store_true", help="c5 pipeline: micro-batches of b_c to the end (no shrinking tail)")
     ap.add_argument("--ablation", action="store_true", help="c5 pipeline: also run rules x reranking x overlap")
     ap.add_argument("--calibrate", action="store_true",
                     help="run one plain elementwise kernel of known size (reads 1 GiB, writes 1 GiB) before the "

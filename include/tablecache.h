@@ -333,7 +333,7 @@ tc_status tc_rerank(const int32_t *table_ids, const int32_t *cu_tables, int32_t 
  * Computation-loading pipeline schedule (Sec. 4.2.2): the ordered requests are computed
  * in micro-batches of b_c while the tables of up to the next b_m requests are copied in.
  * Host only.  The steps' compute ranges [compute_begin, compute_end) follow one another and
- * cover the batch; each holds b_c requests, fewer at the end of the batch or where the
+ * cover the batch; each holds b_c requests, fewer at the end of the batch (or with `taper`) or where the
  * distinct tables of b_c requests would not fit the cache together (the step is cut short
  * and the next one starts there).
  * Before a step's stitch the caller requests the tables of [demand_begin, demand_end) (those
@@ -346,6 +346,9 @@ tc_status tc_rerank(const int32_t *table_ids, const int32_t *cu_tables, int32_t 
  * keep_pinned != 0: the step's own tables stay pinned until its attention layers are enqueued
  * (tc_stitch_alias: the layers read the table slots in place), so they count against the cache
  * while the prefetch range is sized; the caller then unpins after the layers, not after the stitch.
+ * taper != 0: towards the end of the batch a step takes min(b_c, max(1, remaining / 2)) requests
+ * (.., b_c, b_c/2, .., 2, 1, 1).  When the copies are the bottleneck, what runs after the last
+ * copy has landed is the computation of the final step; tapering makes that one request.
  *   table_ids, cu_tables   HOST, request i uses table_ids[cu_tables[i] .. cu_tables[i+1]).
  *   steps_out              HOST, room for `cap` steps; n_queries always suffice.
  * Returns the number of steps, or a negative tc_status: TC_ERR_INVALID (null pointers,
@@ -358,7 +361,7 @@ typedef struct tc_pipe_step {
     int32_t prefetch_begin, prefetch_end;
 } tc_pipe_step;
 int32_t tc_plan_pipeline(const int32_t *table_ids, const int32_t *cu_tables, int32_t n_queries,
-                         int32_t capacity, int32_t b_c, int32_t b_m, int32_t keep_pinned,
+                         int32_t capacity, int32_t b_c, int32_t b_m, int32_t keep_pinned, int32_t taper,
                          tc_pipe_step *steps_out, int32_t cap);
 
 const char *tc_last_error(const tc_ctx *ctx);

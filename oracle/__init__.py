@@ -314,7 +314,7 @@ def replay(model, accesses: Sequence[int]) -> List[Tuple[int, int, int]]:
 # ----------------------------------------------------------------------------- Sec. 4.2.2: pipeline schedule
 
 def plan_pipeline(table_sets: Sequence[Sequence[int]], capacity: int, b_c: int, b_m: int,
-                  keep_pinned: bool = False):
+                  keep_pinned: bool = False, taper: bool = False):
     """Sec. 4.2.2, computation-loading pipeline over an ordered batch: the requests are computed
     b_c at a time, and while a micro-batch is computed the tables of the next b_m requests are
     copied in.  Returns one tuple per micro-batch,
@@ -325,11 +325,14 @@ def plan_pipeline(table_sets: Sequence[Sequence[int]], capacity: int, b_c: int, 
     their tables would outgrow the cache; for the same reason a micro-batch holds fewer than b_c
     requests where the tables of b_c would not fit together (the next one starts there).
     `keep_pinned`: the micro-batch being computed keeps its tables pinned as well (a stitch that
-    points at the cached tables instead of copying them), so they count while the prefetch is sized."""
+    points at the cached tables instead of copying them), so they count while the prefetch is sized.
+    `taper`: near the end a micro-batch takes min(b_c, max(1, remaining // 2)) requests, so the
+    computation left over when the last copy has landed is that of one request."""
     N, steps, asked, c0 = len(table_sets), [], 0, 0
     uni = lambda a, b: set().union(*[set(map(int, x)) for x in table_sets[a:b]]) if b > a else set()
     while c0 < N:
-        full = min(N, c0 + b_c)
+        size = min(b_c, max(1, (N - c0) // 2)) if taper else b_c
+        full = min(N, c0 + size)
         d0 = asked
         # requests c0..asked-1 are here already; ask for more of this micro-batch while they fit
         while asked < full and len(uni(c0, asked + 1)) <= capacity:

@@ -88,7 +88,7 @@ _sig = {
     "tc_rerank": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp]),
     "tc_pin_tables": (_i32, [_vp, _vp, _i32]),
     "tc_unpin_tables": (_i32, [_vp, _vp, _i32]),
-    "tc_plan_pipeline": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _i32]),
+    "tc_plan_pipeline": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _i32]),
 }
 for _n, (_r, _a) in _sig.items():
     getattr(_lib, _n).restype = _r
@@ -342,14 +342,15 @@ def tc_rerank(table_ids, cu_tables, n_tables: int, anchor: int) -> np.ndarray:
     return order[:n]
 
 
-def tc_plan_pipeline(table_ids, cu_tables, capacity: int, b_c: int, b_m: int, keep_pinned: bool = False) -> np.ndarray:
+def tc_plan_pipeline(table_ids, cu_tables, capacity: int, b_c: int, b_m: int, keep_pinned: bool = False,
+                     taper: bool = False) -> np.ndarray:
     """Steps as an int32 array [n_steps, 6]: compute, demand and prefetch ranges (begin, end)."""
     ids, cu = _i32arr(table_ids), _i32arr(cu_tables)
     n = cu.size - 1
     cap = max(1, n)
     steps = np.zeros((cap, 6), dtype=np.int32)
     rc = _lib.tc_plan_pipeline(ids.ctypes.data if ids.size else None, cu.ctypes.data, n, int(capacity), int(b_c),
-                               int(b_m), int(bool(keep_pinned)), steps.ctypes.data, cap)
+                               int(b_m), int(bool(keep_pinned)), int(bool(taper)), steps.ctypes.data, cap)
     if rc < 0:
         raise TcError(rc, "tc_plan_pipeline")
     return steps[:rc]

@@ -135,8 +135,8 @@ tc_status tc_rerank(const int32_t *table_ids, const int32_t *cu_tables, int32_t 
 // whose stitch has not been issued slides over the ordered batch; `held` counts, per table, the
 // window's requests that use it, so its size is the number of slots the window pins.
 int32_t tc_plan_pipeline(const int32_t *table_ids, const int32_t *cu_tables, int32_t n_queries,
-                         int32_t capacity, int32_t b_c, int32_t b_m, int32_t keep_pinned, tc_pipe_step *steps_out,
-                         int32_t cap)
+                         int32_t capacity, int32_t b_c, int32_t b_m, int32_t keep_pinned, int32_t taper,
+                         tc_pipe_step *steps_out, int32_t cap)
 {
     if (n_queries < 0 || capacity < 0 || b_c < 1 || b_m < 0 || cap < 0) return TC_ERR_INVALID;
     if (n_queries == 0) return 0;
@@ -169,7 +169,14 @@ int32_t tc_plan_pipeline(const int32_t *table_ids, const int32_t *cu_tables, int
     for (int32_t c0 = 0; c0 < n_queries; ++n_steps) {
         if (n_steps >= cap) return TC_ERR_INVALID;
         tc_pipe_step &st = steps_out[n_steps];
-        const int64_t full = (int64_t)c0 + b_c < n_queries ? c0 + b_c : n_queries;
+        // with `taper` the last micro-batches halve (.., b_c, b_c/2, .., 2, 1, 1): what is computed
+        // after the final copy has landed is one request instead of b_c
+        int32_t size = b_c;
+        if (taper) {
+            const int32_t half = (n_queries - c0) / 2;
+            size = half < 1 ? 1 : (half < b_c ? half : b_c);
+        }
+        const int64_t full = (int64_t)c0 + size < n_queries ? c0 + size : n_queries;
         st.compute_begin = c0;
         st.demand_begin = frontier;
         // the step takes what has been asked for already (at most b_c requests) and asks for more
@@ -183,7 +190,7 @@ int32_t tc_plan_pipeline(const int32_t *table_ids, const int32_t *cu_tables, int
         if (!keep_pinned)
             for (int32_t i = c0; i < st.compute_end; ++i) drop(i);
         st.prefetch_begin = frontier;
-        const int64_t want = (int64_t)st.compute_end + b_m;
+        const int64_t want = (int64_t)st.compute_end + b_m;      // (b_m is not tapered: the copies should stay ahead)
         while (frontier < n_queries && frontier < want && (int64_t)held.size() + fresh(frontier) <= capacity)
             add(frontier++);
         st.prefetch_end = frontier;

@@ -21,10 +21,11 @@ def flat_tables(queries: Sequence[np.ndarray], a: int, b: int) -> np.ndarray:
     return np.concatenate([np.asarray(q, dtype=np.int32) for q in queries[a:b]]).astype(np.int32)
 
 
-def plan(queries: Sequence[np.ndarray], capacity: int, b_c: int, b_m: int, keep_pinned: bool = False) -> np.ndarray:
+def plan(queries: Sequence[np.ndarray], capacity: int, b_c: int, b_m: int, keep_pinned: bool = False,
+         taper: bool = False) -> np.ndarray:
     ids = flat_tables(queries, 0, len(queries))
     cu = np.concatenate([[0], np.cumsum([len(q) for q in queries])]).astype(np.int32)
-    return B.tc_plan_pipeline(ids, cu, capacity, b_c, b_m, keep_pinned)
+    return B.tc_plan_pipeline(ids, cu, capacity, b_c, b_m, keep_pinned, taper)
 
 
 def run(ctx: "B.Context", queries: Sequence[np.ndarray], steps: np.ndarray, l0: int, l1: int, load_stream,
@@ -41,7 +42,11 @@ def run(ctx: "B.Context", queries: Sequence[np.ndarray], steps: np.ndarray, l0: 
         ids = flat_tables(queries, a, b)
         if ids.size:
             ctx.tc_pin_tables(ids)
-            ctx.tc_load_async(ids, l0, l1, load_stream)
+            # one load call per request: a stitch waits for the copies of the calls that brought its
+            # tables, so a micro-batch at the head of a prefetched range need not wait for the rest
+            for i in range(a, b):
+                if len(queries[i]):
+                    ctx.tc_load_async(np.asarray(queries[i], dtype=np.int32), l0, l1, load_stream)
 
     for c0, c1, d0, d1, p0, p1 in np.asarray(steps).tolist():
         if before_demand is not None:

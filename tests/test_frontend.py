@@ -136,16 +136,16 @@ def test_pipeline_plan_equals_the_checker():
         sets = [rng.integers(0, 14, size=int(rng.integers(0, 5))).tolist() for _ in range(n)]
         b_c, b_m, C = int(rng.integers(1, 7)), int(rng.integers(0, 12)), int(rng.integers(2, 15))
         ids, cu = _flat(sets)
-        keep = bool(trial & 1)
+        keep, taper = bool(trial & 1), bool(trial & 2)
         try:
-            want = oracle.plan_pipeline(sets, C, b_c, b_m, keep_pinned=keep)
+            want = oracle.plan_pipeline(sets, C, b_c, b_m, keep_pinned=keep, taper=taper)
         except ValueError:
             with pytest.raises(B.TcError) as e:
-                B.tc_plan_pipeline(ids, cu, C, b_c, b_m, keep)
+                B.tc_plan_pipeline(ids, cu, C, b_c, b_m, keep, taper)
             assert e.value.code == B.TC_ERR_CAPACITY
             n_err += 1
             continue
-        got = B.tc_plan_pipeline(ids, cu, C, b_c, b_m, keep)
+        got = B.tc_plan_pipeline(ids, cu, C, b_c, b_m, keep, taper)
         assert [tuple(r) for r in got.tolist()] == want, (trial, sets, C, b_c, b_m)
     assert 3 < n_err < 200           # both outcomes were exercised
 

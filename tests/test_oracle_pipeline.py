@@ -159,3 +159,15 @@ def test_plan_with_the_computing_batch_kept_pinned():
         for cls in MODELS:                                     # and the cache then really holds them all
             m = cls(C)
             oracle.simulate_pipeline(m, s, steps, keep_pinned=True)
+
+
+def test_plan_with_tapering_tail():
+    sets = [[i] for i in range(20)]
+    # 20 requests, b_c = 8: 8, then half of what remains each time (12 -> 6, 6 -> 3, 3 -> 1), then singles
+    steps = oracle.plan_pipeline(sets, 40, 8, 8, taper=True)
+    assert [(s[0], s[1]) for s in steps] == [(0, 8), (8, 14), (14, 17), (17, 18), (18, 19), (19, 20)]
+    # the copies stay b_m requests ahead of the computation, whatever the size of its micro-batches
+    assert [(s[4], s[5]) for s in steps] == [(8, 16), (16, 20), (20, 20), (20, 20), (20, 20), (20, 20)]
+    assert steps[0][2:4] == (0, 8) and all(s[2] == s[3] for s in steps[1:])       # nothing else on demand
+    # a batch no longer than b_c still ends on a single request
+    assert [(s[0], s[1]) for s in oracle.plan_pipeline(sets[:5], 40, 8, 8, taper=True)] == [(0, 2), (2, 3), (3, 4), (4, 5)]
