@@ -263,3 +263,51 @@ def test_alias_errors(H):
     # fp32 contexts cannot keep block-format slots
     cfg = B.make_config(1, 8, 2, 64, B.TC_F32, 64, 2, 32, slot_layout=B.TC_SLOTS_BLOCKS)
     assert B.tc_pool_bytes(cfg) == 0
+
+
+@pytest.mark.parametrize("seed", list(range(8)))
+def test_alias_random_batches_match_the_copying_stitch(H, seed):
+    """Seeded random batches (1..5 queries of 1..5 tables with 1..400 tokens, suffixes of 1..200
+    tokens, 0..5 partitions) through the stitch that copies nothing, both kernels, three launches
+    each: against the checker, against the copying stitch on the same inputs (which differs in
+    rounding only: padded key tiles), and bit-identical from launch to launch."""
+    rng = np.random.default_rng(7000 + seed)
+    n_tables = 7
+    B = int(rng.integers(1, 6))
+    cfg = W.scaled(W.CONFIGS["c2"], name="rnd%d" % seed, n_layers=1, n_tables=n_tables, batch=B, capacity=n_tables,
+                   seed=7000 + seed)
+    table_len = rng.integers(1, 401, size=n_tables).astype(np.int32)
+    queries = [rng.choice(n_tables, size=int(rng.integers(1, 6)), replace=True).astype(np.int32) for _ in range(B)]
+    suffix = rng.integers(1, 201, size=B).astype(np.int32)
+    wl = W.Workload(cfg, table_len, queries, suffix)
+    splits = int(rng.choice([0, 1, 2, 3, 5]))
+    q, k, v = wl.suffix_qkv(0)
+    ref = None
+    outs = {}
+    for layout in (0, BLOCKS):
+        for kind in (1, 2):
+            dw = H.DeviceWorkload(wl, slot_layout=layout)
+            dw.ctx.tc_set_attn_kernel(kind)
+            dw.ctx.tc_set_kv_splits(splits)
+            bt, pl = dw.alias() if layout else dw.stitch()
+            dq, dk, dv = (H.to_dev(x, cfg) for x in (q, k, v))
+            rep = []
+            for _ in range(3):
+                out = torch.full_like(dq, float("nan"))
+                dw.ctx.tc_prefill_attn(0, dq, dk, dv, out, wl.cu_seqlens, bt, pl, wl.suffix_len, wl.sm_scale, None)
+                torch.cuda.synchronize()
+                rep.append(out.view(torch.int16).cpu().numpy())
+            np.testing.assert_array_equal(rep[0], rep[2])
+            np.testing.assert_array_equal(rep[1], rep[2])
+            outs[layout, kind] = H.out_to_f64(out, cfg)
+            if ref is None:
+                ref = H.oracle_attn_layer(wl, dw.tables_np, 0, (q, k, v))
+            dw.close()
+    for key, got in outs.items():
+        for i, r in ref.items():
+            sl = slice(int(wl.cu_seqlens[i]), int(wl.cu_seqlens[i + 1]))
+            P = int(table_len[queries[i]].sum())
+            tol = 1e-2 if P >= 64 else max(1e-2, 2.0 ** -7 * 4.7)
+            assert np.abs(got[sl] - r).max() <= tol, (key, i, P, int(suffix[i]), splits)
+    assert np.abs(outs[0, 2] - outs[BLOCKS, 2]).max() <= 1e-2
+    assert np.abs(outs[0, 1] - outs[BLOCKS, 1]).max() <= 1e-2
