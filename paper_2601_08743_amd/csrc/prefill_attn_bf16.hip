@@ -56,31 +56,55 @@ struct RowState {
     float m_run[RB], l_lane[RB];
 };
 
+// Matrix instructions written as inline assembly with their accumulator in ordinary registers
+// (defined with the pipelined path below, where the reason is given).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void mfma_first(f32x16 &acc, const bf16x8 &a, const bf16x8 &b);
+__device__ __forceinline__ void mfma_v(f32x16 &acc, const bf16x8 &a, const bf16x8 &b);
+
 // One key tile for RB row blocks: scores, online softmax, PV.  k_ld / v_ld already point at this
 // lane's operands.  Every K and V fragment read from LDS feeds RB matrix instructions: with
 // RB = 2 the LDS traffic per flop is half that of RB = 1, which is what the LDS (about 100 B per
 // clock and CU, measured) can sustain next to the matrix cores.
-template <int RB>
+// kAsmScores (the kernel that may use 512 registers per wave): left to itself the compiler puts the
+// score accumulators into accumulation registers there and copies all 32 of them out, one by
+// one, for the softmax.  The QK matrix instructions are therefore issued as inline assembly with
+// the accumulators in ordinary registers, and a fence holds the 12 wait states a matrix result
+// needs before a vector instruction may read it (the compiler does not see those instructions'
+// latency).  (O stays with the compiler here: it keeps O in ordinary registers between tiles and
+// copies it into accumulation registers and back around every tile's PV; issuing the PV
+// instructions as assembly with an accumulation-register operand did not stop that, and gave
+// wrong results besides - left alone.)
+template <int RB, bool kAsmScores>
 __device__ __forceinline__ void tile_math(RowState<RB> &st, const bf16x8 (&qf)[RB][8], const char *k_ld,
                                           const char *v_ld, int key0, const int (&limit)[RB],
                                           bool need_mask, uint32_t pads, int hh, float c)
 {
     f32x16 sacc[RB][2];
+    if (!kAsmScores) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
+        for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+            for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) sacc[rb][mb][e] = 0.f;
+                for (int e = 0; e < 16; ++e) sacc[rb][mb][e] = 0.f;
+    }
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
             const bf16x8 ka = *(const bf16x8 *)(k_ld + mb * 32 * kKRow + ks * 32);
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-                sacc[rb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[rb][ks], sacc[rb][mb], 0, 0, 0);
+            for (int rb = 0; rb < RB; ++rb) {
+                if (!kAsmScores) sacc[rb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[rb][ks], sacc[rb][mb], 0, 0, 0);
+                else if (ks == 0) mfma_first(sacc[rb][mb], ka, qf[rb][ks]);
+                else mfma_v(sacc[rb][mb], ka, qf[rb][ks]);
+            }
         }
+    if (kAsmScores) {
+        static_assert(!kAsmScores || RB == 1, "one row block per wave");
+        asm volatile("s_nop 11" : "+v"(sacc[0][0]), "+v"(sacc[0][1]));
+    }
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         if (need_mask) {                               // causal edge, ragged tail or unused block tails in this tile
@@ -92,7 +116,8 @@ __device__ __forceinline__ void tile_math(RowState<RB> &st, const bf16x8 (&qf)[R
                     // position inside its 16-token block, and that block's unused tail (4 bits per block)
                     const int t = 8 * ((e >> 2) & 1) + 4 * hh + (e & 3);
                     const int used = 16 - (int)((pads >> (4 * (2 * mb + (e >> 3)))) & 15u);
-                    if (key > limit[rb] || t >= used) sacc[rb][mb][e] = -INFINITY;
+                    const bool dead = (key > limit[rb]) | (t >= used);     // a select, not a branch
+                    sacc[rb][mb][e] = dead ? -INFINITY : sacc[rb][mb][e];
                 }
         }
         float mx = sacc[rb][0][0];
@@ -102,7 +127,7 @@ __device__ __forceinline__ void tile_math(RowState<RB> &st, const bf16x8 (&qf)[R
         for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[rb][1][e]);
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float mxs = mx * c;
-        if (__any(mxs > st.m_run[rb] + kRescaleThresh)) {   // also taken while m_run is still -inf
+        if (__builtin_expect(__any(mxs > st.m_run[rb] + kRescaleThresh), 0)) {   // rare; also taken while m_run is still -inf
             const float m_new = fmaxf(st.m_run[rb], mxs);
             const float alpha = (st.m_run[rb] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m_run[rb] - m_new);
             st.l_lane[rb] *= alpha;
@@ -134,8 +159,9 @@ __device__ __forceinline__ void tile_math(RowState<RB> &st, const bf16x8 (&qf)[R
         for (int db = 0; db < 4; ++db) {
             const bf16x8 va = *(const bf16x8 *)(v_ld + kk * kHeadBlk + db * 32 * 32);
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
+            for (int rb = 0; rb < RB; ++rb) {
                 st.o[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[rb], st.o[rb][db], 0, 0, 0);
+            }
         }
     }
 }
@@ -193,7 +219,7 @@ __device__ __forceinline__ void fill_bids(int32_t *s_bid, const BatchDev &b, con
 // kStage bytes at the start of `lds`.  With r0 == 0 the first two tiles take their block ids from the
 // item, so their loads do not wait for the block-id table; `do_fill` then fills that table here,
 // after the loads are on their way.
-template <int RB>
+template <int RB, bool kAsmScores>
 __device__ __forceinline__ void tile_loop(RowState<RB> &st, const bf16x8 (&qf)[RB][8], const Geom &g,
                                           const BatchDev &b, const AttnArgs &a, const AttnItem &it,
                                           const ItemRows<RB> &ir, char *lds, int32_t *s_bid, int r0, bool do_fill,
@@ -327,7 +353,7 @@ __device__ __forceinline__ void tile_loop(RowState<RB> &st, const bf16x8 (&qf)[R
                     ((uint32_t)entry_pad(e4_.z) << 8) | ((uint32_t)entry_pad(e4_.w) << 12);       \
             pads_ = __builtin_amdgcn_readfirstlane(pads_);                                        \
         }                                                                                         \
-        tile_math<RB>(st, qf, k_ld + (stage_) * kStage, v_ld + (stage_) * kStage, key0, lim_,     \
+        tile_math<RB, kAsmScores>(st, qf, k_ld + (stage_) * kStage, v_ld + (stage_) * kStage, key0, lim_, \
                       pads_ != 0 || key0 + kAttnKeys - 1 > (pre_ ? P - 1 : ir.wave_stok_min),     \
                       pads_, hh, c);                                                              \
     }
@@ -448,7 +474,7 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
     load_q<RB>(qf, g, a, it, ir, lane >> 5);
     RowState<RB> st;
     reset_rows<RB>(st);
-    tile_loop<RB>(st, qf, g, b, a, it, ir, lds, s_bid, 0, true, tid);
+    tile_loop<RB, false>(st, qf, g, b, a, it, ir, lds, s_bid, 0, true, tid);
     store_rows<RB>(st, g, a, it, ir, w, lane);
 }
 
@@ -502,8 +528,6 @@ __device__ __forceinline__ void load_to_lds(uint32_t lds_dst, const char *base, 
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(__builtin_amdgcn_readfirstlane(lds_dst)), "v"(voff), "s"(sb) : "memory");
 }
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 struct FastState {
     f32x16 S[4];        // scores / weights in stream order: even tile keys 32..63, odd tile keys 0..31,
@@ -878,14 +902,14 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_pipe_kernel(Geom g, BatchDev
         item_rows<1>(ir, g, it, tid2 >> 6, tid2 & 31);
         if (ok) {
             if (it.tile_begin + n_fast < it.tile_end)
-                tile_loop<1>(st, qf, g, b, a, it, ir, lds, s_bid, n_fast, false, tid2);
+                tile_loop<1, true>(st, qf, g, b, a, it, ir, lds, s_bid, n_fast, false, tid2);
         } else {
             reset_rows<1>(st);
-            tile_loop<1>(st, qf, g, b, a, it, ir, lds, s_bid, 0, false, tid2);
+            tile_loop<1, true>(st, qf, g, b, a, it, ir, lds, s_bid, 0, false, tid2);
         }
         store_rows<1>(st, g, a, it, ir, tid2 >> 6, tid2 & 63);
     } else {
-        tile_loop<1>(st, qf, g, b, a, it, ir, lds, s_bid, 0, true, tid);
+        tile_loop<1, true>(st, qf, g, b, a, it, ir, lds, s_bid, 0, true, tid);
         store_rows<1>(st, g, a, it, ir, w, lane);
     }
 }
