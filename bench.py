@@ -301,6 +301,56 @@ def zero_copy_extras(args, wl, qkv, outs_copy, flops_step, stream):
     return res
 
 
+def decode_extras(args, ctx, wl, prefill_layers, P, S, max_blocks, stream):
+    """One generated token per query after the prefill (Sec. 2.2's decoding stage over the stitched
+    cache): every layer appends the token's K/V and attends over the whole sequence.  The work is
+    reading the sequences' K/V once per layer, so the figure is bytes per second of the decode
+    attention kernel: kappa * sum(P + S) per launch."""
+    import torch
+    c = wl.cfg
+    bt, pl = ctx.tc_stitch_kv(wl.table_ids, wl.cu_tables, wl.suffix_len, max_blocks, stream)
+    prefill_layers(bt, pl)
+    cur = (P + S).astype(np.int32)
+    bt = ctx.tc_grow_seqs(bt, cur + 1)
+    g = torch.Generator(device="cpu").manual_seed(7)
+    q = torch.randn(c.batch, c.n_q_heads, c.head_dim, generator=g).bfloat16().cuda()
+    k = torch.randn(c.batch, c.n_kv_heads, c.head_dim, generator=g).bfloat16().cuda()
+    v = torch.randn(c.batch, c.n_kv_heads, c.head_dim, generator=g).bfloat16().cuda()
+    out = torch.empty_like(q)
+    one, cu1 = np.ones(c.batch, dtype=np.int32), np.arange(c.batch + 1, dtype=np.int32)
+
+    def step():
+        for l in range(c.n_layers):
+            ctx.tc_prefill_attn(l, q, k, v, out, cu1, bt, cur, one, wl.sm_scale, stream)
+
+    n = max(5, args.steps // 2)
+    for _ in range(2):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / n
+    kernel, n_splits = ctx.tc_attn_kernel(), ctx.tc_kv_splits()
+    ctx.tc_profile_enable(True)
+    ctx.tc_profile_read()
+    for _ in range(n):
+        step()
+    torch.cuda.synchronize()
+    pr = ctx.tc_profile_read()
+    ctx.tc_profile_enable(False)
+    ctx.tc_release_seqs(bt)
+    a_us = pr["attn"][0] * 1e3 / max(pr["attn"][1], 1)
+    f_us = pr["merge"][0] * 1e3 / max(pr["merge"][1], 1)
+    kv_bytes = 2 * c.n_kv_heads * c.head_dim * c.elem_bytes * int((P + S).sum())
+    return {"decode_ms_per_token_step": round(ms, 4), "decode_attn_kernel_us": round(a_us, 2),
+            "decode_finish_kernel_us": round(f_us, 2), "decode_kv_splits": n_splits,
+            "decode_kernel": {3: "decode_attn_bf16_kernel"}.get(kernel, "prefill kernel %d" % kernel),
+            "decode_kv_gbps": round(kv_bytes / (a_us * 1e-6) / 1e9, 1),
+            "decode_frac_hbm": round(kv_bytes / (a_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -353,7 +403,7 @@ def main():
     max_blocks = max(need) + 1
     max_tok = int(wl.table_len.max())
     cap = c.capacity
-    n_blocks = cap * (-(-max_tok // 16)) + sum(need) + 8
+    n_blocks = cap * (-(-max_tok // 16)) + sum(need) + c.batch + 8      # + one more block per query for the decode extra
     cfg = B.make_config(c.n_layers, c.n_q_heads, c.n_kv_heads, c.head_dim,
                         B.TC_F32 if c.dtype == "f32" else B.TC_BF16, n_blocks, cap, max_tok)
     pool = torch.empty(B.tc_pool_bytes(cfg), dtype=torch.uint8, device="cuda")
@@ -462,6 +512,7 @@ def main():
         extra.update(frontend_extras(wl))
         if c.dtype == "bf16":
             extra.update(zero_copy_extras(args, wl, qkv, outs, flops_step, stream))
+            extra.update(decode_extras(args, ctx, wl, layers, P, S, max_blocks + 1, stream))
     bt, pl = ctx.tc_stitch_kv(ids, cu_t, sl, max_blocks, stream)
     if not args.no_graph:
         g = torch.cuda.CUDAGraph()

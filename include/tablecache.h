@@ -281,9 +281,12 @@ tc_status tc_set_row_blocks(tc_ctx *ctx, int32_t row_blocks);
 /* Which bf16 attention kernel serves work-groups of 128 rows: 0 = automatic (from the number and
  * length of the batch's work items), 1 = the general kernel (register-staged K/V, running-maximum
  * softmax, two work-groups per CU), 2 = the pipelined kernel (direct-to-LDS K/V, fixed softmax
- * reference with overflow fallback, one work-group per CU).  Results do not depend on it beyond
- * rounding.  Invalidates the cached plan.  tc_attn_kernel reports the kernel of the current plan
- * (1 or 2; 0 when no plan is cached, for fp32 contexts and for 256-row work-groups). */
+ * reference with overflow fallback, one work-group per CU), 3 = as 0 (the decode kernels serve
+ * batches in which no query brings more than one new token, unless 1 or 2 is forced: the keys of
+ * a KV head are split over waves and work-groups, a second kernel combines them and adds the new
+ * token).  Results do not depend on it beyond rounding.  Invalidates the cached plan.
+ * tc_attn_kernel reports the kernel of the current plan (1, 2 or 3; 0 when no plan is cached, for
+ * fp32 contexts and for 256-row work-groups). */
 tc_status tc_set_attn_kernel(tc_ctx *ctx, int32_t kind);
 int32_t tc_attn_kernel(const tc_ctx *ctx);
 

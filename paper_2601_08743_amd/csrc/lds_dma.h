@@ -1,0 +1,22 @@
+// Direct global -> LDS loads (global_load_lds_dwordx4), shared by the kernels that stream K/V tiles
+// into LDS without passing through registers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tc {
+
+// 16 bytes per lane from (uniform base + per-lane offset) to LDS at lds_dst + 16 * lane.  The
+// instruction takes its LDS address from M0 and its base from a scalar register pair; both are
+// made uniform explicitly.  Completion is counted in vmcnt like any vector load; the compiler does
+// not know about these loads, so the waits (s_waitcnt vmcnt) are the caller's.
+__device__ __forceinline__ void load_to_lds(uint32_t lds_dst, const char *base, uint32_t voff)
+{
+    const uint64_t b64 = (uint64_t)(uintptr_t)base;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b64), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b64 >> 32));
+    const uint64_t sb = ((uint64_t)hi << 32) | lo;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_dst)), "v"(voff), "s"(sb) : "memory");
+}
+
+}  // namespace tc

@@ -31,6 +31,7 @@
 // arrive folds the others in - was measured 3x slower: device-scope release/acquire on this chip
 // writes back and invalidates the XCD's whole L2, which every work-group would do.)
 #include "kv_append.h"
+#include "lds_dma.h"
 #include "tc_internal.h"
 
 namespace tc {
@@ -517,17 +518,6 @@ static_assert(kLdsBytesPipe <= 160 * 1024 && 2 * kStage <= kFastBid, "LDS layout
 constexpr int kFastMinTiles = 4;
 
 #define TC_SB() __builtin_amdgcn_sched_barrier(0)
-
-// 16 bytes per lane from (uniform base + per-lane offset) to LDS at lds_dst + 16 * lane.
-__device__ __forceinline__ void load_to_lds(uint32_t lds_dst, const char *base, uint32_t voff)
-{
-    // both must sit in scalar registers: make their uniformity explicit
-    const uint64_t b64 = (uint64_t)(uintptr_t)base;
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b64), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b64 >> 32));
-    const uint64_t sb = ((uint64_t)hi << 32) | lo;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(__builtin_amdgcn_readfirstlane(lds_dst)), "v"(voff), "s"(sb) : "memory");
-}
 
 struct FastState {
     f32x16 S[4];        // scores / weights in stream order: even tile keys 32..63, odd tile keys 0..31,

@@ -116,6 +116,7 @@ struct Plan {
     bool valid = false;
     int32_t B = 0, max_blocks = 0, total_S = 0, n_stitch_blk = 0, n_items = 0, max_splits = 1, n_groups = 0, row_blocks = 1;
     bool pipelined = false;     // bf16, one row block per wave: the pipelined attention kernel
+    bool decode = false;        // bf16, at most one new token per query: the decode kernels
     bool rope = false;          // the stitch re-encodes keys by position (Sec. 4.1.1)
     std::vector<int32_t> rope_pos0;      // [B]
     std::vector<double> rope_rev_freq;   // [D/2]
@@ -156,7 +157,7 @@ struct tc_ctx {
     float *d_part = nullptr; size_t d_part_floats = 0;
     int32_t forced_splits = 0;
     int32_t forced_row_blocks = 0;
-    int32_t forced_attn_kernel = 0;   // 0 automatic, 1 general, 2 pipelined
+    int32_t forced_attn_kernel = 0;   // 0 automatic, 1 general, 2 pipelined, 3 decode (where it applies)
     // per-kernel timing (tc_profile_*): pairs of events around launches, drained on read
     bool profiling = false;
     struct Timed { int kind; hipEvent_t a, b; };
@@ -266,6 +267,49 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
     const int G = c.n_q_heads / c.n_kv_heads;
     const bool bf16 = c.dtype == TC_BF16;
     const int KT = bf16 ? kAttnKeys : kF32Keys;
+    p.decode = false;
+    // Decode step: every query brings at most one new token, so a KV head has only G rows and the
+    // work is reading K and V once.  The decode kernels split the keys of a (query, KV head) over
+    // the four waves of a work-group and over `ns` work-groups: enough of them to cover the chip,
+    // but at least eight key tiles each (two per wave).  Sequences that alias table slots carry
+    // unused block tails, which these kernels do not mask: they keep to the prefill kernels.
+    if (bf16 && G <= 32 && p.total_S > 0 && p.block_pad.empty() && ctx->forced_row_blocks == 0 &&
+        (ctx->forced_attn_kernel == 0 || ctx->forced_attn_kernel == 3) &&
+        std::all_of(p.suffix_len.begin(), p.suffix_len.end(), [](int32_t s) { return s <= 1; })) {
+        int n_q = 0;
+        for (int i = 0; i < p.B; ++i) n_q += p.suffix_len[i] > 0 ? 1 : 0;
+        const int cap = std::max(1, (512 + n_q * c.n_kv_heads - 1) / (n_q * c.n_kv_heads));
+        splits_of_q.assign(p.B, 1);
+        p.max_splits = 1;
+        items.clear();
+        groups.clear();
+        for (int i = 0; i < p.B; ++i) {
+            if (p.suffix_len[i] <= 0) continue;
+            const int P = p.prefix_len[i];
+            const int n_tiles = (P + KT - 1) / KT;
+            int ns = ctx->forced_splits > 0 ? ctx->forced_splits : std::min(cap, std::max(1, n_tiles / 8));
+            ns = std::max(ns, (n_tiles + kAttnMaxTiles - 1) / kAttnMaxTiles);
+            ns = std::max(1, std::min(ns, std::max(n_tiles, 1)));
+            splits_of_q[i] = ns;
+            p.max_splits = std::max(p.max_splits, ns);
+            const int32_t *bt = p.block_table.data() + (size_t)i * p.max_blocks;
+            for (int h = 0; h < c.n_kv_heads; ++h)
+                for (int s = 0; s < ns; ++s) {
+                    AttnItem it{};
+                    it.q = i; it.kvh = h; it.tile_begin = (int32_t)((int64_t)n_tiles * s / ns);
+                    it.tile_end = (int32_t)((int64_t)n_tiles * (s + 1) / ns);
+                    it.split = s; it.n_splits = ns; it.P = P; it.S = 1; it.cu = p.cu_seqlens[i];
+                    for (int k = 0; k < 16; ++k) it.bid[k] = bt[0];
+                    items.push_back(it);
+                }
+        }
+        p.n_groups = 0;
+        p.row_blocks = 1;
+        p.n_items = (int32_t)items.size();
+        p.pipelined = false;
+        p.decode = true;
+        return;
+    }
     // key tiles of a query.  bf16 kernel: the tiles of the prefix (from the pool), then the tiles of
     // the suffix (from k_new / v_new); fp32 kernel: one paged sequence of P + S keys
     auto tiles_of = [&](int P, int S) {
@@ -403,7 +447,7 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
             fast_tiles += std::max(std::min(it.tile_end, it.P >> 6) - it.tile_begin, 0);
         }
     p.pipelined = bf16 && rb == 1 && n_real > 0 &&
-                  (ctx->forced_attn_kernel ? ctx->forced_attn_kernel == 2
+                  (ctx->forced_attn_kernel == 1 || ctx->forced_attn_kernel == 2 ? ctx->forced_attn_kernel == 2
                                            : (n_real <= 2 * 256 || fast_tiles >= 48 * n_real));
 }
 
@@ -472,10 +516,10 @@ tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
     p.items_dev = (const AttnItem *)(d + o_it);
     p.groups_dev = (const MergeGroup *)(d + o_gr);
 
-    if (p.max_splits > 1) {
+    if (p.max_splits > 1 || p.decode) {
         // bf16 kernel: per (partition, group, row block) 128 rows x (128 fp16 + 2 floats) in fragment
-        // order, counted in floats; fp32 kernel: per (partition, suffix token, head) D + 2 floats
-        const size_t need = ctx->cfg.dtype == TC_BF16
+        // order, counted in floats; fp32 and decode kernels: per (partition, new token, head) D + 2 floats
+        const size_t need = ctx->cfg.dtype == TC_BF16 && !p.decode
             ? (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * (64 + 2)
             : (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * (ctx->cfg.head_dim + 2);
         if (need > ctx->d_part_floats) {
@@ -1031,6 +1075,17 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
         return fail(ctx, TC_ERR_INVALID, "attn: tensors must be 16-byte aligned");
 
     const bool bf16 = ctx->cfg.dtype == TC_BF16;
+    if (p.decode) {
+        AttnArgs a{};
+        a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
+        a.n_append = p.total_S + p.B; a.items = p.items_dev; a.n_items = p.n_items; a.layer = layer;
+        a.scale_log2 = sm_scale * 1.4426950408889634f;
+        a.part_o = ctx->d_part;
+        a.part_ml = ctx->d_part + (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * ctx->cfg.head_dim;
+        TC_HIP(ctx, timed_launch(ctx, 2, stream, [&](const Launch &ln) { return launch_decode_bf16(ctx->geom, p.dev, a, ln); }));
+        TC_HIP(ctx, timed_launch(ctx, 3, stream, [&](const Launch &ln) { return launch_decode_finish(ctx->geom, p.dev, a, ln); }));
+        return TC_OK;
+    }
     if (!bf16)      // the bf16 attention launch appends in extra work-groups of its own
         TC_HIP(ctx, timed_launch(ctx, 1, stream, [&](const Launch &ln) { return launch_append(ctx->geom, p.dev, layer, k_new, v_new, ln); }));
     AttnArgs a{};
@@ -1178,12 +1233,13 @@ tc_status tc_set_kv_splits(tc_ctx *ctx, int32_t n_splits)
 int32_t tc_attn_kernel(const tc_ctx *ctx)
 {
     if (!ctx || !ctx->plan.valid || ctx->cfg.dtype != TC_BF16 || ctx->plan.row_blocks != 1) return 0;
+    if (ctx->plan.decode) return 3;
     return ctx->plan.pipelined ? 2 : 1;
 }
 
 tc_status tc_set_attn_kernel(tc_ctx *ctx, int32_t kind)
 {
-    if (!ctx || kind < 0 || kind > 2) return TC_ERR_INVALID;
+    if (!ctx || kind < 0 || kind > 3) return TC_ERR_INVALID;
     ctx->forced_attn_kernel = kind;
     ctx->plan.valid = false;
     return TC_OK;

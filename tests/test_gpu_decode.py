@@ -26,8 +26,9 @@ def _draw(seed, *key, shape):
     return W.f32_to_bf16_bits(rng.standard_normal(size=shape, dtype=np.float32))
 
 
+@pytest.mark.parametrize("kind", [0, 1])
 @pytest.mark.parametrize("splits", [0, 3])
-def test_decode_steps_after_prefill(H, splits):
+def test_decode_steps_after_prefill(H, splits, kind):
     cfg = W.WorkloadConfig(name="dec", n_layers=2, n_q_heads=8, n_kv_heads=2, head_dim=128, dtype="bf16", n_tables=6,
                            table_len=(20, 150), batch=3, tables_per_query=(1, 3), choice="uniform",
                            suffix_len=(3, 40), capacity=6, seed=404)
@@ -40,6 +41,7 @@ def test_decode_steps_after_prefill(H, splits):
     dw = H.DeviceWorkload(wl, seq_blocks=seq_blocks)
     if splits:
         dw.ctx.tc_set_kv_splits(splits)
+    dw.ctx.tc_set_attn_kernel(kind)                    # 0: the decode kernels serve the steps; 1: the prefill kernel does
     max_blocks = int(max(-(-(p + s + T) // 16) for p, s in zip(P, S))) + 1
     bt, pl = dw.stitch(max_blocks=max_blocks)
     # prefill: both layers (appends the prompt's own suffix to the pool)
@@ -76,6 +78,7 @@ def test_decode_steps_after_prefill(H, splits):
             out = torch.full_like(dq, float("nan"))
             dw.ctx.tc_prefill_attn(layer, dq, dk, dv, out, cu1, bt, cur, one, wl.sm_scale, None)
             torch.cuda.synchronize()
+            assert dw.ctx.tc_attn_kernel() == (3 if kind == 0 else 1)
             got = H.out_to_f64(out, c)
             for i in range(c.batch):
                 K, V = seq[layer, i]
@@ -122,4 +125,62 @@ def test_grow_errors_change_nothing(H):
     have = int((bt >= 0).sum())
     assert int((grown >= 0).sum()) == have + (3 - int((bt[0] >= 0).sum())) + (3 - int((bt[1] >= 0).sum()))
     dw.ctx.tc_release_seqs(grown)
+    dw.close()
+
+
+def test_decode_batch_c3_shape(H):
+    """c3's batch (32 queries, prefixes of 600 .. 5000 tokens), one decode step on two layers: the
+    decode kernels against the checker on every query, against the prefill kernel on the same
+    inputs, and bit-identical from launch to launch; queries without a new token are skipped."""
+    wl = W.make_workload(W.scaled(W.CONFIGS["c3"], n_layers=2))
+    c = wl.cfg
+    used = sorted(set(wl.table_ids.tolist()))
+    P = np.array([int(wl.table_len[q].sum()) for q in wl.queries])
+    S = wl.suffix_len.astype(int)
+    seq_blocks = int(sum(-(-(p + s + 1) // 16) for p, s in zip(P, S))) + 8
+    dw = H.DeviceWorkload(wl, seq_blocks=seq_blocks, capacity=len(used), tables=used)
+    max_blocks = int(max(-(-(p + s + 1) // 16) for p, s in zip(P, S))) + 1
+    bt, pl = dw.stitch(max_blocks=max_blocks)
+    pre = {}
+    for layer in range(2):
+        _, qkv = dw.attn_layer(layer, bt, pl)
+        pre[layer] = qkv
+    cur = (P + S).astype(np.int32)
+    bt = dw.ctx.tc_grow_seqs(bt, cur + 1)
+    new = np.ones(c.batch, dtype=np.int32)
+    new[5] = 0                                          # one query sits this step out
+    cu1 = np.concatenate([[0], np.cumsum(new)]).astype(np.int32)
+    n_tok = int(new.sum())
+    for layer in range(2):
+        q = _draw(c.seed, layer, 0, 0, shape=(n_tok, c.n_q_heads, c.head_dim))
+        k = _draw(c.seed, layer, 0, 1, shape=(n_tok, c.n_kv_heads, c.head_dim))
+        v = _draw(c.seed, layer, 0, 2, shape=(n_tok, c.n_kv_heads, c.head_dim))
+        dq, dk, dv = H.to_dev(q, c), H.to_dev(k, c), H.to_dev(v, c)
+        outs = {}
+        for kind in (0, 1):
+            dw.ctx.tc_set_attn_kernel(kind)
+            reps = []
+            for _ in range(3):
+                out = torch.full_like(dq, float("nan"))
+                dw.ctx.tc_prefill_attn(layer, dq, dk, dv, out, cu1, bt, cur, new, wl.sm_scale, None)
+                torch.cuda.synchronize()
+                reps.append(out.view(torch.int16).cpu().numpy())
+            assert dw.ctx.tc_attn_kernel() == (3 if kind == 0 else 1)
+            np.testing.assert_array_equal(reps[0], reps[2])
+            np.testing.assert_array_equal(reps[1], reps[2])
+            outs[kind] = H.out_to_f64(out, c)
+        assert np.abs(outs[0] - outs[1]).max() <= 1e-2
+        for i in range(c.batch):
+            if not new[i]:
+                continue
+            ks, vs = H.oracle_sequences(wl, dw.tables_np, layer, i)
+            sl = slice(int(wl.cu_seqlens[i]), int(wl.cu_seqlens[i + 1]))
+            K = np.concatenate([ks, pre[layer][1][sl]])
+            V = np.concatenate([vs, pre[layer][2][sl]])
+            n = int(cu1[i])
+            ref = oracle.prefill_attn(W.storage_to_f64(q[n:n + 1], "bf16"), W.storage_to_f64(K, "bf16"),
+                                      W.storage_to_f64(V, "bf16"), W.storage_to_f64(k[n:n + 1], "bf16"),
+                                      W.storage_to_f64(v[n:n + 1], "bf16"), wl.sm_scale)
+            assert np.abs(outs[0][n:n + 1] - ref).max() <= 1e-2, (layer, i)
+    dw.ctx.tc_release_seqs(bt)
     dw.close()
