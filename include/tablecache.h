@@ -233,8 +233,13 @@ tc_status tc_stitch_kv_rope(tc_ctx *ctx, const int32_t *table_ids, const int32_t
  *   block_table       HOST [B][max_blocks]
  *   prefix_len, suffix_len   HOST [B]
  * The integer arguments normally are the ones tc_stitch_kv returned for the current
- * batch, in which case nothing is uploaded; if they differ, the call re-plans from them
- * (every block id must be a sequence block in range).
+ * batch, in which case nothing is uploaded; if they differ, the call re-plans from them.
+ * Every block id of such a batch must be a sequence block in range, or - with block-format slots
+ * - a block of a slot that holds a fully loaded table, standing where the whole block lies below
+ * prefix_len (a table block is only ever read); which positions of a table's last block hold
+ * tokens follows from the table cached in that slot at the time of the call, so the tables of
+ * sequences made by tc_stitch_alias must stay cached (pinned) for as long as those sequences are
+ * attended to.
  * Errors: TC_ERR_INVALID, TC_ERR_HIP.
  */
 tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void *k_new,
@@ -249,7 +254,9 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
  * are taken lowest-free-first, queries in order).  A decode step is then tc_prefill_attn with
  * suffix_len = 1 and prefix_len = everything already in the pool (the tables' tokens, the prompt's
  * own suffix, the tokens generated so far): the call appends the new token's K/V at position
- * prefix_len and attends to all of it.  Sequences made by tc_stitch_kv only (copied prefixes).
+ * prefix_len and attends to all of it.  Works for sequences made by tc_stitch_kv and by
+ * tc_stitch_alias alike (for the latter prefix_len counts the padded positions, as returned by
+ * the stitch; entries naming table blocks are left as they are).
  *   block_table  HOST in/out [B][max_blocks];  new_len  HOST in [B]
  * Errors: TC_ERR_OOM_POOL (max_blocks too small or no free block; nothing is changed),
  * TC_ERR_INVALID.

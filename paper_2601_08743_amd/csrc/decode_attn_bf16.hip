@@ -147,13 +147,19 @@ __global__ __launch_bounds__(256, 2) void decode_attn_bf16_kernel(Geom g, BatchD
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");               // V area read out
         if (more) issue_v(t + 4);
         const int key0 = (it.tile_begin + t) * kAttnKeys;
-        if (key0 + kAttnKeys > P) {                    // ragged end of the sequence in this tile
+        // positions that hold no key: beyond the end of the sequence, and the unused tail of a
+        // table block read in place (its count rides in the block-table entry)
+        const int4 e4 = *(const int4 *)&s_bid[t * 4];
+        const int pad4 = entry_pad(e4.x) | (entry_pad(e4.y) << 8) | (entry_pad(e4.z) << 16) | (entry_pad(e4.w) << 24);
+        if (pad4 != 0 || key0 + kAttnKeys > P) {
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
+                    const int in_blk = 8 * ((e >> 2) & 1) + 4 * hh + (e & 3);
+                    const int pad = (pad4 >> (8 * (2 * mb + (e >> 3)))) & 255;
                     const int key = key0 + 32 * mb + 8 * (e >> 2) + 4 * hh + (e & 3);
-                    sacc[mb][e] = key >= P ? -INFINITY : sacc[mb][e];
+                    sacc[mb][e] = (key >= P || in_blk >= kBlockTokens - pad) ? -INFINITY : sacc[mb][e];
                 }
         }
         float mx = sacc[0][0];
@@ -229,33 +235,57 @@ __global__ __launch_bounds__(256, 2) void decode_attn_bf16_kernel(Geom g, BatchD
 
 // One work-group of 128 threads per output row (token, head): combine the key partitions, add the
 // new token itself, normalise, write bf16.
-__global__ __launch_bounds__(128) void decode_finish_kernel(Geom g, BatchDev b, AttnArgs a)
+__global__ __launch_bounds__(128) void decode_finish_kernel(Geom g, BatchDev b, AttnArgs a, int max_splits)
 {
     __shared__ float red[2];
     const int row = blockIdx.x, d = threadIdx.x;
-    const int n = row / g.Hq, head = row - n * g.Hq, kvh = head / g.G;
-    const int ns = b.splits_of_q[b.tok_q[n]];
+    const int n = row / g.Hq, head = row - n * g.Hq, kvh = head / g.G;      // n: the token (queries may bring none)
     const int64_t n_rows = (int64_t)b.total_S * g.Hq;
-    // score of the new token against itself
+    // Every load of the kernel is issued before the first use, so that the row costs one round
+    // trip to memory: the query's partition count, the new token, and the first eight partitions'
+    // partials (slots of partitions the query does not have exist in the buffer; they are loaded
+    // and ignored).
+    const int ns = b.splits_of_q[b.tok_q[n]];
     const unsigned short *q16 = (const unsigned short *)a.q + (int64_t)row * 128;
     const unsigned short *k16 = (const unsigned short *)a.k_new + ((int64_t)n * g.Hkv + kvh) * 128;
     const unsigned short *v16 = (const unsigned short *)a.v_new + ((int64_t)n * g.Hkv + kvh) * 128;
-    float prod = __uint_as_float((unsigned)q16[d] << 16) * __uint_as_float((unsigned)k16[d] << 16);
+    const float qd = __uint_as_float((unsigned)q16[d] << 16), kd = __uint_as_float((unsigned)k16[d] << 16);
+    const float vd = __uint_as_float((unsigned)v16[d] << 16);
+    float2 ml[8];
+    float po[8];
+    auto fetch = [&](int s0) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int64_t slot = (int64_t)min(s0 + j, max_splits - 1) * n_rows + row;
+            ml[j] = *(const float2 *)(a.part_ml + slot * 2);
+            po[j] = a.part_o[slot * 128 + d];
+        }
+    };
+    fetch(0);
+    // score of the new token against itself
+    float prod = qd * kd;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) prod += __shfl_xor(prod, off);
     if ((d & 63) == 0) red[d >> 6] = prod;
     __syncthreads();
-    const float s_new = (red[0] + red[1]) * a.scale_log2;
-    float M = s_new;
-    for (int s = 0; s < ns; ++s) M = fmaxf(M, a.part_ml[((int64_t)s * n_rows + row) * 2]);
-    const float w_new = __builtin_amdgcn_exp2f(s_new - M);
-    float L = w_new, acc = w_new * __uint_as_float((unsigned)v16[d] << 16);
-    for (int s = 0; s < ns; ++s) {
-        const int64_t slot = (int64_t)s * n_rows + row;
-        const float ms = a.part_ml[slot * 2];
-        const float wgt = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - M);
-        L += wgt * a.part_ml[slot * 2 + 1];
-        acc += wgt * a.part_o[slot * 128 + d];
+    // running merge, started with the new token alone (weight 1 at its own score)
+    float M = (red[0] + red[1]) * a.scale_log2, L = 1.f, acc = vd;
+    for (int s0 = 0; s0 < ns; s0 += 8) {
+        if (s0 > 0) fetch(s0);
+        float Mc = M;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) Mc = (s0 + j < ns) ? fmaxf(Mc, ml[j].x) : Mc;
+        const float r = __builtin_amdgcn_exp2f(M - Mc);
+        L *= r;
+        acc *= r;
+        M = Mc;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const bool live = s0 + j < ns && ml[j].x != -INFINITY;
+            const float wgt = __builtin_amdgcn_exp2f(ml[j].x - M);
+            L += live ? wgt * ml[j].y : 0.f;
+            acc += live ? wgt * po[j] : 0.f;
+        }
     }
     const __bf16 r = (__bf16)(acc / L);
     ((unsigned short *)a.out)[(int64_t)row * 128 + d] = *(const unsigned short *)&r;
@@ -276,11 +306,12 @@ hipError_t launch_decode_bf16(const Geom &g, const BatchDev &b, const AttnArgs &
     return hipGetLastError();
 }
 
-hipError_t launch_decode_finish(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L)
+hipError_t launch_decode_finish(const Geom &g, const BatchDev &b, const AttnArgs &a, int max_splits, const Launch &L)
 {
     const int n_rows = b.total_S * g.Hq;
     if (n_rows == 0) return hipSuccess;
-    hipExtLaunchKernelGGL(decode_finish_kernel, dim3(n_rows), dim3(128), 0, L.stream, L.start, L.stop, 0, g, b, a);
+    if (max_splits < 1) return hipErrorInvalidValue;
+    hipExtLaunchKernelGGL(decode_finish_kernel, dim3(n_rows), dim3(128), 0, L.stream, L.start, L.stop, 0, g, b, a, max_splits);
     return hipGetLastError();
 }
 

@@ -273,7 +273,7 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
     // the four waves of a work-group and over `ns` work-groups: enough of them to cover the chip,
     // but at least eight key tiles each (two per wave).  Sequences that alias table slots carry
     // unused block tails, which these kernels do not mask: they keep to the prefill kernels.
-    if (bf16 && G <= 32 && p.total_S > 0 && p.block_pad.empty() && ctx->forced_row_blocks == 0 &&
+    if (bf16 && G <= 32 && p.total_S > 0 && ctx->forced_row_blocks == 0 &&
         (ctx->forced_attn_kernel == 0 || ctx->forced_attn_kernel == 3) &&
         std::all_of(p.suffix_len.begin(), p.suffix_len.end(), [](int32_t s) { return s <= 1; })) {
         int n_q = 0;
@@ -287,7 +287,7 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
             if (p.suffix_len[i] <= 0) continue;
             const int P = p.prefix_len[i];
             const int n_tiles = (P + KT - 1) / KT;
-            int ns = ctx->forced_splits > 0 ? ctx->forced_splits : std::min(cap, std::max(1, n_tiles / 8));
+            int ns = ctx->forced_splits > 0 ? ctx->forced_splits : std::min(cap, std::max(1, n_tiles / 6));
             ns = std::max(ns, (n_tiles + kAttnMaxTiles - 1) / kAttnMaxTiles);
             ns = std::max(1, std::min(ns, std::max(n_tiles, 1)));
             splits_of_q[i] = ns;
@@ -929,6 +929,21 @@ tc_status tc_stitch_kv_rope(tc_ctx *ctx, const int32_t *table_ids, const int32_t
                          true, pos0, rope_theta);
 }
 
+// Block-format slots: the number of unused token positions of block id `b` of a table slot, or -1
+// if no fully loaded table covers that block.
+static int32_t slot_block_pad(const tc_ctx *ctx, int32_t b)
+{
+    const int32_t s = b / ctx->slot_blocks, j = b % ctx->slot_blocks;
+    if (s < 0 || s >= (int32_t)ctx->slots.size() || ctx->slots[s].table < 0) return -1;
+    auto it = ctx->tables.find(ctx->slots[s].table);
+    if (it == ctx->tables.end()) return -1;
+    const Table &t = it->second;
+    for (uint8_t l : t.layer_loaded) if (!l) return -1;
+    const int nb = (t.n_tokens + kBlockTokens - 1) / kBlockTokens;
+    if (j >= nb) return -1;
+    return j == nb - 1 ? nb * kBlockTokens - t.n_tokens : 0;
+}
+
 tc_status tc_stitch_alias(tc_ctx *ctx, const int32_t *table_ids, const int32_t *cu_tables, int32_t B,
                           const int32_t *suffix_len, int32_t *block_table, int32_t max_blocks,
                           int32_t *prefix_len, void *stream_)
@@ -1044,6 +1059,7 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
         if (cu_seqlens[0] != 0) return fail(ctx, TC_ERR_INVALID, "attn: cu_seqlens[0] != 0");
         Plan p;
         p.B = B; p.max_blocks = max_blocks;
+        std::set<int32_t> used_slots;
         for (int i = 0; i < B; ++i) {
             if (prefix_len[i] < 0 || suffix_len[i] < 0 || cu_seqlens[i + 1] - cu_seqlens[i] != suffix_len[i])
                 return fail(ctx, TC_ERR_INVALID, "attn: lengths of query %d are inconsistent", i);
@@ -1051,10 +1067,21 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
             if (nb > max_blocks) return fail(ctx, TC_ERR_INVALID, "attn: query %d needs %lld blocks > max_blocks", i, (long long)nb);
             for (int j = 0; j < nb; ++j) {
                 const int32_t b = block_table[(size_t)i * max_blocks + j];
-                if (b < ctx->first_seq || b >= ctx->cfg.n_pool_blocks)
-                    return fail(ctx, TC_ERR_INVALID, "attn: block_table[%d][%d] = %d is not a sequence block", i, j, b);
+                if (b >= ctx->first_seq && b < ctx->cfg.n_pool_blocks) continue;
+                // block-format slots: a block of a cached table, read in place.  Which of its
+                // positions hold tokens follows from the table that sits in the slot now.
+                int32_t pad = -1;
+                if (ctx->cfg.slot_layout == TC_SLOTS_BLOCKS && b >= 0 && b < ctx->first_seq &&
+                    (int64_t)(j + 1) * kBlockTokens <= prefix_len[i])
+                    pad = slot_block_pad(ctx, b);
+                if (pad < 0)
+                    return fail(ctx, TC_ERR_INVALID, "attn: block_table[%d][%d] = %d is not a block this sequence may read", i, j, b);
+                if (p.block_pad.empty()) p.block_pad.assign((size_t)B * max_blocks, 0);
+                p.block_pad[(size_t)i * max_blocks + j] = (uint8_t)pad;
+                used_slots.insert(b / ctx->slot_blocks);
             }
         }
+        p.alias_slots.assign(used_slots.begin(), used_slots.end());
         p.total_S = cu_seqlens[B];
         p.block_table.assign(block_table, block_table + (size_t)B * max_blocks);
         p.cu_seqlens.assign(cu_seqlens, cu_seqlens + B + 1);
@@ -1062,6 +1089,10 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
         p.suffix_len.assign(suffix_len, suffix_len + B);
         tc_status st = upload_plan(ctx, p, {}, {}, {}, stream);
         if (st != TC_OK) return st;
+        for (int32_t sidx : p.alias_slots) {        // the launches come after the loads of what they read
+            Slot &sl = ctx->slots[sidx];
+            if (sl.ready_pending && sl.ready_stream != stream) TC_HIP(ctx, hipStreamWaitEvent(stream, sl.ready, 0));
+        }
         ctx->plan = std::move(p);
     }
     Plan &p = ctx->plan;
@@ -1083,7 +1114,7 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
         a.part_o = ctx->d_part;
         a.part_ml = ctx->d_part + (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * ctx->cfg.head_dim;
         TC_HIP(ctx, timed_launch(ctx, 2, stream, [&](const Launch &ln) { return launch_decode_bf16(ctx->geom, p.dev, a, ln); }));
-        TC_HIP(ctx, timed_launch(ctx, 3, stream, [&](const Launch &ln) { return launch_decode_finish(ctx->geom, p.dev, a, ln); }));
+        TC_HIP(ctx, timed_launch(ctx, 3, stream, [&](const Launch &ln) { return launch_decode_finish(ctx->geom, p.dev, a, p.max_splits, ln); }));
         return TC_OK;
     }
     if (!bf16)      // the bf16 attention launch appends in extra work-groups of its own
@@ -1121,7 +1152,9 @@ tc_status tc_grow_seqs(tc_ctx *ctx, int32_t *block_table, int32_t max_blocks, in
         const int32_t *row = block_table + (size_t)i * max_blocks;
         int h = 0;
         while (h < max_blocks && row[h] >= 0) {
-            if (row[h] < ctx->first_seq || row[h] >= ctx->cfg.n_pool_blocks || !ctx->seq_used[row[h] - ctx->first_seq])
+            const bool table_block = ctx->cfg.slot_layout == TC_SLOTS_BLOCKS && row[h] < ctx->first_seq;   // read in place
+            if (!table_block &&
+                (row[h] < ctx->first_seq || row[h] >= ctx->cfg.n_pool_blocks || !ctx->seq_used[row[h] - ctx->first_seq]))
                 return fail(ctx, TC_ERR_INVALID, "grow: %d is not an allocated sequence block", row[h]);
             ++h;
         }

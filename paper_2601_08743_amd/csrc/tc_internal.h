@@ -127,7 +127,7 @@ hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a,
                             const Launch &L);
 // decode_attn_bf16.hip
 hipError_t launch_decode_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L);
-hipError_t launch_decode_finish(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L);
+hipError_t launch_decode_finish(const Geom &g, const BatchDev &b, const AttnArgs &a, int max_splits, const Launch &L);
 hipError_t launch_attn_f32(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L);
 hipError_t launch_merge(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L);
 hipError_t launch_merge_bf16(const Geom &g, const AttnArgs &a, const MergeGroup *groups, int n_groups,

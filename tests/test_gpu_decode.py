@@ -99,6 +99,95 @@ def test_decode_steps_after_prefill(H, splits, kind):
     dw.close()
 
 
+@pytest.mark.parametrize("kind", [0, 1])
+def test_decode_steps_over_tables_read_in_place(H, kind):
+    """The same over sequences whose table part was never copied (block-format slots,
+    tc_stitch_alias): the decode batches name the table slots' blocks, the library works out from
+    the cached tables which positions of those blocks hold tokens, and the result must be the
+    attention over the plain concatenation.  Positions are those of the padded sequence (each table
+    rounded up to whole blocks); tables of 3 .. 150 tokens, so some are shorter than a block and a
+    key tile can hold several unused tails."""
+    from paper_2601_08743_amd import binding as B
+    cfg = W.WorkloadConfig(name="decal", n_layers=2, n_q_heads=8, n_kv_heads=2, head_dim=128, dtype="bf16", n_tables=7,
+                           table_len=(3, 150), batch=4, tables_per_query=(1, 4), choice="uniform",
+                           suffix_len=(1, 40), capacity=7, seed=406)
+    wl = W.make_workload(cfg)
+    c = wl.cfg
+    T = 20
+    S = wl.suffix_len.astype(int)
+    nb_pref = np.array([sum(-(-int(wl.table_len[t]) // 16) for t in q) for q in wl.queries])
+    Pp = 16 * nb_pref                                  # padded prefix lengths
+    seq_blocks = int(sum(-(-(s + T) // 16) for s in S)) + 4
+    dw = H.DeviceWorkload(wl, seq_blocks=seq_blocks, slot_layout=B.TC_SLOTS_BLOCKS)
+    dw.ctx.tc_set_attn_kernel(kind)
+    max_blocks = int(max(nb + -(-(s + T) // 16) for nb, s in zip(nb_pref, S))) + 1
+    bt, pl = dw.alias(max_blocks=max_blocks)
+    np.testing.assert_array_equal(pl, Pp)
+    pre = {}
+    for layer in range(c.n_layers):
+        out, qkv = dw.attn_layer(layer, bt, pl)
+        pre[layer] = qkv
+    seq = {}
+    for layer in range(c.n_layers):
+        for i in range(c.batch):
+            ks, vs = H.oracle_sequences(wl, dw.tables_np, layer, i)
+            sl = slice(int(wl.cu_seqlens[i]), int(wl.cu_seqlens[i + 1]))
+            seq[layer, i] = [np.concatenate([ks, pre[layer][1][sl]]), np.concatenate([vs, pre[layer][2][sl]])]
+    one = np.ones(c.batch, dtype=np.int32)
+    cu1 = np.arange(c.batch + 1, dtype=np.int32)
+    worst = 0.0
+    for t in range(T):
+        cur = (Pp + S + t).astype(np.int32)
+        grown = dw.ctx.tc_grow_seqs(bt, cur + 1)
+        np.testing.assert_array_equal(grown[bt >= 0], bt[bt >= 0])         # what was there stays
+        own = grown[grown >= dw.first_seq]
+        assert len(set(own.tolist())) == own.size                          # sequence blocks: nobody shares one
+        assert ((grown >= 0).sum(axis=1) == -(-(cur + 1) // 16)).all()
+        bt = grown
+        for layer in range(c.n_layers):
+            q = _draw(c.seed, layer, t, 0, shape=(c.batch, c.n_q_heads, c.head_dim))
+            k = _draw(c.seed, layer, t, 1, shape=(c.batch, c.n_kv_heads, c.head_dim))
+            v = _draw(c.seed, layer, t, 2, shape=(c.batch, c.n_kv_heads, c.head_dim))
+            dq, dk, dv = H.to_dev(q, c), H.to_dev(k, c), H.to_dev(v, c)
+            out = torch.full_like(dq, float("nan"))
+            dw.ctx.tc_prefill_attn(layer, dq, dk, dv, out, cu1, bt, cur, one, wl.sm_scale, None)
+            torch.cuda.synchronize()
+            assert dw.ctx.tc_attn_kernel() == (3 if kind == 0 else 1)
+            got = H.out_to_f64(out, c)
+            for i in range(c.batch):
+                K, V = seq[layer, i]
+                ref = oracle.prefill_attn(W.storage_to_f64(q[i:i + 1], "bf16"), W.storage_to_f64(K, "bf16"),
+                                          W.storage_to_f64(V, "bf16"), W.storage_to_f64(k[i:i + 1], "bf16"),
+                                          W.storage_to_f64(v[i:i + 1], "bf16"), wl.sm_scale)
+                worst = max(worst, float(np.abs(got[i:i + 1] - ref).max()))
+                seq[layer, i] = [np.concatenate([K, k[i:i + 1]]), np.concatenate([V, v[i:i + 1]])]
+    assert worst <= 1e-2, worst
+    # the part of every sequence that is its own (prompt suffix, generated tokens) sits behind the
+    # table blocks, bit for bit; the table slots were only read
+    for layer in range(c.n_layers):
+        for i in range(c.batch):
+            n = int(S[i] + T)
+            kk, vv = dw.ctx.tc_read_seq_kv(layer, bt[i, nb_pref[i]:nb_pref[i] + -(-n // 16)], n, np.uint16)
+            P_real = int(wl.table_len[wl.queries[i]].sum())
+            np.testing.assert_array_equal(kk.view(np.uint8), seq[layer, i][0][P_real:].view(np.uint8))
+            np.testing.assert_array_equal(vv.view(np.uint8), seq[layer, i][1][P_real:].view(np.uint8))
+    # a table block may only stand where the whole block is prefix, and only if a table covers it
+    bad = bt.copy()
+    bad[0, int(cur[0]) // 16] = bt[0, 0]               # the block the new token goes to
+    with pytest.raises(B.TcError) as e:
+        dw.ctx.tc_prefill_attn(0, dq, dk, dv, out, cu1, bad, cur, one, wl.sm_scale, None)
+    assert e.value.code == B.TC_ERR_INVALID
+    t0 = int(wl.queries[0][0])
+    bad = bt.copy()
+    bad[0, 0] = (bt[0, 0] // dw.slot_blocks) * dw.slot_blocks + -(-int(wl.table_len[t0]) // 16)    # behind its table's last block
+    if bad[0, 0] % dw.slot_blocks != 0:
+        with pytest.raises(B.TcError) as e:
+            dw.ctx.tc_prefill_attn(0, dq, dk, dv, out, cu1, bad, cur, one, wl.sm_scale, None)
+        assert e.value.code == B.TC_ERR_INVALID
+    dw.ctx.tc_release_seqs(bt)
+    dw.close()
+
+
 def test_grow_errors_change_nothing(H):
     from paper_2601_08743_amd import binding as B
     cfg = W.WorkloadConfig(name="dec", n_layers=1, n_q_heads=8, n_kv_heads=2, head_dim=128, dtype="bf16", n_tables=2,
