@@ -13,65 +13,133 @@
 
 namespace tc {
 
-// Copy of one block's keys, [t][h][d] rows at k_src + src_off[t] (-1: no such token, zeros) ->
-// the block's K half [h][t][d].
-__device__ __forceinline__ void copy_block_k(const Geom &g, const char *k_src, const int64_t *src_off, char *dst, int tid)
+__device__ __forceinline__ uint4 keep_if(uint4 v, bool keep)        // v, or zeros
+{
+    v.x = keep ? v.x : 0u;
+    v.y = keep ? v.y : 0u;
+    v.z = keep ? v.z : 0u;
+    v.w = keep ? v.w : 0u;
+    return v;
+}
+
+// Copy of one block: token rows [t][h][d] at k_src / v_src + src_off[t] (-1: no such token, zeros)
+// -> the block's K half [h][t][d] at dst and its V half at vdst (through `lds`, [16][row_bytes / 16]
+// chunks, where 2-byte elements are transposed per head).
+//
+// A missing token is loaded from offset 0 (always valid) and the value replaced: written as
+// "offset >= 0 ? load : zero" the compiler selects between the global address and the address of a
+// zero it first stores to scratch memory - 32 bytes of stores per thread, a quarter on top of the
+// block's own bytes.  The loads of a pass (kCopyBatch chunks of K and of V per thread) are all
+// issued before the first store, so that a thread has 128 bytes in flight instead of 16.
+constexpr int kCopyBatch = 4;
+
+// K chunk c of the destination, in address order: consecutive threads write consecutive 16 bytes
+// (a wave covers 1 KB of one head: four token rows), and read 256-byte pieces of four source rows.
+__device__ __forceinline__ uint4 load_k_chunk(const Geom &g, const char *k_src, const int64_t *src_off, int c, bool &ok)
+{
+    const int cph = g.head_bytes >> 4;
+    const int ht = c / cph, dc = c - ht * cph;
+    const int h = ht / kBlockTokens, t = ht - h * kBlockTokens;
+    const int64_t so = src_off[t];
+    ok = so >= 0;
+    return *(const uint4 *)(k_src + (ok ? so : 0) + ((int64_t)(h * cph + dc) << 4));
+}
+// V chunk c in source order (token t, chunk w of its row)
+__device__ __forceinline__ uint4 load_v_chunk(const Geom &g, const char *v_src, const int64_t *src_off, int c, bool &ok)
+{
+    const int cpr = g.row_bytes >> 4;
+    const int t = c / cpr, w = c - t * cpr;
+    const int64_t so = src_off[t];
+    ok = so >= 0;
+    return *(const uint4 *)(v_src + (ok ? so : 0) + ((int64_t)w << 4));
+}
+// where V chunk c goes when it is not transposed: [h][t][d]
+__device__ __forceinline__ int64_t v_plain_offset(const Geom &g, int c)
 {
     const int cpr = g.row_bytes >> 4, cph = g.head_bytes >> 4;
-    const uint4 zero = make_uint4(0, 0, 0, 0);
-    for (int c = tid; c < kBlockTokens * cpr; c += 256) {
-        const int t = c / cpr, w = c - t * cpr;
-        const int h = w / cph, dc = w - h * cph;
-        const int64_t so = src_off[t];
-        const uint4 v = so >= 0 ? *(const uint4 *)(k_src + so + ((int64_t)w << 4)) : zero;
-        *(uint4 *)(dst + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = v;
+    const int t = c / cpr, w = c - t * cpr;
+    const int h = w / cph, dc = w - h * cph;
+    return (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4);
+}
+
+// second half of the transposing path: out chunk oc = (h, d, half): 8 tokens of one (h, d)
+__device__ __forceinline__ void store_v_transposed(const Geom &g, const uint4 *lds, char *vdst, int tid)
+{
+    const unsigned short *l16 = (const unsigned short *)lds;
+    const int row_elems = g.row_bytes >> 1;
+    const int n_out = g.Hkv * g.D * 2;
+    for (int oc = tid; oc < n_out; oc += 256) {
+        const int half = oc & 1;
+        const int hd = oc >> 1;                // h * D + d
+        unsigned short e[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int t = (k & 3) | ((k & 4) << 1) | (half << 2);
+            e[k] = l16[t * row_elems + hd];
+        }
+        uint4 v;
+        v.x = e[0] | ((unsigned)e[1] << 16);
+        v.y = e[2] | ((unsigned)e[3] << 16);
+        v.z = e[4] | ((unsigned)e[5] << 16);
+        v.w = e[6] | ((unsigned)e[7] << 16);
+        *(uint4 *)(vdst + ((int64_t)oc << 4)) = v;
     }
 }
 
-// The same for the values: rows at v_src + src_off[t] -> the block's V half (vdst), transposed
-// per head for 2-byte elements (through `lds`, [16][row_bytes / 16] chunks).
+// The values alone (the re-encoding stitch turns the keys itself).
 template <bool kTransposeV>
 __device__ __forceinline__ void copy_block_v(const Geom &g, const char *v_src, const int64_t *src_off, char *vdst,
                                              uint4 *lds, int tid)
 {
-    const int cpr = g.row_bytes >> 4, cph = g.head_bytes >> 4;
-    const int n_chunks = kBlockTokens * cpr;
-    const uint4 zero = make_uint4(0, 0, 0, 0);
-    if (!kTransposeV) {
-        for (int c = tid; c < n_chunks; c += 256) {
-            const int t = c / cpr, w = c - t * cpr;
-            const int h = w / cph, dc = w - h * cph;
-            const int64_t so = src_off[t];
-            const uint4 v = so >= 0 ? *(const uint4 *)(v_src + so + ((int64_t)w << 4)) : zero;
-            *(uint4 *)(vdst + (int64_t)(h * kBlockTokens + t) * g.head_bytes + (dc << 4)) = v;
-        }
-    } else {
-        for (int c = tid; c < n_chunks; c += 256) {
-            const int t = c / cpr, w = c - t * cpr;
-            const int64_t so = src_off[t];
-            lds[c] = so >= 0 ? *(const uint4 *)(v_src + so + ((int64_t)w << 4)) : zero;
-        }
-        __syncthreads();
-        // out chunk oc = (h, d, half): 8 tokens of one (h, d), 2-byte elements
-        const unsigned short *l16 = (const unsigned short *)lds;
-        const int row_elems = g.row_bytes >> 1;
-        const int n_out = g.Hkv * g.D * 2;
-        for (int oc = tid; oc < n_out; oc += 256) {
-            const int half = oc & 1;
-            const int hd = oc >> 1;                // h * D + d
-            unsigned short e[8];
+    const int n_chunks = kBlockTokens * (g.row_bytes >> 4);
+    for (int c0 = tid; c0 < n_chunks; c0 += 256 * kCopyBatch) {
+        uint4 v[kCopyBatch];
+        bool ok[kCopyBatch];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int t = (k & 3) | ((k & 4) << 1) | (half << 2);
-                e[k] = l16[t * row_elems + hd];
-            }
-            uint4 v;
-            v.x = e[0] | ((unsigned)e[1] << 16);
-            v.y = e[2] | ((unsigned)e[3] << 16);
-            v.z = e[4] | ((unsigned)e[5] << 16);
-            v.w = e[6] | ((unsigned)e[7] << 16);
-            *(uint4 *)(vdst + ((int64_t)oc << 4)) = v;
+        for (int j = 0; j < kCopyBatch; ++j) v[j] = load_v_chunk(g, v_src, src_off, min(c0 + 256 * j, n_chunks - 1), ok[j]);
+#pragma unroll
+        for (int j = 0; j < kCopyBatch; ++j) {
+            const int c = c0 + 256 * j;
+            if (c >= n_chunks) continue;
+            if (kTransposeV) lds[c] = keep_if(v[j], ok[j]);
+            else *(uint4 *)(vdst + v_plain_offset(g, c)) = keep_if(v[j], ok[j]);
         }
+    }
+    if (kTransposeV) {
+        __syncthreads();
+        store_v_transposed(g, lds, vdst, tid);
+    }
+}
+
+// Keys and values of one block together.
+template <bool kTransposeV>
+__device__ __forceinline__ void copy_block_kv(const Geom &g, const char *k_src, const char *v_src, const int64_t *src_off,
+                                              char *dst, char *vdst, uint4 *lds, int tid)
+{
+    const int n_chunks = kBlockTokens * (g.row_bytes >> 4);
+    for (int c0 = tid; c0 < n_chunks; c0 += 256 * kCopyBatch) {
+        uint4 kk[kCopyBatch], vv[kCopyBatch];
+        bool kok[kCopyBatch], vok[kCopyBatch];
+#pragma unroll
+        for (int j = 0; j < kCopyBatch; ++j) kk[j] = load_k_chunk(g, k_src, src_off, min(c0 + 256 * j, n_chunks - 1), kok[j]);
+#pragma unroll
+        for (int j = 0; j < kCopyBatch; ++j) vv[j] = load_v_chunk(g, v_src, src_off, min(c0 + 256 * j, n_chunks - 1), vok[j]);
+#pragma unroll
+        for (int j = 0; j < kCopyBatch; ++j) {
+            const int c = c0 + 256 * j;
+            if (c < n_chunks) *(uint4 *)(dst + ((int64_t)c << 4)) = keep_if(kk[j], kok[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < kCopyBatch; ++j) {
+            const int c = c0 + 256 * j;
+            if (c >= n_chunks) continue;
+            if (kTransposeV) lds[c] = keep_if(vv[j], vok[j]);
+            else *(uint4 *)(vdst + v_plain_offset(g, c)) = keep_if(vv[j], vok[j]);
+        }
+    }
+    if (kTransposeV) {
+        __syncthreads();
+        store_v_transposed(g, lds, vdst, tid);
     }
 }
 
@@ -116,7 +184,8 @@ __global__ __launch_bounds__(256) void stitch_kernel(Geom g, BatchDev b, int l0)
     const int n_chunks = kBlockTokens * cpr;
     const uint4 zero = make_uint4(0, 0, 0, 0);
     if (!kRope) {
-        copy_block_k(g, layer_base, src_off, dst, tid);
+        copy_block_kv<kTransposeV>(g, layer_base, layer_base + (g.slot_bytes >> 1), src_off, dst, dst + (g.block_bytes >> 1), lds, tid);
+        return;
     } else {
         // one unit = the two 16-byte chunks of a head row that hold elements i and i + D/2.  The
         // loads of a pass of kUnits units per thread are issued first; the rotation table is built
@@ -237,8 +306,7 @@ __global__ __launch_bounds__(256) void format_kernel(Geom g, const char *raw, in
     }
     __syncthreads();
     char *dst = g.pool + (int64_t)layer * g.layer_stride + (int64_t)(first_block + blockIdx.x) * g.block_bytes;
-    copy_block_k(g, raw, src_off, dst, tid);
-    copy_block_v<kTransposeV>(g, raw + v_part, src_off, dst + (g.block_bytes >> 1), lds, tid);
+    copy_block_kv<kTransposeV>(g, raw, raw + v_part, src_off, dst, dst + (g.block_bytes >> 1), lds, tid);
 }
 
 hipError_t launch_format(const Geom &g, const void *raw, int64_t v_part, int n_tokens, int first_block, int l0,
