@@ -90,18 +90,27 @@ __device__ __forceinline__ void tile_math(RowState<RB> &st, const bf16x8 (&qf)[R
 #pragma unroll
                 for (int e = 0; e < 16; ++e) sacc[rb][mb][e] = 0.f;
     }
+    // The operand fragments run two reads ahead of the matrix instruction that consumes them (a ring
+    // of three): read one by one in front of its instruction, every fragment costs a full LDS round
+    // trip during which the wave issues nothing.
+    {
+        bf16x8 kf[3];
+#define TC_KFRAG(j) (*(const bf16x8 *)(k_ld + ((j) & 1) * 32 * kKRow + ((j) >> 1) * 32))
+        kf[0] = TC_KFRAG(0);
+        kf[1] = TC_KFRAG(1);
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-            const bf16x8 ka = *(const bf16x8 *)(k_ld + mb * 32 * kKRow + ks * 32);
+        for (int j = 0; j < 16; ++j) {
+            const int ks = j >> 1, mb = j & 1;
+            if (j + 2 < 16) kf[(j + 2) % 3] = TC_KFRAG(j + 2);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                if (!kAsmScores) sacc[rb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[rb][ks], sacc[rb][mb], 0, 0, 0);
-                else if (ks == 0) mfma_first(sacc[rb][mb], ka, qf[rb][ks]);
-                else mfma_v(sacc[rb][mb], ka, qf[rb][ks]);
+                if (!kAsmScores) sacc[rb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j % 3], qf[rb][ks], sacc[rb][mb], 0, 0, 0);
+                else if (ks == 0) mfma_first(sacc[rb][mb], kf[j % 3], qf[rb][ks]);
+                else mfma_v(sacc[rb][mb], kf[j % 3], qf[rb][ks]);
             }
         }
+#undef TC_KFRAG
+    }
     if (kAsmScores) {
         static_assert(!kAsmScores || RB == 1, "one row block per wave");
         asm volatile("s_nop 11" : "+v"(sacc[0][0]), "+v"(sacc[0][1]));
@@ -149,21 +158,28 @@ __device__ __forceinline__ void tile_math(RowState<RB> &st, const bf16x8 (&qf)[R
             }
     }
     // O^T[d][row] += V^T[d][key] P^T[key][row]: four 16-key groups (one pool block each)
+    {
+        bf16x8 vf[3];
+#define TC_VFRAG(j) (*(const bf16x8 *)(v_ld + ((j) >> 2) * kHeadBlk + ((j) & 3) * 32 * 32))
+        vf[0] = TC_VFRAG(0);
+        vf[1] = TC_VFRAG(1);
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        bf16x8 pf[RB];
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 pf[RB];
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
+            for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) pf[rb][e] = (__bf16)sacc[rb][kk >> 1][8 * (kk & 1) + e];
+                for (int e = 0; e < 8; ++e) pf[rb][e] = (__bf16)sacc[rb][kk >> 1][8 * (kk & 1) + e];
 #pragma unroll
-        for (int db = 0; db < 4; ++db) {
-            const bf16x8 va = *(const bf16x8 *)(v_ld + kk * kHeadBlk + db * 32 * 32);
+            for (int db = 0; db < 4; ++db) {
+                const int j = 4 * kk + db;
+                if (j + 2 < 16) vf[(j + 2) % 3] = TC_VFRAG(j + 2);
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                st.o[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[rb], st.o[rb][db], 0, 0, 0);
+                for (int rb = 0; rb < RB; ++rb)
+                    st.o[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j % 3], pf[rb], st.o[rb][db], 0, 0, 0);
             }
         }
+#undef TC_VFRAG
     }
 }
 
