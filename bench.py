@@ -107,6 +107,8 @@ def bench_pipeline(args):
                 torch.cuda.synchronize()
                 ctx.tc_destroy()
             ctx = B.Context(cfg, pool)
+            if args.attn_kernel:
+                ctx.tc_set_attn_kernel(args.attn_kernel)
             for t in range(c.n_tables):
                 ctx.tc_register_table_kv(t, int(wl.table_len[t]), host_kv[t][0], host_kv[t][1])
             ctx.tc_load_async(list(range(c.capacity - 1, -1, -1)), 0, L, s_load)
@@ -359,6 +361,8 @@ def main():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--splits", type=int, default=0, help="force split-KV partitions (0 = automatic)")
     ap.add_argument("--row-blocks", type=int, default=0, help="force 128 (1) or 256 (2) rows per work-group")
+    ap.add_argument("--attn-kernel", type=int, default=0,
+                    help="force a bf16 attention kernel: 1 general, 2 pipelined, 4 alternating wave groups (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the headline step: skip the extra measurements (re-encoding stitch, front end, "
@@ -438,6 +442,8 @@ def main():
         ctx.tc_set_kv_splits(args.splits)
     if args.row_blocks:
         ctx.tc_set_row_blocks(args.row_blocks)
+    if args.attn_kernel:
+        ctx.tc_set_attn_kernel(args.attn_kernel)
 
     ids, cu_t, cu_s, sl = wl.table_ids, wl.cu_tables, wl.cu_seqlens, wl.suffix_len
     scale = wl.sm_scale
@@ -476,7 +482,8 @@ def main():
     n_splits = None
     bt, pl = ctx.tc_stitch_kv(ids, cu_t, sl, max_blocks, stream)
     n_splits = ctx.tc_kv_splits()
-    kernel_name = {0: "attn_%s_kernel" % c.dtype, 1: "attn_bf16_kernel<1>", 2: "attn_bf16_pipe_kernel"}[ctx.tc_attn_kernel()]
+    kernel_name = {0: "attn_%s_kernel" % c.dtype, 1: "attn_bf16_kernel<1>", 2: "attn_bf16_pipe_kernel",
+                   4: "attn_bf16_pp_kernel"}[ctx.tc_attn_kernel()]
 
     flops_layer = attn_flops_per_layer(c, P, S)
     flops_step = flops_layer * c.n_layers

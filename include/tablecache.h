@@ -285,15 +285,19 @@ tc_status tc_set_kv_splits(tc_ctx *ctx, int32_t n_splits);
  * blocks of 32 rows and reuses every K/V fragment twice), 0 = automatic (256 when the batch still
  * yields enough work-groups to fill the chip).  Results do not depend on it beyond rounding. */
 tc_status tc_set_row_blocks(tc_ctx *ctx, int32_t row_blocks);
-/* Which bf16 attention kernel serves work-groups of 128 rows: 0 = automatic (from the number and
- * length of the batch's work items), 1 = the general kernel (register-staged K/V, running-maximum
- * softmax, two work-groups per CU), 2 = the pipelined kernel (direct-to-LDS K/V, fixed softmax
- * reference with overflow fallback, one work-group per CU), 3 = as 0 (the decode kernels serve
- * batches in which no query brings more than one new token, unless 1 or 2 is forced: the keys of
- * a KV head are split over waves and work-groups, a second kernel combines them and adds the new
- * token).  Results do not depend on it beyond rounding.  Invalidates the cached plan.
- * tc_attn_kernel reports the kernel of the current plan (1, 2 or 3; 0 when no plan is cached, for
- * fp32 contexts and for 256-row work-groups). */
+/* Which bf16 attention kernel serves the batch: 0 = automatic (from the number and length of the
+ * batch's work items), 1 = the general kernel (128 rows per work-group, register-staged K/V,
+ * running-maximum softmax, two work-groups per CU), 2 = the pipelined kernel (128 rows,
+ * direct-to-LDS K/V, fixed softmax reference with overflow fallback, one work-group per CU),
+ * 3 = as 0 (the decode kernels serve batches in which no query brings more than one new token,
+ * unless another kernel is forced: the keys of a KV head are split over waves and work-groups, a
+ * second kernel combines them and adds the new token), 4 = the kernel for long launches (256
+ * rows per work-group in two groups of waves that alternate between matrix and vector work; the
+ * suffix is appended to the pool by a launch of its own before attention, which then reads all
+ * keys from the pool; ignored while tc_set_row_blocks forces a row count).  Results do not depend
+ * on it beyond rounding.  Invalidates the cached plan.
+ * tc_attn_kernel reports the kernel of the current plan (1 .. 4; 0 when no plan is cached, for
+ * fp32 contexts and for forced 256-row work-groups of the general kernel). */
 tc_status tc_set_attn_kernel(tc_ctx *ctx, int32_t kind);
 int32_t tc_attn_kernel(const tc_ctx *ctx);
 

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtablecache.so")
-SOURCES = ["tc_host.hip", "kv_stitch.hip", "prefill_attn_bf16.hip", "prefill_attn_f32.hip", "decode_attn_bf16.hip",
+SOURCES = ["tc_host.hip", "kv_stitch.hip", "prefill_attn_bf16.hip", "prefill_attn_f32.hip", "decode_attn_bf16.hip", "prefill_attn_pp_bf16.hip",
            "frontend.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 instructions

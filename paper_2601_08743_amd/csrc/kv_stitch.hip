@@ -63,7 +63,8 @@ __device__ __forceinline__ int64_t v_plain_offset(const Geom &g, int c)
 }
 
 // second half of the transposing path: out chunk oc = (h, d, half): 8 tokens of one (h, d)
-__device__ __forceinline__ void store_v_transposed(const Geom &g, const uint4 *lds, char *vdst, int tid)
+// t_first > 0: tokens below t_first keep what the block already holds (read, merged, written back)
+__device__ __forceinline__ void store_v_transposed(const Geom &g, const uint4 *lds, char *vdst, int tid, int t_first = 0)
 {
     const unsigned short *l16 = (const unsigned short *)lds;
     const int row_elems = g.row_bytes >> 1;
@@ -71,11 +72,15 @@ __device__ __forceinline__ void store_v_transposed(const Geom &g, const uint4 *l
     for (int oc = tid; oc < n_out; oc += 256) {
         const int half = oc & 1;
         const int hd = oc >> 1;                // h * D + d
+        uint4 old = make_uint4(0, 0, 0, 0);
+        if (t_first > 0) old = *(const uint4 *)(vdst + ((int64_t)oc << 4));
+        const unsigned o32[4] = {old.x, old.y, old.z, old.w};
         unsigned short e[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int t = (k & 3) | ((k & 4) << 1) | (half << 2);
-            e[k] = l16[t * row_elems + hd];
+            const unsigned short fresh = l16[t * row_elems + hd];
+            e[k] = t >= t_first ? fresh : (unsigned short)(o32[k >> 1] >> (16 * (k & 1)));
         }
         uint4 v;
         v.x = e[0] | ((unsigned)e[1] << 16);
@@ -114,9 +119,10 @@ __device__ __forceinline__ void copy_block_v(const Geom &g, const char *v_src, c
 // Keys and values of one block together.
 template <bool kTransposeV>
 __device__ __forceinline__ void copy_block_kv(const Geom &g, const char *k_src, const char *v_src, const int64_t *src_off,
-                                              char *dst, char *vdst, uint4 *lds, int tid)
+                                              char *dst, char *vdst, uint4 *lds, int tid, int t_first = 0)
 {
     const int n_chunks = kBlockTokens * (g.row_bytes >> 4);
+    const int cpr = g.row_bytes >> 4, cph = g.head_bytes >> 4;
     for (int c0 = tid; c0 < n_chunks; c0 += 256 * kCopyBatch) {
         uint4 kk[kCopyBatch], vv[kCopyBatch];
         bool kok[kCopyBatch], vok[kCopyBatch];
@@ -127,19 +133,20 @@ __device__ __forceinline__ void copy_block_kv(const Geom &g, const char *k_src, 
 #pragma unroll
         for (int j = 0; j < kCopyBatch; ++j) {
             const int c = c0 + 256 * j;
-            if (c < n_chunks) *(uint4 *)(dst + ((int64_t)c << 4)) = keep_if(kk[j], kok[j]);
+            // (K chunk c belongs to token (c / cph) % 16, V chunk c to token c / cpr)
+            if (c < n_chunks && (c / cph) % kBlockTokens >= t_first) *(uint4 *)(dst + ((int64_t)c << 4)) = keep_if(kk[j], kok[j]);
         }
 #pragma unroll
         for (int j = 0; j < kCopyBatch; ++j) {
             const int c = c0 + 256 * j;
             if (c >= n_chunks) continue;
             if (kTransposeV) lds[c] = keep_if(vv[j], vok[j]);
-            else *(uint4 *)(vdst + v_plain_offset(g, c)) = keep_if(vv[j], vok[j]);
+            else if (c / cpr >= t_first) *(uint4 *)(vdst + v_plain_offset(g, c)) = keep_if(vv[j], vok[j]);
         }
     }
     if (kTransposeV) {
         __syncthreads();
-        store_v_transposed(g, lds, vdst, tid);
+        store_v_transposed(g, lds, vdst, tid, t_first);
     }
 }
 
@@ -346,6 +353,65 @@ __global__ __launch_bounds__(256) void append_kernel(Geom g, BatchDev b, int lay
                                                      const char *k_new, const char *v_new)
 {
     append_unit<kTransposeV>(g, b, layer, k_new, v_new, blockIdx.x, threadIdx.x);
+}
+
+// Append by blocks, for launches that must have the suffix in the pool before attention starts:
+// one work-group per sequence block that holds suffix tokens.  A block that lies wholly behind the
+// prefix is written like a stitched block (rows of k_new / v_new as the source, zeros behind the
+// end of the sequence); in the one block a query may share with its prefix the prefix tokens stay
+// (keys: their rows are skipped; transposed values: 16 bytes read, merged, written back).
+template <bool kTransposeV>
+__global__ __launch_bounds__(256) void append_blocks_kernel(Geom g, BatchDev b, int layer,
+                                                            const char *k_new, const char *v_new)
+{
+    extern __shared__ uint4 lds[];
+    __shared__ int64_t src_off[kBlockTokens];
+    const int tid = threadIdx.x;
+    // which query, which of its blocks: the queries' block counts are fetched 256 at a time (one
+    // round trip), then every thread walks them in LDS
+    __shared__ int s_P[256], s_S[256], s_cu[256];
+    int rem = blockIdx.x, i = -1, P = 0, S = 0, cu = 0;
+    for (int i0 = 0; i0 < b.B && i < 0; i0 += 256) {
+        if (i0 + tid < b.B) {
+            const int c0 = b.cu_seqlens[i0 + tid];
+            s_P[tid] = b.prefix_len[i0 + tid];
+            s_S[tid] = b.cu_seqlens[i0 + tid + 1] - c0;
+            s_cu[tid] = c0;
+        }
+        __syncthreads();
+        const int m = min(256, b.B - i0);
+        for (int j = 0; j < m; ++j) {
+            const int Pq = s_P[j], Sq = s_S[j];
+            const int nb = Sq > 0 ? ((Pq + Sq + kBlockTokens - 1) >> 4) - (Pq >> 4) : 0;
+            if (rem < nb) { i = i0 + j; P = Pq; S = Sq; cu = s_cu[j]; break; }
+            rem -= nb;
+        }
+        __syncthreads();
+    }
+    if (i < 0) return;
+    // token t of the block is suffix token p0 + t - P (none before the prefix ends or behind the
+    // sequence's end: the former keep what the stitch wrote, the latter become zeros)
+    const int blk = (P >> 4) + rem, p0 = blk * kBlockTokens;
+    const int t_first = max(P - p0, 0);
+    if (tid < kBlockTokens) {
+        const int pos = p0 + tid;
+        src_off[tid] = pos >= P && pos < P + S ? (int64_t)(cu + pos - P) * g.row_bytes : -1;
+    }
+    __syncthreads();
+    const int phys = entry_bid(b.block_table[(int64_t)i * b.max_blocks + blk]);
+    char *dst = g.pool + (int64_t)layer * g.layer_stride + (int64_t)phys * g.block_bytes;
+    copy_block_kv<kTransposeV>(g, k_new, v_new, src_off, dst, dst + (g.block_bytes >> 1), lds, tid, t_first);
+}
+
+hipError_t launch_append_blocks(const Geom &g, const BatchDev &b, int layer, const void *k_new, const void *v_new,
+                                int n_blocks, const Launch &L)
+{
+    if (n_blocks == 0) return hipSuccess;
+    if (g.esize == 2)
+        TC_LAUNCH(append_blocks_kernel<true>, n_blocks, kBlockTokens * g.row_bytes, L, g, b, layer, (const char *)k_new, (const char *)v_new);
+    else
+        TC_LAUNCH(append_blocks_kernel<false>, n_blocks, 0, L, g, b, layer, (const char *)k_new, (const char *)v_new);
+    return hipGetLastError();
 }
 
 hipError_t launch_append(const Geom &g, const BatchDev &b, int layer, const void *k_new,

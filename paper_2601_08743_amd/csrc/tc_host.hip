@@ -117,6 +117,7 @@ struct Plan {
     int32_t B = 0, max_blocks = 0, total_S = 0, n_stitch_blk = 0, n_items = 0, max_splits = 1, n_groups = 0, row_blocks = 1;
     bool pipelined = false;     // bf16, one row block per wave: the pipelined attention kernel
     bool decode = false;        // bf16, at most one new token per query: the decode kernels
+    bool pingpong = false;      // bf16, 256 rows per work-group in two alternating wave groups; the suffix is appended first
     bool rope = false;          // the stitch re-encodes keys by position (Sec. 4.1.1)
     std::vector<int32_t> rope_pos0;      // [B]
     std::vector<double> rope_rev_freq;   // [D/2]
@@ -268,6 +269,7 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
     const bool bf16 = c.dtype == TC_BF16;
     const int KT = bf16 ? kAttnKeys : kF32Keys;
     p.decode = false;
+    p.pingpong = false;
     // Decode step: every query brings at most one new token, so a KV head has only G rows and the
     // work is reading K and V once.  The decode kernels split the keys of a (query, KV head) over
     // the four waves of a work-group and over `ns` work-groups: enough of them to cover the chip,
@@ -312,12 +314,33 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
     }
     // key tiles of a query.  bf16 kernel: the tiles of the prefix (from the pool), then the tiles of
     // the suffix (from k_new / v_new); fp32 kernel: one paged sequence of P + S keys
+    // the alternating-groups bf16 kernel reads the suffix from the pool as well (it is appended by a
+    // launch of its own first), so it, too, sees one paged sequence
+    // It is chosen for long launches (estimated from the row tiles x key tiles of the batch at
+    // ~0.85 us per 128 x 64 tile and CU): its own append launch costs ~10 us, and with 256 rows per
+    // work-group a short launch would not fill the chip.  Measured: c3 (1140 items of ~24 tiles)
+    // 207 + 12 us against 226 us in the general kernel, c4 775 + 14 us against 814 us in the pipelined
+    // one; c2 (17 us) and the micro-batches of the loading pipeline stay with the other kernels.
+    bool pp = false;
+    if (bf16 && ctx->forced_row_blocks == 0) {
+        if (ctx->forced_attn_kernel == 4) pp = true;
+        else if (ctx->forced_attn_kernel == 0) {
+            double work = 0;
+            for (int i = 0; i < p.B; ++i)
+                if (p.suffix_len[i] > 0)
+                    work += (double)c.n_kv_heads * ((p.suffix_len[i] * G + kAttnRows - 1) / kAttnRows) *
+                            ((p.prefix_len[i] + p.suffix_len[i] + KT - 1) / KT);
+            pp = work * 0.85 / 256.0 >= 80.0;
+        }
+    }
+    const bool unified = !bf16 || pp;
+    p.pingpong = pp;
     auto tiles_of = [&](int P, int S) {
-        return bf16 ? (P + KT - 1) / KT + (S + KT - 1) / KT : (P + S + KT - 1) / KT;
+        return unified ? (P + S + KT - 1) / KT : (P + KT - 1) / KT + (S + KT - 1) / KT;
     };
     // bf16: 128 rows per work-group; 256 (two row blocks per wave, half the LDS traffic per flop but one
     // wave per SIMD) is kept as an option: it is slower until its matrix and vector work overlap
-    const int rb = (bf16 && ctx->forced_row_blocks > 0) ? ctx->forced_row_blocks : 1;
+    const int rb = pp ? 2 : (bf16 && ctx->forced_row_blocks > 0) ? ctx->forced_row_blocks : 1;
     p.row_blocks = rb;
     const int RT = bf16 ? kAttnRows * rb : kF32Rows;
     int64_t base = 0, tiles_sum = 0, n_q = 0;
@@ -360,8 +383,8 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
         if (S <= 0) continue;
         const int n_tiles = tiles_of(P, S);
         // last block a tile load may touch: bf16 reads only prefix blocks from the pool
-        const int last_blk = std::max(0, (bf16 ? (P + kBlockTokens - 1) / kBlockTokens
-                                               : (P + S + kBlockTokens - 1) / kBlockTokens) - 1);
+        const int last_blk = std::max(0, (unified ? (P + S + kBlockTokens - 1) / kBlockTokens
+                                                  : (P + kBlockTokens - 1) / kBlockTokens) - 1);
         int ns = std::min(want, ctx->forced_splits > 0 ? n_tiles : std::max(1, n_tiles / 2));
         if (bf16) ns = std::max(ns, (n_tiles + kAttnMaxTiles - 1) / kAttnMaxTiles);   // block ids of a range fit LDS
         ns = std::max(1, std::min(ns, n_tiles));
@@ -372,7 +395,7 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
         // is transposed on the way into LDS), so the tiles are cut by weight, not by count.
         std::vector<int> cut(ns + 1, 0);
         {
-            const int npt = bf16 ? (P + KT - 1) / KT : n_tiles;
+            const int npt = unified ? n_tiles : (P + KT - 1) / KT;
             const int w_new = 4;
             const int64_t total_w = npt + (int64_t)(n_tiles - npt) * w_new;
             int t = 0;
@@ -400,7 +423,7 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
                         const int idx = std::min(t0 * (KT / kBlockTokens) + k, last_blk);
                         it.bid[k] = bt[idx] | (pad_of ? (int32_t)((uint32_t)pad_of[idx] << kPadShift) : 0);
                     }
-                    if (pad_of && bf16) {
+                    if (pad_of && bf16 && !pp) {
                         const int n_fast = std::min(t1, P >> 6) - t0;
                         for (int k = t0 * 4; k < (t0 + std::max(n_fast, 0)) * 4; ++k) it.n_pad_fast += pad_of[k];
                     }
@@ -446,7 +469,7 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
             ++n_real;
             fast_tiles += std::max(std::min(it.tile_end, it.P >> 6) - it.tile_begin, 0);
         }
-    p.pipelined = bf16 && rb == 1 && n_real > 0 &&
+    p.pipelined = bf16 && rb == 1 && !pp && n_real > 0 &&
                   (ctx->forced_attn_kernel == 1 || ctx->forced_attn_kernel == 2 ? ctx->forced_attn_kernel == 2
                                            : (n_real <= 2 * 256 || fast_tiles >= 48 * n_real));
 }
@@ -1117,18 +1140,26 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
         TC_HIP(ctx, timed_launch(ctx, 3, stream, [&](const Launch &ln) { return launch_decode_finish(ctx->geom, p.dev, a, p.max_splits, ln); }));
         return TC_OK;
     }
-    if (!bf16)      // the bf16 attention launch appends in extra work-groups of its own
+    if (!bf16)      // the bf16 attention launches append in extra work-groups of their own, except:
         TC_HIP(ctx, timed_launch(ctx, 1, stream, [&](const Launch &ln) { return launch_append(ctx->geom, p.dev, layer, k_new, v_new, ln); }));
+    if (p.pingpong) {   // this kernel reads the suffix from the pool: it is appended first, block by block
+        int n_blk = 0;
+        for (int i = 0; i < p.B; ++i)
+            if (p.suffix_len[i] > 0)
+                n_blk += (p.prefix_len[i] + p.suffix_len[i] + kBlockTokens - 1) / kBlockTokens - p.prefix_len[i] / kBlockTokens;
+        TC_HIP(ctx, timed_launch(ctx, 1, stream, [&](const Launch &ln) { return launch_append_blocks(ctx->geom, p.dev, layer, k_new, v_new, n_blk, ln); }));
+    }
     AttnArgs a{};
     a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
-    a.n_append = bf16 ? p.total_S + p.B : 0; a.items = p.items_dev; a.n_items = p.n_items; a.layer = layer;
+    a.n_append = bf16 && !p.pingpong ? p.total_S + p.B : 0; a.items = p.items_dev; a.n_items = p.n_items; a.layer = layer;
     a.scale_log2 = sm_scale * 1.4426950408889634f;
     a.part_o = ctx->d_part;
     a.part_ml = !ctx->d_part ? nullptr
               : bf16 ? ctx->d_part + (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * 64
                      : ctx->d_part + (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * ctx->cfg.head_dim;
     TC_HIP(ctx, timed_launch(ctx, 2, stream, [&](const Launch &ln) {
-        return bf16 ? launch_attn_bf16(ctx->geom, p.dev, a, p.row_blocks, p.pipelined, ln)
+        return p.pingpong ? launch_attn_pp_bf16(ctx->geom, p.dev, a, ln)
+             : bf16 ? launch_attn_bf16(ctx->geom, p.dev, a, p.row_blocks, p.pipelined, ln)
                     : launch_attn_f32(ctx->geom, p.dev, a, ln);
     }));
     if (p.max_splits > 1)
@@ -1265,14 +1296,16 @@ tc_status tc_set_kv_splits(tc_ctx *ctx, int32_t n_splits)
 
 int32_t tc_attn_kernel(const tc_ctx *ctx)
 {
-    if (!ctx || !ctx->plan.valid || ctx->cfg.dtype != TC_BF16 || ctx->plan.row_blocks != 1) return 0;
+    if (!ctx || !ctx->plan.valid || ctx->cfg.dtype != TC_BF16) return 0;
     if (ctx->plan.decode) return 3;
+    if (ctx->plan.pingpong) return 4;
+    if (ctx->plan.row_blocks != 1) return 0;
     return ctx->plan.pipelined ? 2 : 1;
 }
 
 tc_status tc_set_attn_kernel(tc_ctx *ctx, int32_t kind)
 {
-    if (!ctx || kind < 0 || kind > 3) return TC_ERR_INVALID;
+    if (!ctx || kind < 0 || kind > 4) return TC_ERR_INVALID;
     ctx->forced_attn_kernel = kind;
     ctx->plan.valid = false;
     return TC_OK;

@@ -126,6 +126,9 @@ hipError_t launch_readback(const Geom &g, int layer, const int32_t *blocks_dev, 
 hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, int row_blocks, bool pipelined,
                             const Launch &L);
 // decode_attn_bf16.hip
+hipError_t launch_append_blocks(const Geom &g, const BatchDev &b, int layer, const void *k_new, const void *v_new,
+                                int n_blocks, const Launch &L);
+hipError_t launch_attn_pp_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L);
 hipError_t launch_decode_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L);
 hipError_t launch_decode_finish(const Geom &g, const BatchDev &b, const AttnArgs &a, int max_splits, const Launch &L);
 hipError_t launch_attn_f32(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L);

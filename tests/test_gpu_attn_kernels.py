@@ -32,7 +32,7 @@ def _errs(H, dw, bt, pl, layer):
     return res, out, qkv
 
 
-@pytest.mark.parametrize("kind", [1, 2])
+@pytest.mark.parametrize("kind", [1, 2, 4])
 @pytest.mark.parametrize("splits", [1, 3, 8])
 def test_both_kernels_c2_shape(H, kind, splits):
     """The c2 shape (P ~ 4.1k, S = 128, ragged last prefix tile, two causal suffix tiles) through

@@ -26,7 +26,7 @@ def _draw(seed, *key, shape):
     return W.f32_to_bf16_bits(rng.standard_normal(size=shape, dtype=np.float32))
 
 
-@pytest.mark.parametrize("kind", [0, 1])
+@pytest.mark.parametrize("kind", [0, 1, 4])
 @pytest.mark.parametrize("splits", [0, 3])
 def test_decode_steps_after_prefill(H, splits, kind):
     cfg = W.WorkloadConfig(name="dec", n_layers=2, n_q_heads=8, n_kv_heads=2, head_dim=128, dtype="bf16", n_tables=6,
@@ -41,7 +41,8 @@ def test_decode_steps_after_prefill(H, splits, kind):
     dw = H.DeviceWorkload(wl, seq_blocks=seq_blocks)
     if splits:
         dw.ctx.tc_set_kv_splits(splits)
-    dw.ctx.tc_set_attn_kernel(kind)                    # 0: the decode kernels serve the steps; 1: the prefill kernel does
+    dw.ctx.tc_set_attn_kernel(kind)                    # 0: the decode kernels serve the steps; 1, 4: a prefill kernel does
+                                                       # (4 appends by blocks in a launch of its own: the pool check below covers it)
     max_blocks = int(max(-(-(p + s + T) // 16) for p, s in zip(P, S))) + 1
     bt, pl = dw.stitch(max_blocks=max_blocks)
     # prefill: both layers (appends the prompt's own suffix to the pool)
@@ -78,7 +79,7 @@ def test_decode_steps_after_prefill(H, splits, kind):
             out = torch.full_like(dq, float("nan"))
             dw.ctx.tc_prefill_attn(layer, dq, dk, dv, out, cu1, bt, cur, one, wl.sm_scale, None)
             torch.cuda.synchronize()
-            assert dw.ctx.tc_attn_kernel() == (3 if kind == 0 else 1)
+            assert dw.ctx.tc_attn_kernel() == (3 if kind == 0 else kind)
             got = H.out_to_f64(out, c)
             for i in range(c.batch):
                 K, V = seq[layer, i]

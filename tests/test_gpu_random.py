@@ -1,7 +1,7 @@
 """GPU: randomly drawn batches through every way the library can serve them.  Each case draws a
 head configuration (1..4 KV heads, 1..8 query heads per KV head), 2..8 tables of a few to a few
 hundred tokens, 1..5 queries with 0..5 tables and 0..200 suffix tokens each, the stitch (copying
-or in place), the attention kernel (automatic, general, pipelined) and the number of key
+or in place), the attention kernel (automatic, general, pipelined, alternating wave groups) and the number of key
 partitions; runs one prefill layer twice (the two launches must agree bit for bit), checks it
 against the CPU checker, then grows every sequence by one token and checks a decode step (decode
 kernels or the prefill kernel).  Tolerance: 1e-2 max-abs, scaled by the largest reference value of
@@ -36,7 +36,7 @@ def _case(H, seed):
                            choice="uniform", suffix_len=(0, int(rng.choice([1, 17, 90, 200]))), capacity=nt,
                            seed=1000 + seed)
     wl = W.make_workload(cfg)
-    alias, kind = bool(rng.integers(0, 2)), int(rng.choice([0, 1, 2]))
+    alias, kind = bool(rng.integers(0, 2)), int(rng.choice([0, 1, 2, 4]))
     splits = int(rng.choice([0, 0, 1, 2, 3, 5]))
     S = wl.suffix_len.astype(int)
     P = np.array([int(wl.table_len[q].sum()) for q in wl.queries])
