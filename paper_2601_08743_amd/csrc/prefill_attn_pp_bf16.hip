@@ -102,7 +102,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
             load_to_lds(kd + i * 1024, src, rb * 256 + (((lane & 15) ^ rb) * 16));
         }
 #pragma unroll
-        for (int i = i0; i < i0 + 2; ++i) load_to_lds(vd + i * 1024, src + v_half + i * 1024, lane * 16);
+        for (int i = i0; i < i0 + 2; ++i)               // V chunks in operand order (see v_off)
+            load_to_lds(vd + i * 1024, src + v_half + i * 1024, (2 * (lane & 31) + (lane >> 5)) * 16);
     };
     if (0 < n) issue_tile(0);
     if (1 < n) issue_tile(1);
@@ -110,6 +111,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
     // ---- state
     f32x16 o[4], sacc[2];         // sacc: scores of the tile between its M and V phase
     bf16x8 pf[4];                 // weights of the tile between its V phase and the next M phase (always written first)
+    bf16x8 vpre[2];               // first V fragments of that M phase
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -118,7 +120,10 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
     const float c = a.scale_log2;
     typedef const __attribute__((address_space(3))) bf16x8 *lds_frag;
     const uint32_t k_off = r32 * 256 + ((hh ^ (r32 & 15)) << 4);
-    const uint32_t v_off = kPpV + r32 * 32 + hh * 16;
+    // V: within each 1 KB (32 d-rows of 32 bytes) the loads fetch token half 0 of all rows, then half 1,
+    // so that lane (row r32, half hh) reads position r32 + 32 hh = its lane number: 16 consecutive lanes
+    // read 256 consecutive bytes (at the rows' own 32-byte pitch they would hit half the banks twice)
+    const uint32_t v_off = kPpV + lane * 16;
 
     // M(t): PV(t-1) first - it uses up the weights, whose registers the new scores can then take -
     // then QK(t); operand fragments run two reads ahead of their matrix instructions
@@ -128,8 +133,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
         if (do_pv) {
             bf16x8 vf[3];
 #define TC_VF(j) (*(lds_frag)(uintptr_t)(vb + ((j) >> 2) * 4096 + ((j) & 3) * 1024))
-            vf[0] = TC_VF(0);
-            vf[1] = TC_VF(1);
+            vf[0] = vpre[0];                           // read at the end of the softmax phase before
+            vf[1] = vpre[1];
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 if (j + 2 < 16) vf[(j + 2) % 3] = TC_VF(j + 2);
@@ -201,6 +206,11 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
         for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
             for (int e = 0; e < 8; ++e) pf[kk][e] = (__bf16)sacc[kk >> 1][8 * (kk & 1) + e];
+        // the next matrix phase starts with PV of this tile: its first two V fragments are fetched now,
+        // so that its first matrix instruction does not wait for an LDS round trip
+        const uint32_t vb = lds0 + (t % kPpVBufs) * kPpTile + v_off;
+        vpre[0] = *(lds_frag)(uintptr_t)(vb);
+        vpre[1] = *(lds_frag)(uintptr_t)(vb + 1024);
     };
     // the wave's own part of tile t must have landed before the barrier that lets the first wave
     // read it; the tile issued after it may still be in flight
