@@ -249,7 +249,7 @@ def test_repeated_launches_are_bit_identical(H, heads):
     wl = _one_table_per_query(P, S, seed=777)
     wl = W.Workload(W.scaled(wl.cfg, n_q_heads=Hq, n_kv_heads=Hkv), wl.table_len, wl.queries, wl.suffix_len)
     q, k, v = wl.suffix_qkv(0)
-    for kind in (2, 1):
+    for kind in (2, 1, 4):
         dw = H.DeviceWorkload(wl)
         dw.ctx.tc_set_attn_kernel(kind)
         dw.ctx.tc_set_kv_splits(1)
