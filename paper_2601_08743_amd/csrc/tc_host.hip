@@ -273,8 +273,8 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
     // Decode step: every query brings at most one new token, so a KV head has only G rows and the
     // work is reading K and V once.  The decode kernels split the keys of a (query, KV head) over
     // the four waves of a work-group and over `ns` work-groups: enough of them to cover the chip,
-    // but at least eight key tiles each (two per wave).  Sequences that alias table slots carry
-    // unused block tails, which these kernels do not mask: they keep to the prefill kernels.
+    // but at least six key tiles each.  Unused block tails of sequences that alias table slots ride
+    // in the device block table and are masked by the kernel.
     if (bf16 && G <= 32 && p.total_S > 0 && ctx->forced_row_blocks == 0 &&
         (ctx->forced_attn_kernel == 0 || ctx->forced_attn_kernel == 3) &&
         std::all_of(p.suffix_len.begin(), p.suffix_len.end(), [](int32_t s) { return s <= 1; })) {

@@ -68,7 +68,7 @@ struct BatchDev {
 
 // One unit of attention work: a tile of rows of one (query, KV head) against a range of key tiles.
 // Everything the work-group needs to start loading is in the item itself (one scalar fetch):
-// the query's lengths and the block ids of its first two key tiles.
+// the query's lengths and the block-table entries of its first four key tiles.
 struct AttnItem {
     int32_t q;           // query index, -1 = padding item
     int32_t kvh;
