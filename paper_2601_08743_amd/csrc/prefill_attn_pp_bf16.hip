@@ -40,6 +40,7 @@ constexpr int kPpKBufs = 3, kPpVBufs = 4;
 constexpr int kPpV = kPpKBufs * kPpTile;             // V ring behind the K ring
 constexpr int kPpBid = kPpV + kPpVBufs * kPpTile;    // block-table entries of the item's key range
 constexpr int kPpLds = kPpBid + kAttnMaxTiles * 4 * 4 + 256;   // + slack to align the rings to 256 B
+constexpr int kPpRing = 5;                           // operand fragments in flight: reads run kPpRing - 1 matrix instructions ahead
 constexpr float kPpRescale = 8.f;                    // log2 units: rescale O only when the maximum grew by more
 
 __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b, AttnArgs a)
@@ -126,19 +127,24 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
     const uint32_t v_off = kPpV + lane * 16;
 
     // M(t): PV(t-1) first - it uses up the weights, whose registers the new scores can then take -
-    // then QK(t); operand fragments run two reads ahead of their matrix instructions
+    // then QK(t); operand fragments are read kPpRing - 1 matrix instructions ahead (an LDS round trip
+    // is longer than two of them)
     auto m_phase = [&](int t, bool do_qk, bool do_pv) {
         const uint32_t kb = lds0 + (t % kPpKBufs) * kPpTile + k_off;
         const uint32_t vb = lds0 + ((t + kPpVBufs - 1) % kPpVBufs) * kPpTile + v_off;
         if (do_pv) {
-            bf16x8 vf[3];
+            bf16x8 vf[kPpRing];
 #define TC_VF(j) (*(lds_frag)(uintptr_t)(vb + ((j) >> 2) * 4096 + ((j) & 3) * 1024))
             vf[0] = vpre[0];                           // read at the end of the softmax phase before
             vf[1] = vpre[1];
 #pragma unroll
+            for (int j = 2; j < kPpRing - 1; ++j) vf[j] = TC_VF(j);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
             for (int j = 0; j < 16; ++j) {
-                if (j + 2 < 16) vf[(j + 2) % 3] = TC_VF(j + 2);
-                o[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j % 3], pf[j >> 2], o[j & 3], 0, 0, 0);
+                if (j + kPpRing - 1 < 16) vf[(j + kPpRing - 1) % kPpRing] = TC_VF(j + kPpRing - 1);
+                o[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j % kPpRing], pf[j >> 2], o[j & 3], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);     // keep the reads where they are: ahead (the scheduler pulls them back to their use)
             }
 #undef TC_VF
         }
@@ -147,14 +153,16 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) sacc[mb][e] = 0.f;
-            bf16x8 kf[3];
+            bf16x8 kf[kPpRing];
 #define TC_KF(j) (*(lds_frag)(uintptr_t)((kb ^ (((j) >> 1) << 5)) + ((j) & 1) * 32 * 256))
-            kf[0] = TC_KF(0);
-            kf[1] = TC_KF(1);
+#pragma unroll
+            for (int j = 0; j < kPpRing - 1; ++j) kf[j] = TC_KF(j);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
-                if (j + 2 < 16) kf[(j + 2) % 3] = TC_KF(j + 2);
-                sacc[j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j % 3], qf[j >> 1], sacc[j & 1], 0, 0, 0);
+                if (j + kPpRing - 1 < 16) kf[(j + kPpRing - 1) % kPpRing] = TC_KF(j + kPpRing - 1);
+                sacc[j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j % kPpRing], qf[j >> 1], sacc[j & 1], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
 #undef TC_KF
         }
