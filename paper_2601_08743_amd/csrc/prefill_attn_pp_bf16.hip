@@ -39,7 +39,7 @@ constexpr int kPpTile = kAttnKeys * 256;             // 16 KB: a K tile (64 rows
 constexpr int kPpKBufs = 3, kPpVBufs = 4;
 constexpr int kPpV = kPpKBufs * kPpTile;             // V ring behind the K ring
 constexpr int kPpBid = kPpV + kPpVBufs * kPpTile;    // block-table entries of the item's key range
-constexpr int kPpLds = kPpBid + kAttnMaxTiles * 4 * 4 + 256;   // + slack to align the rings to 256 B
+constexpr int kPpLds = kPpBid + kPpMaxTiles * 4 * 4 + 256;   // + slack to align the rings to 256 B
 constexpr int kPpRing = 5;                           // operand fragments in flight: reads run kPpRing - 1 matrix instructions ahead
 constexpr float kPpRescale = 8.f;                    // log2 units: rescale O only when the maximum grew by more
 

@@ -370,7 +370,8 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
             const double load = std::ceil((double)n_q * c.n_kv_heads * ns / 8.0) * items_per_bucket / 32.0;
             const double per_cu = load <= 1.0 ? 1.0 : (load <= 2.0 ? 2.0 : load);
             const double merge = ns > 1 ? 1.0 + 0.93e-4 * ns * rows : 0.0;   // fp16 partials: 264 B per row and partition
-            const double cost = per_cu * (tiles / ns) * (per_cu >= 2.0 ? 0.7 : 1.0) + 3.0 + merge;
+            // (two work-groups on a CU overlap each other's stalls; the long-launch kernel runs one per CU)
+            const double cost = per_cu * (tiles / ns) * (per_cu >= 2.0 && !pp ? 0.7 : 1.0) + 3.0 + merge;
             if (cost < best - 1e-9) { best = cost; want = ns; }
         }
     }
@@ -386,7 +387,10 @@ void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
         const int last_blk = std::max(0, (unified ? (P + S + kBlockTokens - 1) / kBlockTokens
                                                   : (P + kBlockTokens - 1) / kBlockTokens) - 1);
         int ns = std::min(want, ctx->forced_splits > 0 ? n_tiles : std::max(1, n_tiles / 2));
-        if (bf16) ns = std::max(ns, (n_tiles + kAttnMaxTiles - 1) / kAttnMaxTiles);   // block ids of a range fit LDS
+        if (bf16) {                                      // block ids of a range fit LDS
+            const int cap = pp ? kPpMaxTiles : kAttnMaxTiles;
+            ns = std::max(ns, (n_tiles + cap - 1) / cap);
+        }
         ns = std::max(1, std::min(ns, n_tiles));
         splits_of_q[i] = ns;
         p.max_splits = std::max(p.max_splits, ns);

@@ -11,6 +11,7 @@ constexpr int kBlockTokens = 16;     // tokens per pool block
 constexpr int kAttnRows = 128;       // bf16 kernel: rows (suffix token x group head) per work-group and row block
 constexpr int kAttnKeys = 64;        // bf16 kernel: keys per tile (4 pool blocks)
 constexpr int kAttnMaxTiles = 256;   // bf16 kernel: key tiles per work item (block ids kept in LDS)
+constexpr int kPpMaxTiles = 1024;    // the same for the long-launch kernel, which has the LDS to spare
 constexpr int kF32Rows = 4;          // fp32 kernel: rows per work-group (one per wave)
 constexpr int kF32Keys = 64;         // fp32 kernel: keys per tile
 
