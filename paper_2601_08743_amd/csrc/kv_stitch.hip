@@ -63,17 +63,30 @@ __device__ __forceinline__ int64_t v_plain_offset(const Geom &g, int c)
 }
 
 // second half of the transposing path: out chunk oc = (h, d, half): 8 tokens of one (h, d)
-// t_first > 0: tokens below t_first keep what the block already holds (read, merged, written back)
-__device__ __forceinline__ void store_v_transposed(const Geom &g, const uint4 *lds, char *vdst, int tid, int t_first = 0)
+// t_first > 0: tokens below t_first keep what the block already holds: `old` brings the block's
+// chunks (chunk tid + 256 k in old[k]), read by the caller before anything else so that the read is
+// not one more round trip at the end; they are merged and written back.
+constexpr int kOldChunks = 8;                  // covers Hkv * D * 2 <= 2048 chunks; beyond that the chunk is read here
+__device__ __forceinline__ void store_v_transposed(const Geom &g, const uint4 *lds, char *vdst, int tid, int t_first = 0,
+                                                   const uint4 *old_pre = nullptr)
 {
     const unsigned short *l16 = (const unsigned short *)lds;
     const int row_elems = g.row_bytes >> 1;
     const int n_out = g.Hkv * g.D * 2;
-    for (int oc = tid; oc < n_out; oc += 256) {
+    for (int k = 0; tid + 256 * k < n_out; ++k) {
+        const int oc = tid + 256 * k;
         const int half = oc & 1;
         const int hd = oc >> 1;                // h * D + d
         uint4 old = make_uint4(0, 0, 0, 0);
-        if (t_first > 0) old = *(const uint4 *)(vdst + ((int64_t)oc << 4));
+        if (t_first > 0) {
+            if (old_pre && k < kOldChunks) {
+                // (selected, not indexed, so that the array stays in registers)
+#pragma unroll
+                for (int q = 0; q < kOldChunks; ++q) if (q == k) old = old_pre[q];
+            } else {
+                old = *(const uint4 *)(vdst + ((int64_t)oc << 4));
+            }
+        }
         const unsigned o32[4] = {old.x, old.y, old.z, old.w};
         unsigned short e[8];
 #pragma unroll
@@ -123,6 +136,13 @@ __device__ __forceinline__ void copy_block_kv(const Geom &g, const char *k_src, 
 {
     const int n_chunks = kBlockTokens * (g.row_bytes >> 4);
     const int cpr = g.row_bytes >> 4, cph = g.head_bytes >> 4;
+    uint4 old_v[kOldChunks];
+    if (kTransposeV && t_first > 0) {              // the shared block's values, on their way while the rows are fetched
+        const int n_out = g.Hkv * g.D * 2;
+#pragma unroll
+        for (int k = 0; k < kOldChunks; ++k)
+            old_v[k] = *(const uint4 *)(vdst + ((int64_t)min(tid + 256 * k, n_out - 1) << 4));
+    }
     for (int c0 = tid; c0 < n_chunks; c0 += 256 * kCopyBatch) {
         uint4 kk[kCopyBatch], vv[kCopyBatch];
         bool kok[kCopyBatch], vok[kCopyBatch];
@@ -146,7 +166,7 @@ __device__ __forceinline__ void copy_block_kv(const Geom &g, const char *k_src, 
     }
     if (kTransposeV) {
         __syncthreads();
-        store_v_transposed(g, lds, vdst, tid, t_first);
+        store_v_transposed(g, lds, vdst, tid, t_first, old_v);
     }
 }
 
