@@ -149,10 +149,9 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
 #undef TC_VF
         }
         if (do_qk) {
+            f32x16 zero;                               // the first product of each half starts from the constant 0
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) sacc[mb][e] = 0.f;
+            for (int e = 0; e < 16; ++e) zero[e] = 0.f;
             bf16x8 kf[kPpRing];
 #define TC_KF(j) (*(lds_frag)(uintptr_t)((kb ^ (((j) >> 1) << 5)) + ((j) & 1) * 32 * 256))
 #pragma unroll
@@ -161,7 +160,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 if (j + kPpRing - 1 < 16) kf[(j + kPpRing - 1) % kPpRing] = TC_KF(j + kPpRing - 1);
-                sacc[j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j % kPpRing], qf[j >> 1], sacc[j & 1], 0, 0, 0);
+                sacc[j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j % kPpRing], qf[j >> 1], j < 2 ? zero : sacc[j & 1], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
 #undef TC_KF
@@ -230,24 +229,25 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
     // ---- intervals (barrier to barrier).  Group A does M(t) in interval 2t and V(t) in 2t+1, group B
     // one interval later: both run the same loop, B behind one extra barrier at the start and A
     // through one at the end.  Tile t is first read in interval 2t (A's M(t)): A's waves make sure of
-    // their part at the end of their V(t-1), B's at the end of their M(t-1).  A tile's buffers were
-    // last read in interval 2t-3, so it may be requested from interval 2t-4+... = top of iteration t-2.
+    // their part at the end of their V(t-1), B's at the end of their M(t-1).  Tile t+2 is requested at
+    // the start of a wave's V(t) (A: interval 2t+1, B: 2t+2); the buffers it goes to were last read in
+    // interval 2t-1.
     if (n > 0) {
         wait_tile(0);
         __syncthreads();                               // tile 0 visible
         if (grp) __syncthreads();
-        if (2 < n) issue_tile(2);
         m_phase(0, true, false);
-        if (grp) wait_tile(1);
+        if (grp) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // tile 1 (B has requested nothing younger)
         __syncthreads();
+        if (2 < n) issue_tile(2);
         v_phase(0);
         if (!grp) wait_tile(1);
         __syncthreads();
         for (int t = 1; t < n; ++t) {
-            if (t + 2 < n) issue_tile(t + 2);
             m_phase(t, true, true);
-            if (grp) wait_tile(t + 1);
+            if (grp) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // tile t+1
             __syncthreads();
+            if (t + 2 < n) issue_tile(t + 2);          // in the softmax phase, which has the time to spare
             v_phase(t);
             if (!grp) wait_tile(t + 1);
             __syncthreads();
