@@ -103,10 +103,13 @@ def test_c3_full_batch(H):
     dw.close()
 
 
-@pytest.mark.parametrize("row_blocks", [1, 2])
+@pytest.mark.parametrize("row_blocks", [0, 1, 2])
 def test_c4_long_prefix(H, row_blocks):
-    """c4's per-layer shape (60 tables, P = 24.6k, S = 512, B = 4, 32q/8kv) on 2 of its 32 layers:
-    the long-prefix split-KV path, with both work-group shapes."""
+    """c4's per-layer shape (60 tables, P = 24.6k, S = 512, B = 4, 32q/8kv) on 2 of its 32 layers.
+    row_blocks 0 is the configuration the bench times: the automatic choice, which is the
+    long-launch kernel with the whole key range (392 tiles) in one work item and the suffix appended
+    by blocks first - the pool is therefore also read back behind the attention launch.  1 and 2
+    force the other kernels' work-group shapes: the long-prefix split-KV path."""
     wl = W.make_workload(W.scaled(W.CONFIGS["c4"], n_layers=2))
     dw = H.DeviceWorkload(wl)
     dw.ctx.tc_set_row_blocks(row_blocks)
@@ -116,8 +119,19 @@ def test_c4_long_prefix(H, row_blocks):
     rng = np.random.default_rng(2)
     out, qkv = dw.attn_layer(1, bt, pl)
     e, rel = _sample_rows(H, dw, bt, pl, 1, out, qkv, [0, 3], 3, rng)
-    print("c4 shape rb=%d: splits %d, sampled max-abs %.3e rel %.3e" % (row_blocks, dw.ctx.tc_kv_splits(), e, rel))
-    assert dw.ctx.tc_kv_splits() >= 2            # the block ids of a work item's key range must fit LDS
+    print("c4 shape rb=%d: kernel %d, splits %d, sampled max-abs %.3e rel %.3e" % (
+        row_blocks, dw.ctx.tc_attn_kernel(), dw.ctx.tc_kv_splits(), e, rel))
+    if row_blocks == 0:
+        assert dw.ctx.tc_attn_kernel() == 4 and dw.ctx.tc_kv_splits() == 1
+        for i in (0, 3):                          # prefix untouched by the append, suffix where it belongs
+            P, S = int(pl[i]), int(wl.suffix_len[i])
+            kk, vv = dw.ctx.tc_read_seq_kv(1, bt[i, :-(-(P + S) // 16)], P + S, np.uint16)
+            ks, vs = H.oracle_sequences(wl, dw.tables_np, 1, i)
+            sl = slice(int(wl.cu_seqlens[i]), int(wl.cu_seqlens[i + 1]))
+            np.testing.assert_array_equal(kk.view(np.uint8), np.concatenate([ks, qkv[1][sl]]).view(np.uint8))
+            np.testing.assert_array_equal(vv.view(np.uint8), np.concatenate([vs, qkv[2][sl]]).view(np.uint8))
+    else:
+        assert dw.ctx.tc_kv_splits() >= 2        # the block ids of a work item's key range must fit LDS
     assert e <= 1e-2 and rel <= 0.06
     dw.close()
 
