@@ -342,7 +342,6 @@ int32_t tc_trie_match(const tc_trie *trie, const int32_t *s, int32_t len, int32_
 tc_status tc_rerank(const int32_t *table_ids, const int32_t *cu_tables, int32_t n_queries, int32_t n_tables,
                     int32_t anchor, int32_t *order_out);
 
-/* Text for the most recent error on this context; library-owned, valid until the next call. */
 /*
  * Computation-loading pipeline schedule (Sec. 4.2.2): the ordered requests are computed
  * in micro-batches of b_c while the tables of up to the next b_m requests are copied in.
@@ -378,6 +377,7 @@ int32_t tc_plan_pipeline(const int32_t *table_ids, const int32_t *cu_tables, int
                          int32_t capacity, int32_t b_c, int32_t b_m, int32_t keep_pinned, int32_t taper,
                          tc_pipe_step *steps_out, int32_t cap);
 
+/* Text for the most recent error on this context; library-owned, valid until the next call. */
 const char *tc_last_error(const tc_ctx *ctx);
 /* Library version string. */
 const char *tc_version(void);

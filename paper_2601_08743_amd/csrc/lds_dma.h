@@ -9,7 +9,10 @@ namespace tc {
 // 16 bytes per lane from (uniform base + per-lane offset) to LDS at lds_dst + 16 * lane.  The
 // instruction takes its LDS address from M0 and its base from a scalar register pair; both are
 // made uniform explicitly.  Completion is counted in vmcnt like any vector load; the compiler does
-// not know about these loads, so the waits (s_waitcnt vmcnt) are the caller's.
+// not know about these loads, so the waits (s_waitcnt vmcnt) are the caller's.  M0 cannot be
+// named as clobbered (the compiler reserves it and warns that such a clobber is undefined); what
+// must hold instead - that the compiler itself never keeps a value in M0 in a kernel that uses these
+// loads - is checked on the emitted assembly by tests/test_kernel_schedule.py.
 __device__ __forceinline__ void load_to_lds(uint32_t lds_dst, const char *base, uint32_t voff)
 {
     const uint64_t b64 = (uint64_t)(uintptr_t)base;

@@ -522,8 +522,8 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_bf16_kernel(Geom g,
 constexpr int kFastKTile = kAttnKeys * 256;               // 16 KB, swizzled rows
 constexpr int kFastBufs = 4;
 constexpr int kFastV = kFastBufs * kFastKTile;            // V buffers follow the K buffers
-constexpr int kFastBid = kFastV + kFastBufs * kVTile;     // block ids of the item's key range
-constexpr int kLdsBytesPipe = kFastBid + kBidBytes;
+constexpr int kFastBid = kFastV + kFastBufs * kVTile;     // block ids of the item's key range (up to kPipeMaxTiles tiles)
+constexpr int kLdsBytesPipe = kFastBid + kPipeMaxTiles * 4 * 4;
 static_assert(kLdsBytesPipe <= 160 * 1024 && 2 * kStage <= kFastBid, "LDS layout");
 // Shorter runs take the general loop.  Runs of exactly three tiles are excluded on evidence, not
 // on a found cause: on some machines their first launches in a process returned wrong rows

@@ -2,6 +2,7 @@
 // device table cache with its replacement rules (paper App. A), the sequence-block allocator,
 // per-batch planning (stitch descriptors, attention work list, split-KV) and kernel launches.
 #include "../../include/tablecache.h"
+#include "host_logic.h"
 #include "tc_internal.h"
 
 #include <algorithm>
@@ -13,6 +14,7 @@
 #include <list>
 #include <map>
 #include <memory>
+#include <mutex>
 #include <set>
 #include <string>
 #include <unordered_map>
@@ -21,78 +23,6 @@
 using namespace tc;
 
 namespace {
-
-// ------------------------------------------------------------------ replacement rules (App. A)
-// Each rule answers three questions about the set of cached tables: is the request cached,
-// what happens on a hit, and who goes when a miss finds the cache full.  Tables a caller has
-// pinned are passed over: the victim is the rule's first choice among the others (-1: none left).
-using PinMap = std::unordered_map<int32_t, int32_t>;
-
-class Replacement {
-public:
-    virtual ~Replacement() {}
-    virtual bool cached(int32_t id) const = 0;
-    virtual void on_hit(int32_t id) = 0;
-    virtual int32_t pick_victim(const PinMap &pins) const = 0;
-    virtual void remove(int32_t id) = 0;
-    virtual void insert(int32_t id) = 0;
-    virtual size_t size() const = 0;
-    virtual void tick() {}                         // called once per request, before anything else
-};
-
-// LRU: recency list, most recent at the front; the end is evicted.
-class LruRule : public Replacement {
-    std::list<int32_t> order_;
-    std::unordered_map<int32_t, std::list<int32_t>::iterator> pos_;
-public:
-    bool cached(int32_t id) const override { return pos_.count(id) != 0; }
-    void on_hit(int32_t id) override { order_.splice(order_.begin(), order_, pos_[id]); }
-    int32_t pick_victim(const PinMap &pins) const override {
-        for (auto it = order_.rbegin(); it != order_.rend(); ++it) if (!pins.count(*it)) return *it;
-        return -1;
-    }
-    void remove(int32_t id) override { order_.erase(pos_[id]); pos_.erase(id); }
-    void insert(int32_t id) override { order_.push_front(id); pos_[id] = order_.begin(); }
-    size_t size() const override { return pos_.size(); }
-};
-
-// FIFO: a queue; hits leave it alone; the head is evicted, arrivals join the tail.
-class FifoRule : public Replacement {
-    std::list<int32_t> queue_;
-    std::unordered_map<int32_t, std::list<int32_t>::iterator> pos_;
-public:
-    bool cached(int32_t id) const override { return pos_.count(id) != 0; }
-    void on_hit(int32_t) override {}
-    int32_t pick_victim(const PinMap &pins) const override {
-        for (int32_t id : queue_) if (!pins.count(id)) return id;
-        return -1;
-    }
-    void remove(int32_t id) override { queue_.erase(pos_[id]); pos_.erase(id); }
-    void insert(int32_t id) override { queue_.push_back(id); pos_[id] = std::prev(queue_.end()); }
-    size_t size() const override { return pos_.size(); }
-};
-
-// LFU: (frequency, timestamp) per table; smallest frequency goes, ties by smallest timestamp.
-class LfuRule : public Replacement {
-    struct Stat { int64_t freq, stamp; };
-    std::unordered_map<int32_t, Stat> stat_;
-    int64_t clock_ = 0;
-public:
-    void tick() override { ++clock_; }
-    bool cached(int32_t id) const override { return stat_.count(id) != 0; }
-    void on_hit(int32_t id) override { Stat &s = stat_[id]; s.freq += 1; s.stamp = clock_; }
-    int32_t pick_victim(const PinMap &pins) const override {
-        int32_t best = -1; Stat bs{0, 0};
-        for (const auto &kv : stat_)
-            if (pins.count(kv.first)) continue;
-            else if (best < 0 || kv.second.freq < bs.freq ||
-                (kv.second.freq == bs.freq && kv.second.stamp < bs.stamp)) { best = kv.first; bs = kv.second; }
-        return best;
-    }
-    void remove(int32_t id) override { stat_.erase(id); }
-    void insert(int32_t id) override { stat_[id] = Stat{1, clock_}; }
-    size_t size() const override { return stat_.size(); }
-};
 
 struct Table {
     int32_t n_tokens = 0;
@@ -107,31 +37,20 @@ struct Slot {
     hipStream_t ready_stream = nullptr;
     bool ready_pending = false;        // a record exists that other streams may have to wait for
     int32_t read_ev = -1;              // index into the read-event ring, -1 = never read
+    uint32_t read_gen = 0;             // generation of that ring entry when the slot's stitch recorded it
+    hipStream_t read_stream = nullptr; // stream of that stitch
     hipStream_t reader_stream = nullptr;   // block-format slots: stream of the last attention launch that
     bool reader_pending = false;           // read the slot through an aliasing sequence, not yet ordered
 };
 
-// The integer plan of one batch, host copy and layout of the device copy.
-struct Plan {
-    bool valid = false;
-    int32_t B = 0, max_blocks = 0, total_S = 0, n_stitch_blk = 0, n_items = 0, max_splits = 1, n_groups = 0, row_blocks = 1;
-    bool pipelined = false;     // bf16, one row block per wave: the pipelined attention kernel
-    bool decode = false;        // bf16, at most one new token per query: the decode kernels
-    bool pingpong = false;      // bf16, 256 rows per work-group in two alternating wave groups; the suffix is appended first
-    bool rope = false;          // the stitch re-encodes keys by position (Sec. 4.1.1)
-    std::vector<int32_t> rope_pos0;      // [B]
-    std::vector<double> rope_rev_freq;   // [D/2]
-    std::vector<int32_t> block_table, cu_seqlens, prefix_len, suffix_len;
-    std::vector<uint8_t> block_pad;      // aliasing sequences: unused token positions per block-table entry, else empty
-    std::vector<int32_t> alias_slots;    // table slots whose blocks the batch's sequences alias
-    BatchDev dev{};
-    const AttnItem *items_dev = nullptr;
-    const MergeGroup *groups_dev = nullptr;
-};
-
 inline size_t align8(size_t n) { return (n + 7) & ~size_t(7); }
 
+// Capacity of a fixed workspace for plans and split-KV partials (callers that cannot allocate).
+constexpr size_t kScratchPlanInts = size_t(1) << 20;
+constexpr size_t kScratchPartFloats = size_t(15) << 20;
+
 }  // namespace
+
 
 struct tc_ctx {
     tc_config cfg{};
@@ -143,10 +62,10 @@ struct tc_ctx {
     PinMap pins;                           // table -> pin count (> 0)
     std::vector<Slot> slots;
     std::set<int32_t> free_slots;
-    std::set<int32_t> free_seq;            // free sequence blocks, ordered
-    std::vector<uint8_t> seq_used;         // by block id - first_seq
+    SeqBlocks seq;                         // sequence blocks [first_seq, n_pool_blocks)
     std::vector<int32_t> trace;            // (table, hit, evicted) triples
     std::vector<hipEvent_t> read_ring;     // events recorded after stitch kernels
+    std::vector<uint32_t> read_gen;        // how often each ring entry has been recorded
     int32_t read_next = 0;
     hipEvent_t raw_ev = nullptr;           // block-format slots: the raw staging area was last used up to here,
     hipStream_t raw_stream = nullptr;      // on this stream
@@ -156,9 +75,10 @@ struct tc_ctx {
     int32_t *d_plan = nullptr; size_t d_plan_ints = 0;
     hipEvent_t stage_ev = nullptr; bool stage_pending = false;
     float *d_part = nullptr; size_t d_part_floats = 0;
-    int32_t forced_splits = 0;
-    int32_t forced_row_blocks = 0;
-    int32_t forced_attn_kernel = 0;   // 0 automatic, 1 general, 2 pipelined, 3 decode (where it applies)
+    int device = 0;                        // the device the context was created on
+    char *scratch_dev = nullptr;           // that device's copy of the static workspace (tc_prefill_attn_noalloc)
+    char *d_read = nullptr; size_t d_read_bytes = 0;   // tc_read_seq_kv's staging, grown on demand
+    PlanKnobs knobs;                       // tc_set_kv_splits / tc_set_row_blocks / tc_set_attn_kernel
     // per-kernel timing (tc_profile_*): pairs of events around launches, drained on read
     bool profiling = false;
     struct Timed { int kind; hipEvent_t a, b; };
@@ -197,6 +117,32 @@ hipEvent_t take_event(tc_ctx *ctx)
     return e;
 }
 
+// Record the next event of the read ring on `stream`; returns its index (-1 on error).
+int32_t record_read(tc_ctx *ctx, hipStream_t stream)
+{
+    const int32_t ev = ctx->read_next;
+    if (hipEventRecord(ctx->read_ring[ev], stream) != hipSuccess) return -1;
+    ctx->read_next = (ctx->read_next + 1) % (int32_t)ctx->read_ring.size();
+    ++ctx->read_gen[ev];
+    return ev;
+}
+
+// Make `stream` wait for the last stitch that read slot `s`.  The ring entry the slot remembers may
+// have been recorded again since (64 stitches later, possibly on another stream): then it no longer
+// stands for that stitch, and a fresh event on the stitch's own stream - which covers everything
+// enqueued there so far - takes its place.
+hipError_t wait_for_reader(tc_ctx *ctx, Slot &s, hipStream_t stream)
+{
+    if (s.read_ev < 0) return hipSuccess;
+    int32_t ev = s.read_ev;
+    if (ctx->read_gen[ev] != s.read_gen) {
+        ev = record_read(ctx, s.read_stream);
+        if (ev < 0) return hipErrorUnknown;
+    }
+    s.read_ev = -1;
+    return hipStreamWaitEvent(stream, ctx->read_ring[ev], 0);
+}
+
 // Run `launch` on `stream`; with profiling on, give it two events that receive the dispatch's
 // begin and end timestamps.
 template <typename F>
@@ -232,11 +178,20 @@ bool config_ok(const tc_config *c)
 
 int esize_of(const tc_config &c) { return c.dtype == TC_F32 ? 4 : 2; }
 
-tc_status ensure_stage(tc_ctx *ctx, size_t ints)
+// Make room for a plan of `ints` integers: the pinned staging buffer on the host and, unless the
+// plan goes to the static workspace (`fixed`), the device buffer.  The staging buffer is created
+// by tc_create with the static workspace's plan capacity, so a fixed plan never allocates.
+tc_status ensure_stage(tc_ctx *ctx, size_t ints, bool fixed)
 {
     if (ctx->stage_pending) {                       // the previous upload still reads the staging buffer
         TC_HIP(ctx, hipEventSynchronize(ctx->stage_ev));
         ctx->stage_pending = false;
+    }
+    if (fixed) {
+        if (ints > kScratchPlanInts || ints > ctx->h_stage_ints)
+            return fail(ctx, TC_ERR_CAPACITY, "attn (no allocation): the batch's plan needs %zu integers, the fixed workspace holds %zu",
+                        ints, std::min(kScratchPlanInts, ctx->h_stage_ints));
+        return TC_OK;
     }
     if (ints > ctx->h_stage_ints) {
         if (ctx->h_stage) TC_HIP(ctx, hipHostFree(ctx->h_stage));
@@ -257,236 +212,18 @@ tc_status ensure_stage(tc_ctx *ctx, size_t ints)
 
 struct SegInfo { int32_t start, len, slot; };
 
-// Attention work list for the batch in `p` (host arrays filled in).  Items of one
-// (query, KV head, split) read the same K/V; they are given work-group ids that are congruent
-// modulo 8 so that they land on the same XCD and share its L2 (work-groups go to the 8 XCDs
-// round-robin by id).  Holes are padded with no-op items (q = -1).
-void plan_attention(const tc_ctx *ctx, Plan &p, std::vector<AttnItem> &items,
-                    std::vector<int32_t> &splits_of_q, std::vector<MergeGroup> &groups)
-{
-    const tc_config &c = ctx->cfg;
-    const int G = c.n_q_heads / c.n_kv_heads;
-    const bool bf16 = c.dtype == TC_BF16;
-    const int KT = bf16 ? kAttnKeys : kF32Keys;
-    p.decode = false;
-    p.pingpong = false;
-    // Decode step: every query brings at most one new token, so a KV head has only G rows and the
-    // work is reading K and V once.  The decode kernels split the keys of a (query, KV head) over
-    // the four waves of a work-group and over `ns` work-groups: enough of them to cover the chip,
-    // but at least six key tiles each.  Unused block tails of sequences that alias table slots ride
-    // in the device block table and are masked by the kernel.
-    if (bf16 && G <= 32 && p.total_S > 0 && ctx->forced_row_blocks == 0 &&
-        (ctx->forced_attn_kernel == 0 || ctx->forced_attn_kernel == 3) &&
-        std::all_of(p.suffix_len.begin(), p.suffix_len.end(), [](int32_t s) { return s <= 1; })) {
-        int n_q = 0;
-        for (int i = 0; i < p.B; ++i) n_q += p.suffix_len[i] > 0 ? 1 : 0;
-        const int cap = std::max(1, (512 + n_q * c.n_kv_heads - 1) / (n_q * c.n_kv_heads));
-        splits_of_q.assign(p.B, 1);
-        p.max_splits = 1;
-        items.clear();
-        groups.clear();
-        for (int i = 0; i < p.B; ++i) {
-            if (p.suffix_len[i] <= 0) continue;
-            const int P = p.prefix_len[i];
-            const int n_tiles = (P + KT - 1) / KT;
-            int ns = ctx->forced_splits > 0 ? ctx->forced_splits : std::min(cap, std::max(1, n_tiles / 6));
-            ns = std::max(ns, (n_tiles + kAttnMaxTiles - 1) / kAttnMaxTiles);
-            ns = std::max(1, std::min(ns, std::max(n_tiles, 1)));
-            splits_of_q[i] = ns;
-            p.max_splits = std::max(p.max_splits, ns);
-            const int32_t *bt = p.block_table.data() + (size_t)i * p.max_blocks;
-            for (int h = 0; h < c.n_kv_heads; ++h)
-                for (int s = 0; s < ns; ++s) {
-                    AttnItem it{};
-                    it.q = i; it.kvh = h; it.tile_begin = (int32_t)((int64_t)n_tiles * s / ns);
-                    it.tile_end = (int32_t)((int64_t)n_tiles * (s + 1) / ns);
-                    it.split = s; it.n_splits = ns; it.P = P; it.S = 1; it.cu = p.cu_seqlens[i];
-                    for (int k = 0; k < 16; ++k) it.bid[k] = bt[0];
-                    items.push_back(it);
-                }
-        }
-        p.n_groups = 0;
-        p.row_blocks = 1;
-        p.n_items = (int32_t)items.size();
-        p.pipelined = false;
-        p.decode = true;
-        return;
-    }
-    // key tiles of a query.  bf16 kernel: the tiles of the prefix (from the pool), then the tiles of
-    // the suffix (from k_new / v_new); fp32 kernel: one paged sequence of P + S keys
-    // the alternating-groups bf16 kernel reads the suffix from the pool as well (it is appended by a
-    // launch of its own first), so it, too, sees one paged sequence
-    // It is chosen for long launches (estimated from the row tiles x key tiles of the batch at
-    // ~0.85 us per 128 x 64 tile and CU): its own append launch costs ~10 us, and with 256 rows per
-    // work-group a short launch would not fill the chip.  Measured: c3 (1140 items of ~24 tiles)
-    // 207 + 12 us against 226 us in the general kernel, c4 775 + 14 us against 814 us in the pipelined
-    // one; c2 (17 us) and the micro-batches of the loading pipeline stay with the other kernels.
-    bool pp = false;
-    if (bf16 && ctx->forced_row_blocks == 0) {
-        if (ctx->forced_attn_kernel == 4) pp = true;
-        else if (ctx->forced_attn_kernel == 0) {
-            double work = 0;
-            for (int i = 0; i < p.B; ++i)
-                if (p.suffix_len[i] > 0)
-                    work += (double)c.n_kv_heads * ((p.suffix_len[i] * G + kAttnRows - 1) / kAttnRows) *
-                            ((p.prefix_len[i] + p.suffix_len[i] + KT - 1) / KT);
-            pp = work * 0.85 / 256.0 >= 80.0;
-        }
-    }
-    const bool unified = !bf16 || pp;
-    p.pingpong = pp;
-    auto tiles_of = [&](int P, int S) {
-        return unified ? (P + S + KT - 1) / KT : (P + KT - 1) / KT + (S + KT - 1) / KT;
-    };
-    // bf16: 128 rows per work-group; 256 (two row blocks per wave, half the LDS traffic per flop but one
-    // wave per SIMD) is kept as an option: it is slower until its matrix and vector work overlap
-    const int rb = pp ? 2 : (bf16 && ctx->forced_row_blocks > 0) ? ctx->forced_row_blocks : 1;
-    p.row_blocks = rb;
-    const int RT = bf16 ? kAttnRows * rb : kF32Rows;
-    int64_t base = 0, tiles_sum = 0, n_q = 0;
-    for (int i = 0; i < p.B; ++i)
-        if (p.suffix_len[i] > 0) {
-            base += (int64_t)c.n_kv_heads * ((p.suffix_len[i] * G + RT - 1) / RT);
-            tiles_sum += tiles_of(p.prefix_len[i], p.suffix_len[i]);
-            ++n_q;
-        }
-    // Number of key partitions: a small cost model, in units of one key tile of one work-group
-    // (~1.4 us).  The work items of one (query, KV head, partition) - a bucket - go to one XCD (they
-    // share its L2), so what counts is the most loaded XCD: buckets per XCD x items per bucket over
-    // its 32 CUs gives the work-groups per CU (a whole number while the chip is not full: 35 items
-    // on an XCD mean 3 CUs run two and the launch takes as long as with 64); times the key tiles per
-    // work-group (co-resident work-groups overlap each other's stalls: x0.7); plus a fixed start-up
-    // and epilogue cost; plus the merge: a launch and the partials written and read back at about
-    // 4 TB/s.  Fitted to split-count sweeps and per-work-group traces on c2, c3 and c5-sized batches.
-    int want = 1;
-    if (ctx->forced_splits > 0) want = ctx->forced_splits;
-    else if (base > 0) {
-        const double tiles = (double)tiles_sum / (double)n_q;
-        const double items_per_bucket = (double)base / (double)(n_q * c.n_kv_heads);
-        const double rows = (double)p.total_S * c.n_q_heads;
-        double best = 1e30;
-        for (int ns = 1; ns <= 32; ++ns) {
-            if (ns > 1 && tiles / ns < 2.0) break;
-            const double load = std::ceil((double)n_q * c.n_kv_heads * ns / 8.0) * items_per_bucket / 32.0;
-            const double per_cu = load <= 1.0 ? 1.0 : (load <= 2.0 ? 2.0 : load);
-            const double merge = ns > 1 ? 1.0 + 0.93e-4 * ns * rows : 0.0;   // fp16 partials: 264 B per row and partition
-            // (two work-groups on a CU overlap each other's stalls; the long-launch kernel runs one per CU)
-            const double cost = per_cu * (tiles / ns) * (per_cu >= 2.0 && !pp ? 0.7 : 1.0) + 3.0 + merge;
-            if (cost < best - 1e-9) { best = cost; want = ns; }
-        }
-    }
-    splits_of_q.assign(p.B, 1);
-    p.max_splits = 1;
-    std::vector<std::vector<AttnItem>> buckets;     // items of one (query, KV head, partition)
-    int n_groups = 0;
-    for (int i = 0; i < p.B; ++i) {
-        const int S = p.suffix_len[i], P = p.prefix_len[i];
-        if (S <= 0) continue;
-        const int n_tiles = tiles_of(P, S);
-        // last block a tile load may touch: bf16 reads only prefix blocks from the pool
-        const int last_blk = std::max(0, (unified ? (P + S + kBlockTokens - 1) / kBlockTokens
-                                                  : (P + kBlockTokens - 1) / kBlockTokens) - 1);
-        int ns = std::min(want, ctx->forced_splits > 0 ? n_tiles : std::max(1, n_tiles / 2));
-        if (bf16) {                                      // block ids of a range fit LDS
-            const int cap = pp ? kPpMaxTiles : kAttnMaxTiles;
-            ns = std::max(ns, (n_tiles + cap - 1) / cap);
-        }
-        ns = std::max(1, std::min(ns, n_tiles));
-        splits_of_q[i] = ns;
-        p.max_splits = std::max(p.max_splits, ns);
-        const int n_mt = (S * G + RT - 1) / RT;
-        // Partition boundaries.  A suffix tile of the bf16 kernel costs about 4 prefix tiles (its V
-        // is transposed on the way into LDS), so the tiles are cut by weight, not by count.
-        std::vector<int> cut(ns + 1, 0);
-        {
-            const int npt = unified ? n_tiles : (P + KT - 1) / KT;
-            const int w_new = 4;
-            const int64_t total_w = npt + (int64_t)(n_tiles - npt) * w_new;
-            int t = 0;
-            int64_t acc = 0;
-            for (int s = 1; s < ns; ++s) {
-                const int64_t goal = total_w * s / ns;
-                while (t < n_tiles - (ns - s) && acc + (t < npt ? 1 : w_new) <= goal) { acc += (t < npt ? 1 : w_new); ++t; }
-                if (t < s) { acc += (t < npt ? 1 : w_new); ++t; }        // every partition gets a tile
-                cut[s] = t;
-            }
-            cut[ns] = n_tiles;
-        }
-        const int32_t *bt = p.block_table.data() + (size_t)i * p.max_blocks;
-        const uint8_t *pad_of = p.block_pad.empty() ? nullptr : p.block_pad.data() + (size_t)i * p.max_blocks;
-        for (int h = 0; h < c.n_kv_heads; ++h) {
-            for (int s = 0; s < ns; ++s) {
-                const int t0 = cut[s], t1 = cut[s + 1];
-                std::vector<AttnItem> bucket;
-                for (int mt = 0; mt < n_mt; ++mt) {
-                    AttnItem it{};
-                    it.q = i; it.kvh = h; it.m0 = mt * RT; it.tile_begin = t0; it.tile_end = t1;
-                    it.split = s; it.n_splits = ns; it.group = n_groups + mt;
-                    it.P = P; it.S = S; it.cu = p.cu_seqlens[i];
-                    for (int k = 0; k < 16; ++k) {
-                        const int idx = std::min(t0 * (KT / kBlockTokens) + k, last_blk);
-                        it.bid[k] = bt[idx] | (pad_of ? (int32_t)((uint32_t)pad_of[idx] << kPadShift) : 0);
-                    }
-                    if (pad_of && bf16 && !pp) {
-                        const int n_fast = std::min(t1, P >> 6) - t0;
-                        for (int k = t0 * 4; k < (t0 + std::max(n_fast, 0)) * 4; ++k) it.n_pad_fast += pad_of[k];
-                    }
-                    bucket.push_back(it);
-                }
-                buckets.push_back(std::move(bucket));
-            }
-            for (int mt = 0; mt < n_mt; ++mt) groups.push_back(MergeGroup{h, mt * RT, ns, p.cu_seqlens[i], S, {0, 0, 0}});
-            n_groups += n_mt;
-        }
-    }
-    p.n_groups = n_groups;
-    // Longest buckets first, each to the XCD with the least work so far (key tiles x items): long
-    // work-groups start early, XCDs finish together.
-    std::stable_sort(buckets.begin(), buckets.end(), [](const std::vector<AttnItem> &x, const std::vector<AttnItem> &y) {
-        return x[0].tile_end - x[0].tile_begin > y[0].tile_end - y[0].tile_begin;
-    });
-    std::vector<std::vector<AttnItem>> per_xcd(8);
-    int64_t xcd_load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (auto &bk : buckets) {
-        int xcd = 0;
-        for (int x = 1; x < 8; ++x)
-            if (xcd_load[x] < xcd_load[xcd]) xcd = x;
-        xcd_load[xcd] += (int64_t)(bk[0].tile_end - bk[0].tile_begin + 3) * (int64_t)bk.size();
-        for (auto &it : bk) { it.n_groups = n_groups; per_xcd[xcd].push_back(it); }
-    }
-    size_t longest = 0;
-    for (auto &v : per_xcd) longest = std::max(longest, v.size());
-    items.clear();
-    for (size_t k = 0; k < longest; ++k)
-        for (int x = 0; x < 8; ++x)
-            if (k < per_xcd[x].size()) items.push_back(per_xcd[x][k]);
-            else { AttnItem pad{}; pad.q = -1; pad.n_splits = 1; items.push_back(pad); }
-    while (!items.empty() && items.back().q < 0) items.pop_back();
-    p.n_items = (int32_t)items.size();
-    // Which bf16 kernel (one row block per wave).  The pipelined one holds 132 KB of LDS, so one
-    // work-group per CU: nothing hides a work-group's start-up and drain.  It wins when a launch is a
-    // single round of work-groups or when they are long; many short ones (measured: 1140 work-groups
-    // of ~20 key tiles, 743 vs 647 TFLOP/s) are better off two per CU in the general kernel.
-    int64_t n_real = 0, fast_tiles = 0;
-    for (const AttnItem &it : items)
-        if (it.q >= 0) {
-            ++n_real;
-            fast_tiles += std::max(std::min(it.tile_end, it.P >> 6) - it.tile_begin, 0);
-        }
-    p.pipelined = bf16 && rb == 1 && !pp && n_real > 0 &&
-                  (ctx->forced_attn_kernel == 1 || ctx->forced_attn_kernel == 2 ? ctx->forced_attn_kernel == 2
-                                           : (n_real <= 2 * 256 || fast_tiles >= 48 * n_real));
-}
-
 // Serialise the plan into the staging buffer and enqueue its upload on `stream`.
+// `fixed`: the device copy and the partials go to the static workspace; nothing is allocated, and a
+// batch that does not fit it is refused.
 tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
                       const std::vector<int32_t> &seg_end_of_q, const std::vector<StitchBlk> &sblk,
-                      hipStream_t stream)
+                      hipStream_t stream, bool fixed = false)
 {
     std::vector<AttnItem> items;
     std::vector<int32_t> splits_of_q;
     std::vector<MergeGroup> groups;
-    plan_attention(ctx, p, items, splits_of_q, groups);
+    if (!plan_attention(ctx->cfg, ctx->knobs, p, items, splits_of_q, groups))
+        return fail(ctx, TC_ERR_INVALID, "attn: a work item's key range exceeds its kernel's block-id table");
 
     const size_t B = p.B, nseg = segs.size();
     size_t off = 0;
@@ -498,7 +235,17 @@ tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
     const size_t o_gr = take(groups.size() * (sizeof(MergeGroup) / 4));
     const size_t o_rp = take(p.rope ? B : 0), o_rf = take(p.rope ? p.rope_rev_freq.size() * 2 : 0);
     const size_t total = std::max(off, size_t(8));
-    tc_status st = ensure_stage(ctx, total);
+    // split-KV partials.  bf16 kernels: per (partition, group, row block) 128 rows x (128 fp16 + 2
+    // floats) in fragment order, counted in floats; fp32 and decode kernels: per (partition, new
+    // token, head) D + 2 floats
+    const size_t part_need = !(p.max_splits > 1 || p.decode) ? 0
+        : ctx->cfg.dtype == TC_BF16 && !p.decode
+            ? (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * (64 + 2)
+            : (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * (ctx->cfg.head_dim + 2);
+    if (fixed && part_need > kScratchPartFloats)
+        return fail(ctx, TC_ERR_CAPACITY, "attn (no allocation): the split-KV partials need %zu floats, the fixed workspace holds %zu",
+                    part_need, kScratchPartFloats);
+    tc_status st = ensure_stage(ctx, total, fixed);
     if (st != TC_OK) return st;
     int32_t *h = ctx->h_stage;
     std::memset(h, 0, total * sizeof(int32_t));
@@ -525,11 +272,12 @@ tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
         std::memcpy(h + o_rf, p.rope_rev_freq.data(), p.rope_rev_freq.size() * sizeof(double));
     }
 
-    TC_HIP(ctx, hipMemcpyAsync(ctx->d_plan, h, total * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+    int32_t *d_dst = fixed ? (int32_t *)ctx->scratch_dev : ctx->d_plan;
+    TC_HIP(ctx, hipMemcpyAsync(d_dst, h, total * sizeof(int32_t), hipMemcpyHostToDevice, stream));
     TC_HIP(ctx, hipEventRecord(ctx->stage_ev, stream));
     ctx->stage_pending = true;
 
-    const int32_t *d = ctx->d_plan;
+    const int32_t *d = d_dst;
     p.dev.block_table = d + o_bt; p.dev.cu_seqlens = d + o_cu; p.dev.prefix_len = d + o_pl;
     p.dev.suffix_len = d + o_sl; p.dev.seg_start = d + o_ss; p.dev.seg_len = d + o_sn;
     p.dev.seg_slot = d + o_st; p.dev.seg_end_of_q = d + o_se;
@@ -543,18 +291,20 @@ tc_status upload_plan(tc_ctx *ctx, Plan &p, const std::vector<SegInfo> &segs,
     p.items_dev = (const AttnItem *)(d + o_it);
     p.groups_dev = (const MergeGroup *)(d + o_gr);
 
-    if (p.max_splits > 1 || p.decode) {
-        // bf16 kernel: per (partition, group, row block) 128 rows x (128 fp16 + 2 floats) in fragment
-        // order, counted in floats; fp32 and decode kernels: per (partition, new token, head) D + 2 floats
-        const size_t need = ctx->cfg.dtype == TC_BF16 && !p.decode
-            ? (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * (64 + 2)
-            : (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * (ctx->cfg.head_dim + 2);
-        if (need > ctx->d_part_floats) {
+    p.fixed = fixed;
+    p.part = nullptr;
+    if (fixed) {
+        // nothing in the partials has to start at zero: every slot a merge reads was written by the
+        // attention launch before it
+        if (part_need) p.part = (float *)(ctx->scratch_dev + kScratchPlanInts * 4);
+    } else if (part_need) {
+        if (part_need > ctx->d_part_floats) {
             if (ctx->d_part) TC_HIP(ctx, hipFree(ctx->d_part));
             ctx->d_part = nullptr; ctx->d_part_floats = 0;
-            TC_HIP(ctx, hipMalloc((void **)&ctx->d_part, need * sizeof(float)));
-            ctx->d_part_floats = need;
+            TC_HIP(ctx, hipMalloc((void **)&ctx->d_part, part_need * sizeof(float)));
+            ctx->d_part_floats = part_need;
         }
+        p.part = ctx->d_part;
     }
     p.valid = true;
     return TC_OK;
@@ -603,6 +353,11 @@ tc_status tc_create(const tc_config *cfg, void *kv_pool_dev, size_t pool_bytes, 
 
     std::unique_ptr<tc_ctx> ctx(new tc_ctx);
     ctx->cfg = *cfg;
+    if (hipGetDevice(&ctx->device) != hipSuccess) return TC_ERR_HIP;
+    // pinned staging for plan uploads, sized so that a plan bound for the static workspace always fits
+    if (hipHostMalloc((void **)&ctx->h_stage, kScratchPlanInts * sizeof(int32_t), hipHostMallocDefault) != hipSuccess)
+        return TC_ERR_HIP;
+    ctx->h_stage_ints = kScratchPlanInts;
     ctx->slot_blocks = (cfg->max_table_tokens + kBlockTokens - 1) / kBlockTokens;
     ctx->first_seq = tc_first_seq_block(cfg);
     Geom &g = ctx->geom;
@@ -626,9 +381,7 @@ tc_status tc_create(const tc_config *cfg, void *kv_pool_dev, size_t pool_bytes, 
     g.row_bytes = g.Hkv * g.D * g.esize;
     g.head_bytes = g.D * g.esize;
 
-    if (cfg->policy == TC_POLICY_LRU) ctx->rule.reset(new LruRule);
-    else if (cfg->policy == TC_POLICY_FIFO) ctx->rule.reset(new FifoRule);
-    else ctx->rule.reset(new LfuRule);
+    ctx->rule.reset(make_rule(cfg->policy));
 
     ctx->slots.resize(cfg->table_capacity);
     for (int s = 0; s < cfg->table_capacity; ++s) {
@@ -636,12 +389,12 @@ tc_status tc_create(const tc_config *cfg, void *kv_pool_dev, size_t pool_bytes, 
         ctx->free_slots.insert(s);
     }
     ctx->read_ring.resize(64);
+    ctx->read_gen.assign(64, 0);
     for (auto &e : ctx->read_ring)
         if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return TC_ERR_HIP;
     if (hipEventCreateWithFlags(&ctx->stage_ev, hipEventDisableTiming) != hipSuccess) return TC_ERR_HIP;
     if (hipEventCreateWithFlags(&ctx->raw_ev, hipEventDisableTiming) != hipSuccess) return TC_ERR_HIP;
-    for (int64_t b = ctx->first_seq; b < cfg->n_pool_blocks; ++b) ctx->free_seq.insert((int32_t)b);
-    ctx->seq_used.assign((size_t)(cfg->n_pool_blocks - ctx->first_seq), 0);
+    ctx->seq.reset(ctx->first_seq, cfg->n_pool_blocks);
     *out = ctx.release();
     return TC_OK;
 }
@@ -657,6 +410,7 @@ tc_status tc_destroy(tc_ctx *ctx)
     if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
     if (ctx->d_plan) (void)hipFree(ctx->d_plan);
     if (ctx->d_part) (void)hipFree(ctx->d_part);
+    if (ctx->d_read) (void)hipFree(ctx->d_read);
     for (auto &t : ctx->timed) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); }
     for (auto &e : ctx->ev_pool) (void)hipEventDestroy(e);
     delete ctx;
@@ -690,45 +444,56 @@ tc_status tc_load_async(tc_ctx *ctx, const int32_t *table_ids, int32_t n, int32_
         if (!ctx->tables.count(table_ids[k])) return fail(ctx, TC_ERR_UNKNOWN_TABLE, "load: table %d not registered", table_ids[k]);
     hipStream_t stream = (hipStream_t)stream_;
     const Geom &g = ctx->geom;
-    std::set<int32_t> touched;
+    // Slots that received copies get their `ready` event recorded behind them on every way out of
+    // this call, the early returns included: ids before a failing one stay requested and marked
+    // loaded, and whoever reads their slots from another stream must find an event that covers
+    // the copies already enqueued.
+    struct ReadyGuard {
+        tc_ctx *ctx; hipStream_t stream; std::set<int32_t> touched;
+        hipError_t flush() {
+            hipError_t first = hipSuccess;
+            for (int32_t s : touched) {
+                Slot &sl = ctx->slots[s];
+                const hipError_t e = hipEventRecord(sl.ready, stream);
+                if (e != hipSuccess && first == hipSuccess) first = e;
+                sl.ready_stream = stream;
+                sl.ready_pending = true;
+            }
+            touched.clear();
+            return first;
+        }
+        ~ReadyGuard() { (void)flush(); }
+    } guard{ctx, stream, {}};
+    std::set<int32_t> &touched = guard.touched;
     for (int k = 0; k < n; ++k) {
         const int32_t id = table_ids[k];
         Table &t = ctx->tables[id];
-        ctx->rule->tick();
-        int32_t evicted = -1;
-        const bool hit = ctx->rule->cached(id);
-        if (hit) {
-            ctx->rule->on_hit(id);
-        } else {
-            if ((int64_t)ctx->rule->size() >= ctx->cfg.table_capacity) {
-                evicted = ctx->rule->pick_victim(ctx->pins);
-                if (evicted < 0)
-                    return fail(ctx, TC_ERR_CAPACITY, "load: table %d needs a slot and all %d cached tables are pinned",
-                                id, (int)ctx->cfg.table_capacity);
-                ctx->rule->remove(evicted);
+        const CacheStep step = cache_request(*ctx->rule, ctx->pins, ctx->cfg.table_capacity, id);
+        if (step.refused)
+            return fail(ctx, TC_ERR_CAPACITY, "load: table %d needs a slot and all %d cached tables are pinned",
+                        id, (int)ctx->cfg.table_capacity);
+        const bool hit = step.hit;
+        const int32_t evicted = step.evicted;
+        if (!hit) {
+            if (evicted >= 0) {
                 Table &v = ctx->tables[evicted];
                 ctx->free_slots.insert(v.slot);
                 ctx->slots[v.slot].table = -1;
                 v.slot = -1;
                 std::fill(v.layer_loaded.begin(), v.layer_loaded.end(), 0);
             }
-            ctx->rule->insert(id);
             t.slot = *ctx->free_slots.begin();
             ctx->free_slots.erase(ctx->free_slots.begin());
             Slot &s = ctx->slots[t.slot];
             s.table = id;
-            if (s.read_ev >= 0) {       // a stitch may still be reading the previous occupant
-                TC_HIP(ctx, hipStreamWaitEvent(stream, ctx->read_ring[s.read_ev], 0));
-                s.read_ev = -1;
-            }
+            TC_HIP(ctx, wait_for_reader(ctx, s, stream));   // a stitch may still be reading the previous occupant
             if (s.ready_pending && s.ready_stream != stream)   // earlier copies into this slot on another stream
                 TC_HIP(ctx, hipStreamWaitEvent(stream, s.ready, 0));
             if (s.reader_pending) {     // attention launches read the previous occupant in place: wait for
                                         // everything enqueued so far on the stream they run on
                 if (s.reader_stream != stream) {
-                    const int32_t ev = ctx->read_next;
-                    ctx->read_next = (ctx->read_next + 1) % (int32_t)ctx->read_ring.size();
-                    TC_HIP(ctx, hipEventRecord(ctx->read_ring[ev], s.reader_stream));
+                    const int32_t ev = record_read(ctx, s.reader_stream);
+                    if (ev < 0) return fail(ctx, TC_ERR_HIP, "load: hipEventRecord failed");
                     TC_HIP(ctx, hipStreamWaitEvent(stream, ctx->read_ring[ev], 0));
                     for (Slot &o : ctx->slots)      // the same event covers every slot read on that stream
                         if (o.reader_pending && o.reader_stream == s.reader_stream) o.reader_pending = false;
@@ -751,6 +516,7 @@ tc_status tc_load_async(tc_ctx *ctx, const int32_t *table_ids, int32_t n, int32_
             if (blocks && ctx->raw_pending && ctx->raw_stream != stream)
                 TC_HIP(ctx, hipStreamWaitEvent(stream, ctx->raw_ev, 0));
             char *dst = (blocks ? g.tab_base : g.tab_base + (int64_t)t.slot * g.slot_bytes) + (size_t)l * width;
+            touched.insert(t.slot);
             TC_HIP(ctx, hipMemcpyAsync(dst, t.host_k + (size_t)l * width, width * (e - l), hipMemcpyHostToDevice, stream));
             TC_HIP(ctx, hipMemcpyAsync(dst + (g.slot_bytes >> 1), t.host_v + (size_t)l * width, width * (e - l),
                                        hipMemcpyHostToDevice, stream));
@@ -762,16 +528,10 @@ tc_status tc_load_async(tc_ctx *ctx, const int32_t *table_ids, int32_t n, int32_
                 ctx->raw_pending = true;
             }
             for (int x = l; x < e; ++x) t.layer_loaded[x] = 1;
-            touched.insert(t.slot);
             l = e;
         }
     }
-    for (int32_t s : touched) {
-        Slot &sl = ctx->slots[s];
-        TC_HIP(ctx, hipEventRecord(sl.ready, stream));
-        sl.ready_stream = stream;
-        sl.ready_pending = true;
-    }
+    TC_HIP(ctx, guard.flush());
     return TC_OK;
 }
 
@@ -871,8 +631,8 @@ static tc_status stitch_common(tc_ctx *ctx, const int32_t *table_ids, const int3
         need_total += need[i];
         total_S += suffix_len[i];
     }
-    if (need_total > (int64_t)ctx->free_seq.size())
-        return fail(ctx, TC_ERR_OOM_POOL, "stitch: need %lld sequence blocks, %zu free", (long long)need_total, ctx->free_seq.size());
+    if (need_total > (int64_t)ctx->seq.n_free())
+        return fail(ctx, TC_ERR_OOM_POOL, "stitch: need %lld sequence blocks, %zu free", (long long)need_total, ctx->seq.n_free());
     if (total_S > INT32_MAX / 2) return fail(ctx, TC_ERR_INVALID, "stitch: batch too long");
 
     // ---- build the plan (host side), then allocate
@@ -892,7 +652,8 @@ static tc_status stitch_common(tc_ctx *ctx, const int32_t *table_ids, const int3
         const double two_pi = 6.283185307179586476925286766559;
         for (int i = 0; i < D / 2; ++i) p.rope_rev_freq[i] = std::pow(rope_theta, -2.0 * i / D) / two_pi;
     }
-    auto next_free = ctx->free_seq.begin();
+    const std::vector<int32_t> lowest = ctx->seq.lowest((size_t)need_total);
+    auto next_free = lowest.begin();
     std::vector<StitchBlk> sblk;
     for (int i = 0; i < B; ++i) {
         int seg = i ? seg_end_of_q[i - 1] : 0;
@@ -911,11 +672,7 @@ static tc_status stitch_common(tc_ctx *ctx, const int32_t *table_ids, const int3
 
     // ---- commit: take the blocks, order the gather after the loads it reads, launch
     for (int i = 0; i < B; ++i)
-        for (int j = 0; j < need[i]; ++j) {
-            const int32_t phys = p.block_table[(size_t)i * max_blocks + j];
-            ctx->free_seq.erase(phys);
-            ctx->seq_used[phys - ctx->first_seq] = 1;
-        }
+        for (int j = 0; j < need[i]; ++j) ctx->seq.take(p.block_table[(size_t)i * max_blocks + j]);
     std::set<int32_t> used_slots;
     for (const SegInfo &s : segs) used_slots.insert(s.slot);
     for (int32_t s : used_slots) {
@@ -926,10 +683,12 @@ static tc_status stitch_common(tc_ctx *ctx, const int32_t *table_ids, const int3
     ctx->plan = std::move(p);
     TC_HIP(ctx, timed_launch(ctx, 0, stream, [&](const Launch &ln) { return launch_stitch(ctx->geom, ctx->plan.dev, 0, L, ctx->plan.rope, ln); }));
     if (!used_slots.empty()) {
-        const int32_t ev = ctx->read_next;
-        ctx->read_next = (ctx->read_next + 1) % (int32_t)ctx->read_ring.size();
-        TC_HIP(ctx, hipEventRecord(ctx->read_ring[ev], stream));
-        for (int32_t s : used_slots) ctx->slots[s].read_ev = ev;
+        const int32_t ev = record_read(ctx, stream);
+        if (ev < 0) return fail(ctx, TC_ERR_HIP, "stitch: hipEventRecord failed");
+        for (int32_t s : used_slots) {
+            Slot &sl = ctx->slots[s];
+            sl.read_ev = ev; sl.read_gen = ctx->read_gen[ev]; sl.read_stream = stream;
+        }
     }
     if (B > 0) {
         std::memcpy(block_table, ctx->plan.block_table.data(), (size_t)B * max_blocks * sizeof(int32_t));
@@ -1010,8 +769,8 @@ tc_status tc_stitch_alias(tc_ctx *ctx, const int32_t *table_ids, const int32_t *
         need_total += n_suf[i];
         total_S += suffix_len[i];
     }
-    if (need_total > (int64_t)ctx->free_seq.size())
-        return fail(ctx, TC_ERR_OOM_POOL, "alias: need %lld sequence blocks, %zu free", (long long)need_total, ctx->free_seq.size());
+    if (need_total > (int64_t)ctx->seq.n_free())
+        return fail(ctx, TC_ERR_OOM_POOL, "alias: need %lld sequence blocks, %zu free", (long long)need_total, ctx->seq.n_free());
     if (total_S > INT32_MAX / 2) return fail(ctx, TC_ERR_INVALID, "alias: batch too long");
 
     // ---- the plan: each table contributes the blocks of its slot, the suffix gets blocks of its own
@@ -1023,7 +782,8 @@ tc_status tc_stitch_alias(tc_ctx *ctx, const int32_t *table_ids, const int32_t *
     p.prefix_len.assign(B, 0);
     p.suffix_len.assign(suffix_len, suffix_len + B);
     std::set<int32_t> used_slots;
-    auto next_free = ctx->free_seq.begin();
+    const std::vector<int32_t> lowest = ctx->seq.lowest((size_t)need_total);
+    auto next_free = lowest.begin();
     for (int i = 0; i < B; ++i) {
         p.cu_seqlens[i + 1] = p.cu_seqlens[i] + suffix_len[i];
         p.prefix_len[i] = n_pref[i] * kBlockTokens;
@@ -1043,11 +803,7 @@ tc_status tc_stitch_alias(tc_ctx *ctx, const int32_t *table_ids, const int32_t *
 
     // ---- commit: take the suffix blocks; whatever follows on `stream` comes after the loads it reads
     for (int i = 0; i < B; ++i)
-        for (int j = n_pref[i]; j < n_pref[i] + n_suf[i]; ++j) {
-            const int32_t phys = p.block_table[(size_t)i * max_blocks + j];
-            ctx->free_seq.erase(phys);
-            ctx->seq_used[phys - ctx->first_seq] = 1;
-        }
+        for (int j = n_pref[i]; j < n_pref[i] + n_suf[i]; ++j) ctx->seq.take(p.block_table[(size_t)i * max_blocks + j]);
     for (int32_t s : used_slots) {
         Slot &sl = ctx->slots[s];
         if (sl.ready_pending && sl.ready_stream != stream)
@@ -1063,10 +819,14 @@ tc_status tc_stitch_alias(tc_ctx *ctx, const int32_t *table_ids, const int32_t *
     return TC_OK;
 }
 
-tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,
-                          void *out, const int32_t *cu_seqlens, const int32_t *block_table,
-                          int32_t max_blocks, const int32_t *prefix_len, const int32_t *suffix_len,
-                          int32_t B, float sm_scale, void *stream_)
+}  // extern "C"
+
+// Common body of tc_prefill_attn and tc_prefill_attn_noalloc (`fixed`: plan and partials in the static
+// workspace, no allocation on the way).
+static tc_status prefill_common(tc_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,
+                                void *out, const int32_t *cu_seqlens, const int32_t *block_table,
+                                int32_t max_blocks, const int32_t *prefix_len, const int32_t *suffix_len,
+                                int32_t B, float sm_scale, void *stream_, bool fixed)
 {
     if (!ctx) return TC_ERR_INVALID;
     if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, TC_ERR_INVALID, "attn: layer %d out of range", layer);
@@ -1076,7 +836,7 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
     if (!cu_seqlens || !block_table || !prefix_len || !suffix_len) return fail(ctx, TC_ERR_INVALID, "attn: null integer argument");
     hipStream_t stream = (hipStream_t)stream_;
     Plan &cur = ctx->plan;
-    const bool same = cur.valid && cur.B == B && cur.max_blocks == max_blocks &&
+    const bool same = cur.valid && cur.fixed == fixed && cur.B == B && cur.max_blocks == max_blocks &&
                       !std::memcmp(cur.cu_seqlens.data(), cu_seqlens, (size_t)(B + 1) * 4) &&
                       !std::memcmp(cur.prefix_len.data(), prefix_len, (size_t)B * 4) &&
                       !std::memcmp(cur.suffix_len.data(), suffix_len, (size_t)B * 4) &&
@@ -1114,7 +874,7 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
         p.cu_seqlens.assign(cu_seqlens, cu_seqlens + B + 1);
         p.prefix_len.assign(prefix_len, prefix_len + B);
         p.suffix_len.assign(suffix_len, suffix_len + B);
-        tc_status st = upload_plan(ctx, p, {}, {}, {}, stream);
+        tc_status st = upload_plan(ctx, p, {}, {}, {}, stream, fixed);
         if (st != TC_OK) return st;
         for (int32_t sidx : p.alias_slots) {        // the launches come after the loads of what they read
             Slot &sl = ctx->slots[sidx];
@@ -1138,8 +898,8 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
         a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
         a.n_append = p.total_S + p.B; a.items = p.items_dev; a.n_items = p.n_items; a.layer = layer;
         a.scale_log2 = sm_scale * 1.4426950408889634f;
-        a.part_o = ctx->d_part;
-        a.part_ml = ctx->d_part + (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * ctx->cfg.head_dim;
+        a.part_o = p.part;
+        a.part_ml = p.part + (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * ctx->cfg.head_dim;
         TC_HIP(ctx, timed_launch(ctx, 2, stream, [&](const Launch &ln) { return launch_decode_bf16(ctx->geom, p.dev, a, ln); }));
         TC_HIP(ctx, timed_launch(ctx, 3, stream, [&](const Launch &ln) { return launch_decode_finish(ctx->geom, p.dev, a, p.max_splits, ln); }));
         return TC_OK;
@@ -1157,10 +917,10 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
     a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
     a.n_append = bf16 && !p.pingpong ? p.total_S + p.B : 0; a.items = p.items_dev; a.n_items = p.n_items; a.layer = layer;
     a.scale_log2 = sm_scale * 1.4426950408889634f;
-    a.part_o = ctx->d_part;
-    a.part_ml = !ctx->d_part ? nullptr
-              : bf16 ? ctx->d_part + (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * 64
-                     : ctx->d_part + (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * ctx->cfg.head_dim;
+    a.part_o = p.part;
+    a.part_ml = !p.part ? nullptr
+              : bf16 ? p.part + (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * 64
+                     : p.part + (size_t)p.max_splits * p.total_S * ctx->cfg.n_q_heads * ctx->cfg.head_dim;
     TC_HIP(ctx, timed_launch(ctx, 2, stream, [&](const Launch &ln) {
         return p.pingpong ? launch_attn_pp_bf16(ctx->geom, p.dev, a, ln)
              : bf16 ? launch_attn_bf16(ctx->geom, p.dev, a, p.row_blocks, p.pipelined, ln)
@@ -1172,6 +932,17 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
                         : launch_merge(ctx->geom, p.dev, a, ln);
         }));
     return TC_OK;
+}
+
+extern "C" {
+
+tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,
+                          void *out, const int32_t *cu_seqlens, const int32_t *block_table,
+                          int32_t max_blocks, const int32_t *prefix_len, const int32_t *suffix_len,
+                          int32_t B, float sm_scale, void *stream)
+{
+    return prefill_common(ctx, layer, q, k_new, v_new, out, cu_seqlens, block_table, max_blocks, prefix_len,
+                          suffix_len, B, sm_scale, stream, false);
 }
 
 tc_status tc_grow_seqs(tc_ctx *ctx, int32_t *block_table, int32_t max_blocks, int32_t B, const int32_t *new_len)
@@ -1188,8 +959,7 @@ tc_status tc_grow_seqs(tc_ctx *ctx, int32_t *block_table, int32_t max_blocks, in
         int h = 0;
         while (h < max_blocks && row[h] >= 0) {
             const bool table_block = ctx->cfg.slot_layout == TC_SLOTS_BLOCKS && row[h] < ctx->first_seq;   // read in place
-            if (!table_block &&
-                (row[h] < ctx->first_seq || row[h] >= ctx->cfg.n_pool_blocks || !ctx->seq_used[row[h] - ctx->first_seq]))
+            if (!table_block && !ctx->seq.allocated(row[h]))
                 return fail(ctx, TC_ERR_INVALID, "grow: %d is not an allocated sequence block", row[h]);
             ++h;
         }
@@ -1199,15 +969,10 @@ tc_status tc_grow_seqs(tc_ctx *ctx, int32_t *block_table, int32_t max_blocks, in
             return fail(ctx, TC_ERR_OOM_POOL, "grow: query %d needs %d blocks, max_blocks is %d", i, want[i], max_blocks);
         if (want[i] > h) need_total += want[i] - h;
     }
-    if (need_total > (int64_t)ctx->free_seq.size())
-        return fail(ctx, TC_ERR_OOM_POOL, "grow: need %lld sequence blocks, %zu free", (long long)need_total, ctx->free_seq.size());
+    if (need_total > (int64_t)ctx->seq.n_free())
+        return fail(ctx, TC_ERR_OOM_POOL, "grow: need %lld sequence blocks, %zu free", (long long)need_total, ctx->seq.n_free());
     for (int i = 0; i < B; ++i)
-        for (int j = have[i]; j < want[i]; ++j) {
-            const int32_t phys = *ctx->free_seq.begin();
-            ctx->free_seq.erase(ctx->free_seq.begin());
-            ctx->seq_used[phys - ctx->first_seq] = 1;
-            block_table[(size_t)i * max_blocks + j] = phys;
-        }
+        for (int j = have[i]; j < want[i]; ++j) block_table[(size_t)i * max_blocks + j] = ctx->seq.take_lowest();
     return TC_OK;
 }
 
@@ -1222,13 +987,10 @@ tc_status tc_release_seqs(tc_ctx *ctx, const int32_t *block_table, int32_t max_b
         const int32_t b = block_table[k];
         if (b < 0) continue;
         if (ctx->cfg.slot_layout == TC_SLOTS_BLOCKS && b < ctx->first_seq) continue;   // a table slot's block, aliased
-        if (b < ctx->first_seq || b >= ctx->cfg.n_pool_blocks || !ctx->seq_used[b - ctx->first_seq] || !seen.insert(b).second)
+        if (!ctx->seq.allocated(b) || !seen.insert(b).second)
             return fail(ctx, TC_ERR_INVALID, "release: %d is not an allocated sequence block", b);
     }
-    for (int32_t b : seen) {
-        ctx->seq_used[b - ctx->first_seq] = 0;
-        ctx->free_seq.insert(b);
-    }
+    for (int32_t b : seen) ctx->seq.release(b);
     if (ctx->plan.valid && (!seen.empty() || !ctx->plan.alias_slots.empty()))
         ctx->plan.valid = false;               // its blocks may be handed out again
     return TC_OK;
@@ -1247,10 +1009,15 @@ tc_status tc_read_seq_kv(tc_ctx *ctx, int32_t layer, const int32_t *blocks, int3
             return fail(ctx, TC_ERR_INVALID, "read: block %d is not a sequence block", blocks[j]);
     hipStream_t stream = (hipStream_t)stream_;
     const size_t bytes = (size_t)n_tokens * ctx->geom.row_bytes;
-    char *d_k = nullptr, *d_v = nullptr; int32_t *d_b = nullptr;
-    TC_HIP(ctx, hipMalloc((void **)&d_k, bytes));
-    TC_HIP(ctx, hipMalloc((void **)&d_v, bytes));
-    TC_HIP(ctx, hipMalloc((void **)&d_b, nb * sizeof(int32_t)));
+    const size_t ids_at = (2 * bytes + 255) & ~size_t(255), need = ids_at + (size_t)nb * sizeof(int32_t);
+    if (need > ctx->d_read_bytes) {                  // one staging buffer, kept and grown on demand
+        if (ctx->d_read) TC_HIP(ctx, hipFree(ctx->d_read));
+        ctx->d_read = nullptr; ctx->d_read_bytes = 0;
+        TC_HIP(ctx, hipMalloc((void **)&ctx->d_read, need * 2));
+        ctx->d_read_bytes = need * 2;
+    }
+    char *d_k = ctx->d_read, *d_v = ctx->d_read + bytes;
+    int32_t *d_b = (int32_t *)(ctx->d_read + ids_at);
     tc_status st = TC_OK;
     hipError_t e = hipMemcpyAsync(d_b, blocks, nb * sizeof(int32_t), hipMemcpyHostToDevice, stream);
     if (e == hipSuccess) e = launch_readback(ctx->geom, layer, d_b, n_tokens, d_k, d_v, stream);
@@ -1258,7 +1025,6 @@ tc_status tc_read_seq_kv(tc_ctx *ctx, int32_t layer, const int32_t *blocks, int3
     if (e == hipSuccess) e = hipMemcpyAsync(out_v, d_v, bytes, hipMemcpyDeviceToHost, stream);
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
     if (e != hipSuccess) st = fail(ctx, TC_ERR_HIP, "read: %s", hipGetErrorString(e));
-    (void)hipFree(d_k); (void)hipFree(d_v); (void)hipFree(d_b);
     return st;
 }
 
@@ -1293,7 +1059,7 @@ int32_t tc_kv_splits(const tc_ctx *ctx) { return (ctx && ctx->plan.valid) ? ctx-
 tc_status tc_set_kv_splits(tc_ctx *ctx, int32_t n_splits)
 {
     if (!ctx || n_splits < 0) return TC_ERR_INVALID;
-    ctx->forced_splits = n_splits;
+    ctx->knobs.forced_splits = n_splits;
     ctx->plan.valid = false;
     return TC_OK;
 }
@@ -1310,7 +1076,7 @@ int32_t tc_attn_kernel(const tc_ctx *ctx)
 tc_status tc_set_attn_kernel(tc_ctx *ctx, int32_t kind)
 {
     if (!ctx || kind < 0 || kind > 4) return TC_ERR_INVALID;
-    ctx->forced_attn_kernel = kind;
+    ctx->knobs.forced_attn_kernel = kind;
     ctx->plan.valid = false;
     return TC_OK;
 }
@@ -1318,7 +1084,7 @@ tc_status tc_set_attn_kernel(tc_ctx *ctx, int32_t kind)
 tc_status tc_set_row_blocks(tc_ctx *ctx, int32_t row_blocks)
 {
     if (!ctx || row_blocks < 0 || row_blocks > 2) return TC_ERR_INVALID;
-    ctx->forced_row_blocks = row_blocks;
+    ctx->knobs.forced_row_blocks = row_blocks;
     ctx->plan.valid = false;
     return TC_OK;
 }
