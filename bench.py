@@ -7,7 +7,12 @@ tables' KV into sequence blocks, all layers) followed by tc_prefill_attn for eve
 the sequence blocks.  Inputs (table KV in the device table cache, per-layer q/k/v) are
 resident in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|c1|c2|c3|c4|c5|c5db] [--no-cpu-baseline]
+
+The default (`all`) times the long-schema workload c4 - the largest single-GPU configuration,
+26 TFLOP of counted attention work and 25.8 GB of gather per step - as the headline with exactly
+K steps, and then the batch-1 case c2, the 32-query batch c3 and the cold-cache loading pipeline
+c5 as labelled sub-records of the same line, each with its own kernel times and roofline fractions.
 """
 from __future__ import annotations
 
@@ -25,6 +30,8 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0          # MI355X dense bf16 matrix peak
 PEAK_FP32_TFLOPS = 157.3           # MI355X fp32 vector peak
 PEAK_HBM_GBPS = 8000.0
+METRIC = "suffix prefill attn TFLOP/s + KV-stitch GB/s; per-query prefill ms (1 GPU)"
+LLC_BYTES = 256 << 20               # last-level cache: destinations of small gathers are rotated past it
 
 
 def attn_flops_per_layer(cfg, P, S):
@@ -34,14 +41,16 @@ def attn_flops_per_layer(cfg, P, S):
 
 
 def read_traffic(workload):
-    """HBM bytes per attention launch from the committed counter summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", "prefill_attn_bf16_%s_pmc.txt" % workload)
-    try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split()[1])
-    except OSError:
-        pass
+    """HBM bytes per attention launch (FETCH_SIZE + WRITE_SIZE counter runs of this same command,
+    scaled by a copy kernel of known size) from the committed counter summary of the workload."""
+    import glob
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "prefill_attn_*_%s_pmc.txt" % workload))):
+        try:
+            for line in open(path):
+                if line.startswith("traffic_bytes_per_launch"):
+                    return float(line.split()[1])
+        except OSError:
+            pass
     return None
 
 
@@ -177,6 +186,7 @@ def bench_pipeline(args):
                 "misses": misses, "h2d_bytes": nbytes, "t_pipeline_ms": round(T_p, 3), "t_loads_ms": round(T_l, 3),
                 "t_compute_ms": round(T_c, 3), "exposed_load_ms": round(T_p - T_c, 3)}
 
+    link_peak = link_peak_gbps()
     policy = {"lru": 0, "fifo": 1, "lfu": 2}[args.policy]
     r = case(policy, args.rerank, b_c, b_m, args.steps, args.warmup)
     T_p, T_l, T_c, nbytes = r["t_pipeline_ms"], r["t_loads_ms"], r["t_compute_ms"], r["h2d_bytes"]
@@ -187,7 +197,7 @@ def bench_pipeline(args):
                     for pol in (0, 1, 2) for rr in (False, True) for serial in (True, False)]
     flops = attn_flops_per_layer(c, P_all, S_all) * L
     res = {
-        "metric": "suffix prefill attn TFLOP/s (cold-cache pipeline: loads + stitch + per-layer attention)",
+        "metric": METRIC, "what": "cold-cache pipeline: loads + stitch + per-layer attention",
         "value": round(flops / (T_p * 1e-3) / 1e12, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(T_p, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
@@ -205,13 +215,18 @@ def bench_pipeline(args):
         "h2d_gbps_in_pipeline": round(nbytes / (T_p * 1e-3) / 1e9, 2),
         "compute_tflops_no_loads": round(flops / (T_c * 1e-3) / 1e12, 2),
         "roofline": {"bound": "host-link", "achieved": round(nbytes / (T_p * 1e-3) / 1e9, 2),
-                     "peak": None, "unit": "GB/s", "frac": None, "traffic": None,
-                     "note": "link-bound: the copies of a batch take longer than its compute"},
+                     "peak": round(link_peak, 2), "unit": "GB/s", "frac": round(nbytes / (T_p * 1e-3) / 1e9 / link_peak, 4),
+                     "traffic": None,
+                     "note": "link-bound: the copies of a batch take longer than its compute; peak = this box's own "
+                             "pinned 1 GiB host-to-device copy, measured in this run"},
+        "h2d_frac_of_link_loads_only": round(nbytes / (T_l * 1e-3) / 1e9 / link_peak, 4),
         "cpu_baseline": None, "setup_s": round(setup_s, 1),
     }
     if ablation is not None:
         res["ablation"] = ablation
-    print(json.dumps(res))
+    del pool
+    torch.cuda.empty_cache()
+    return res
 
 
 def frontend_extras(wl):
@@ -353,52 +368,30 @@ def decode_extras(args, ctx, wl, prefill_layers, P, S, max_blocks, stream):
             "decode_frac_hbm": round(kv_bytes / (a_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4)}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2")
-    ap.add_argument("--splits", type=int, default=0, help="force split-KV partitions (0 = automatic)")
-    ap.add_argument("--row-blocks", type=int, default=0, help="force 128 (1) or 256 (2) rows per work-group")
-    ap.add_argument("--attn-kernel", type=int, default=0,
-                    help="force a bf16 attention kernel: 1 general, 2 pipelined, 4 alternating wave groups (0 = automatic)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true",
-                    help="only the headline step: skip the extra measurements (re-encoding stitch, front end, "
-                         "stitch without copying, graph replay); used for profiler runs")
-    ap.add_argument("--no-graph", action="store_true", help="skip the extra timing of the layer loop replayed as a HIP graph")
-    ap.add_argument("--micro-batch", type=int, default=8, help="b_c: requests computed per micro-batch (c5 pipeline)")
-    ap.add_argument("--prefetch", type=int, default=-1, help="b_m: requests loaded ahead (c5 pipeline; default b_c, 0 = no overlap)")
-    ap.add_argument("--policy", default="lru", choices=["lru", "fifo", "lfu"], help="replacement rule (c5 pipeline)")
-    ap.add_argument("--rerank", action="store_true", help="visit the batch in reranked order (c5 pipeline)")
-    ap.add_argument("--no-taper", action="store_true", help="c5 pipeline: micro-batches of b_c to the end (no shrinking tail)")
-    ap.add_argument("--ablation", action="store_true", help="c5 pipeline: also run rules x reranking x overlap")
-    ap.add_argument("--calibrate", action="store_true",
-                    help="run one plain elementwise kernel of known size (reads 1 GiB, writes 1 GiB) before the "
-                         "timed region, as the reference for scaling HBM counters of a --pmc run")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-
+def link_peak_gbps():
+    """The box's own large-transfer rate, pinned host memory to the device: the denominator for the loads."""
     import torch
-    from paper_2601_08743_amd import binding as B          # raises if the HIP library is not built
+    n = 1 << 30
+    h = torch.empty(n, dtype=torch.uint8).pin_memory()
+    d = torch.empty(n, dtype=torch.uint8, device="cuda")
+    best = 0.0
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        d.copy_(h, non_blocking=True)
+        torch.cuda.synchronize()
+        best = max(best, n / (time.perf_counter() - t0) / 1e9)
+    del h, d
+    return best
+
+
+def bench_resident(args, name, steps, warmup, extras=True, cpu_baseline=True):
+    """One configuration whose tables all fit the device cache (c1-c4): returns its record."""
+    import torch
+    from paper_2601_08743_amd import binding as B
     from paper_2601_08743_amd import workloads as W
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    if args.calibrate:
-        x = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
-        y = torch.empty_like(x)
-        torch.add(x, 1, out=y)
-        torch.cuda.synchronize()
-        del x, y
-    if args.workload in ("c5", "c5db"):
-        if args.steps == 50:
-            args.steps, args.warmup = 3, 1
-        return bench_pipeline(args)
-    wl = W.get(args.workload)
+    wl = W.get(name)
     c = wl.cfg
     t_setup = time.time()
     P = np.array([int(wl.table_len[q].sum()) for q in wl.queries])
@@ -407,7 +400,15 @@ def main():
     max_blocks = max(need) + 1
     max_tok = int(wl.table_len.max())
     cap = c.capacity
-    n_blocks = cap * (-(-max_tok // 16)) + sum(need) + c.batch + 8      # + one more block per query for the decode extra
+    kappa = 2 * c.n_kv_heads * c.head_dim * c.elem_bytes
+    # A gather whose destination fits the last-level cache would be timed against the cache, not HBM:
+    # the blocks of a step are given back only `rotate` steps later, so the lowest-free allocator
+    # hands every step fresh blocks and a destination is not written again before more than the
+    # cache's size has gone by.  (The source tables are the same every step: on c1 and c2 they stay
+    # cache-resident, which is why the HBM claim is made on c3 and c4.)
+    dest_bytes = kappa * c.n_layers * sum(need) * 16
+    rotate = int(min(8, max(1, -(-2 * LLC_BYTES // max(dest_bytes, 1)))))
+    n_blocks = cap * (-(-max_tok // 16)) + (rotate + 1) * sum(need) + c.batch + 8   # + one more block per query for the decode extra
     cfg = B.make_config(c.n_layers, c.n_q_heads, c.n_kv_heads, c.head_dim,
                         B.TC_F32 if c.dtype == "f32" else B.TC_BF16, n_blocks, cap, max_tok)
     pool = torch.empty(B.tc_pool_bytes(cfg), dtype=torch.uint8, device="cuda")
@@ -416,18 +417,19 @@ def main():
 
     # offline part: register every table of the database, make the cache warm
     resident = list(range(c.n_tables))[:cap]
-    tables_np = {}
+    tables_np, keep_host = {}, []
+    used = set(wl.table_ids.tolist())
     for t in range(c.n_tables):
         k, v = wl.table_kv(t)
         hk, hv = torch.from_numpy(k).pin_memory(), torch.from_numpy(v).pin_memory()
+        keep_host.append((hk, hv))
         ctx.tc_register_table_kv(t, int(wl.table_len[t]), hk, hv)
-        if t in set(wl.table_ids.tolist()):
+        if t in used:
             tables_np[t] = (k, v)
     ctx.tc_load_async(resident, 0, c.n_layers, stream)
     missing = [int(t) for t in wl.table_ids if t not in set(resident)]
     if missing:
         raise SystemExit("workload %s needs the loading pipeline (tables %s not resident)" % (c.name, missing[:5]))
-    tdt = torch.float32 if c.dtype == "f32" else torch.bfloat16
 
     def dev(a):
         t = torch.from_numpy(np.ascontiguousarray(a))
@@ -458,28 +460,36 @@ def main():
         layers(bt, pl)
         return bt
 
-    def run(n):
-        """n steps; the blocks of a step are released once the next step has been enqueued on the
-        same stream (stream order makes that safe for the kernels of the earlier step)."""
-        for _ in range(n):
-            bt = step()
-            ctx.tc_release_seqs(bt)
+    held = []
 
-    for _ in range(args.warmup):
+    def run(n):
+        """n steps; the blocks of a step are released `rotate` steps later, once those steps have been
+        enqueued on the same stream (stream order makes that safe for the earlier step's kernels)."""
+        for _ in range(n):
+            held.append(step())
+            if len(held) > rotate - 1:
+                ctx.tc_release_seqs(held.pop(0))
+
+    def drain():
+        while held:
+            ctx.tc_release_seqs(held.pop(0))
+
+    for _ in range(warmup):
         run(1)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run(args.steps)
+    run(steps)
     torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
 
-    # per-kernel durations: HIP events around every launch, on the launch stream
+    # per-kernel durations: every launch carries two HIP events that receive its own begin and end
+    # timestamps on the stream it is launched on (a second pass of the same steps)
     ctx.tc_profile_enable(True)
-    run(args.steps)
+    run(steps)
     torch.cuda.synchronize()
     prof = ctx.tc_profile_read()
     ctx.tc_profile_enable(False)
-    n_splits = None
+    drain()
     bt, pl = ctx.tc_stitch_kv(ids, cu_t, sl, max_blocks, stream)
     n_splits = ctx.tc_kv_splits()
     kernel_name = {0: "attn_%s_kernel" % c.dtype, 1: "attn_bf16_kernel<1>", 2: "attn_bf16_pipe_kernel",
@@ -487,7 +497,6 @@ def main():
 
     flops_layer = attn_flops_per_layer(c, P, S)
     flops_step = flops_layer * c.n_layers
-    kappa = 2 * c.n_kv_heads * c.head_dim * c.elem_bytes
     stitch_bytes = 2 * kappa * c.n_layers * int(P.sum())
     attn_us = prof["attn"][0] * 1e3 / max(prof["attn"][1], 1)
     merge_us = prof["merge"][0] * 1e3 / max(prof["merge"][1], 1)
@@ -498,15 +507,14 @@ def main():
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
     extra = {}
-    if args.no_extras:
-        args.no_graph = True
+    no_graph = args.no_graph or not extras
     # the re-encoding stitch (keys rotary-encoded by position while they are copied): same bytes, an
     # extra measurement beside the step; the step itself uses the plain stitch
     ctx.tc_release_seqs(bt)
-    ctx.tc_profile_enable(not args.no_extras)
+    ctx.tc_profile_enable(extras)
     ctx.tc_profile_read()
-    if not args.no_extras:
-        for _ in range(max(3, args.steps // 5)):
+    if extras:
+        for _ in range(max(3, steps // 5)):
             bt_r, _ = ctx.tc_stitch_kv_rope(ids, cu_t, sl, None, 1.0e6, max_blocks, stream)
             ctx.tc_release_seqs(bt_r)
         torch.cuda.synchronize()
@@ -518,10 +526,12 @@ def main():
         extra["stitch_rope_frac_hbm"] = round(stitch_bytes / (rope_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4)
         extra.update(frontend_extras(wl))
         if c.dtype == "bf16":
-            extra.update(zero_copy_extras(args, wl, qkv, outs, flops_step, stream))
-            extra.update(decode_extras(args, ctx, wl, layers, P, S, max_blocks + 1, stream))
+            sub = argparse.Namespace(**vars(args))
+            sub.steps, sub.warmup = steps, warmup
+            extra.update(zero_copy_extras(sub, wl, qkv, outs, flops_step, stream))
+            extra.update(decode_extras(sub, ctx, wl, layers, P, S, max_blocks + 1, stream))
     bt, pl = ctx.tc_stitch_kv(ids, cu_t, sl, max_blocks, stream)
-    if not args.no_graph:
+    if not no_graph:
         g = torch.cuda.CUDAGraph()
         layers(bt, pl)
         torch.cuda.synchronize()
@@ -531,67 +541,160 @@ def main():
             g.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(steps):
             g.replay()
         torch.cuda.synchronize()
-        g_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        g_ms = (time.perf_counter() - t0) * 1e3 / steps
         extra["graph_layers_ms"] = round(g_ms, 4)
         extra["graph_layers_tflops"] = round(flops_step / (g_ms * 1e-3) / 1e12, 2)
+        del g
 
-    # CPU baseline: the checker as it stands, on the same workload (also a parity spot check)
+    # CPU baseline: the checker as it stands on the same workload - every row and head of a stated
+    # sample of (layer, query) pairs, which is also a full-size parity check of those outputs; the
+    # gather checker (a byte loop) is timed on the same pairs
     cpu = None
     parity = None
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         import oracle
         layers(bt, pl)
         torch.cuda.synchronize()
-        n_layers_cpu = c.n_layers
-        est = flops_step / 10e9
-        if est > 40:                        # bound the sample to roughly 10-30 s of CPU work
-            n_layers_cpu = max(1, int(c.n_layers * 25 / est))
-        t_cpu, worst = 0.0, 0.0
-        qs = list(range(c.batch))
-        for l in range(n_layers_cpu):
+        fl_q = [4 * c.n_q_heads * c.head_dim * (int(s) * int(p) + int(s) * (int(s) + 1) // 2) for p, s in zip(P, S)]
+        rate = 15e9                                               # the checker's usual rate on the box's 16 threads
+        est_all = flops_step / rate
+        if est_all <= 30:
+            layer_set, q_set = list(range(c.n_layers)), list(range(c.batch))
+        else:
+            layer_set = [0, c.n_layers - 1]
+            q_set = sorted({int(P.argmax()), int(P.argmin())} | set(np.linspace(0, c.batch - 1, 4).astype(int).tolist()))[:4]
+            while len(q_set) > 1 and 2 * sum(fl_q[i] for i in q_set) / rate > 32:
+                q_set.pop(len(q_set) // 2)
+        t_cpu, t_gather, gather_bytes, worst, fl_done = 0.0, 0.0, 0, 0.0, 0
+        for l in layer_set:
             q_np, k_np, v_np = qkv_np[l]
             got = outs[l].float().cpu().numpy().astype(np.float64)
-            for i in qs:
+            for i in q_set:
                 tk = {int(t): tables_np[int(t)][0][l:l + 1] for t in wl.queries[i]}
                 tv = {int(t): tables_np[int(t)][1][l:l + 1] for t in wl.queries[i]}
+                t1 = time.perf_counter()
                 ks, vs = oracle.stitch(tk, wl.queries[i])[0], oracle.stitch(tv, wl.queries[i])[0]
+                t_gather += time.perf_counter() - t1
+                gather_bytes += 2 * (ks.nbytes + vs.nbytes)
                 s_ = slice(int(cu_s[i]), int(cu_s[i + 1]))
                 a = [W.storage_to_f64(x, c.dtype) for x in (q_np[s_], ks, vs, k_np[s_], v_np[s_])]
                 t1 = time.perf_counter()
                 ref = oracle.prefill_attn(*a, scale)
                 t_cpu += time.perf_counter() - t1
+                fl_done += fl_q[i]
                 worst = max(worst, float(np.abs(got[s_] - ref).max()))
-        cpu = {"value": round(flops_layer * n_layers_cpu / t_cpu / 1e12, 6), "unit": "TFLOP/s",
+        frac_done = fl_done / flops_step
+        cpu = {"value": round(fl_done / t_cpu / 1e12, 6), "unit": "TFLOP/s",
                "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": "%s, all queries and heads, layers 0..%d of %d (%.1f s of fp64 naive attention)" %
-                         (c.name, n_layers_cpu - 1, c.n_layers, t_cpu)}
+               "sample": "%s: every row and head of layers %s x queries %s = %.2f %% of the step's counted flops "
+                         "(%.1f s of fp64 naive attention; the whole step extrapolates linearly to %.0f s)" % (
+                             c.name, layer_set if len(layer_set) <= 4 else "0..%d" % (c.n_layers - 1),
+                             q_set if len(q_set) <= 8 else "0..%d" % (c.batch - 1), 100 * frac_done, t_cpu,
+                             t_cpu / frac_done),
+               "gather": {"value": round(gather_bytes / max(t_gather, 1e-9) / 1e9, 3), "unit": "GB/s",
+                          "sample": "the gather checker (byte loop, one thread) on the same (layer, query) pairs: "
+                                    "%.1f MB read + written in %.3f s" % (gather_bytes / 1e6, t_gather)}}
         parity = worst
     ctx.tc_release_seqs(bt)
 
+    stitch_gbps = stitch_bytes / (stitch_us * 1e-6) / 1e9
     res = {
-        "metric": "suffix prefill attn TFLOP/s (whole step: KV stitch + per-layer append, attention, split-KV merge)",
-        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": METRIC,
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": c.dtype, "data": "synthetic",
         "config": {"workload": "%s: L=%d Hq=%d Hkv=%d D=%d, %d tables U[%d,%d] tok, B=%d, P=%s, S=%s, block 16" % (
             c.name, c.n_layers, c.n_q_heads, c.n_kv_heads, c.head_dim, c.n_tables, c.table_len[0],
             c.table_len[1], c.batch, P.tolist() if c.batch <= 4 else "sum %d" % P.sum(),
-            S.tolist() if c.batch <= 4 else "sum %d" % S.sum()), "kv_splits": n_splits},
+            S.tolist() if c.batch <= 4 else "sum %d" % S.sum()), "kv_splits": n_splits,
+            "stitch_destinations_rotated_over_steps": rotate},
+        "what": "value = counted attention flops of a step / whole-step wall time (KV stitch + per-layer append, "
+                "attention, split-KV merge)",
         "prefill_ms_per_query": round(ms_per_step / c.batch, 4),
         "attn_kernel_us": round(attn_us, 2), "merge_kernel_us": round(merge_us, 2),
         "append_kernel_us": round(append_us, 2), "stitch_kernel_us": round(stitch_us, 2),
         "attn_tflops_kernel_time": round(attn_tflops_kernel, 2),
-        "stitch_gbps": round(stitch_bytes / (stitch_us * 1e-6) / 1e9, 1),
-        "stitch_frac_hbm": round(stitch_bytes / (stitch_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4),
+        "stitch_gbps": round(stitch_gbps, 1),
+        "stitch_frac_hbm": round(stitch_gbps / PEAK_HBM_GBPS, 4),
         "roofline": {"bound": "mfma" if c.dtype == "bf16" else "alu", "achieved": round(attn_tflops_kernel, 2),
                      "peak": peak, "unit": "TFLOP/s", "frac": round(attn_tflops_kernel / peak, 4),
                      "traffic": read_traffic(c.name), "kernel": kernel_name},
+        "roofline_stitch": {"bound": "hbm", "achieved": round(stitch_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                            "frac": round(stitch_gbps / PEAK_HBM_GBPS, 4), "kernel": "stitch_kernel",
+                            "bytes_per_launch": stitch_bytes},
         "cpu_baseline": cpu, "parity_max_abs_vs_oracle": parity, "setup_s": round(setup_s, 1),
     }
     res.update(extra)
+    torch.cuda.synchronize()
+    ctx.tc_destroy()
+    del pool, qkv, outs, keep_host
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="all",
+                    help="all (default: c4 as the headline, c2 / c3 / c5 as sub-records) or one of c1 c2 c3 c4 c5 c5db")
+    ap.add_argument("--splits", type=int, default=0, help="force split-KV partitions (0 = automatic)")
+    ap.add_argument("--row-blocks", type=int, default=0, help="force 128 (1) or 256 (2) rows per work-group")
+    ap.add_argument("--attn-kernel", type=int, default=0,
+                    help="force a bf16 attention kernel: 1 general, 2 pipelined, 4 alternating wave groups (0 = automatic)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the headline step: skip the extra measurements (re-encoding stitch, front end, "
+                         "stitch without copying, decode steps, graph replay) and the sub-records; used for profiler runs")
+    ap.add_argument("--no-graph", action="store_true", help="skip the extra timing of the layer loop replayed as a HIP graph")
+    ap.add_argument("--micro-batch", type=int, default=8, help="b_c: requests computed per micro-batch (c5 pipeline)")
+    ap.add_argument("--prefetch", type=int, default=-1, help="b_m: requests loaded ahead (c5 pipeline; default b_c, 0 = no overlap)")
+    ap.add_argument("--policy", default="lru", choices=["lru", "fifo", "lfu"], help="replacement rule (c5 pipeline)")
+    ap.add_argument("--rerank", action="store_true", help="visit the batch in reranked order (c5 pipeline)")
+    ap.add_argument("--no-taper", action="store_true", help="c5 pipeline: micro-batches of b_c to the end (no shrinking tail)")
+    ap.add_argument("--ablation", action="store_true", help="c5 pipeline: also run rules x reranking x overlap")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="run one plain elementwise kernel of known size (reads 1 GiB, writes 1 GiB) before the "
+                         "timed region, as the reference for scaling HBM counters of a --pmc run")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2601_08743_amd import binding as B          # noqa: F401  raises if the HIP library is not built
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate:
+        x = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
+        y = torch.empty_like(x)
+        torch.add(x, 1, out=y)
+        torch.cuda.synchronize()
+        del x, y
+    extras, cpu = not args.no_extras, not args.no_cpu_baseline
+    if args.workload in ("c5", "c5db"):
+        if args.steps == 20:
+            args.steps, args.warmup = 3, 1
+        res = bench_pipeline(args)
+    elif args.workload != "all":
+        res = bench_resident(args, args.workload, args.steps, args.warmup, extras, cpu)
+    else:
+        res = bench_resident(args, "c4", args.steps, args.warmup, extras, cpu)
+        if extras:
+            t0 = time.time()
+            sub = {}
+            sub["c2"] = bench_resident(args, "c2", 50, 5, True, cpu)
+            sub["c3"] = bench_resident(args, "c3", 10, 3, True, cpu)
+            pa = argparse.Namespace(**vars(args))
+            pa.workload, pa.steps, pa.warmup = "c5", 2, 1
+            sub["c5"] = bench_pipeline(pa)
+            res["sub_records"] = sub
+            res["sub_records_s"] = round(time.time() - t0, 1)
     print(json.dumps(res))
 
 
