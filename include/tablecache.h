@@ -249,6 +249,31 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
                           float sm_scale, void *stream);
 
 /*
+ * tc_prefill_attn for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same results
+ * as tc_prefill_attn; the difference is where the library keeps its own working memory for the call
+ * - the batch's integer plan (work items, block tables, lengths) and the split-KV partials.
+ * tc_prefill_attn puts them in buffers it allocates and grows on demand; this entry point puts them
+ * in a fixed 64 MiB workspace that the library's code object carries (4 MiB plan, 60 MiB partials;
+ * one copy per GPU, held until the process ends) and calls no hipMalloc, hipFree or other allocating
+ * routine.  A batch whose plan or partials do not fit is refused with TC_ERR_CAPACITY and nothing
+ * is enqueued (for scale: c2 needs 0.1 MiB + 7.6 MiB, a c5 micro-batch of 8 queries 0.5 + 21.6 MiB;
+ * c3 and c4 run unsplit and need no partials).
+ * Every call re-plans from its integer arguments unless they equal those of the previous call
+ * through this entry point (a batch stitched by tc_stitch_kv is planned again here, once).
+ * All contexts on one GPU share that GPU's workspace, which keeps the last call's contents (nothing
+ * in it has to start at zero: every partial a merge reads was written by the attention launch
+ * before it): calls through this entry point that overlap on one GPU - different streams, different
+ * contexts - race; keep them on one stream or order them with events.
+ * Errors: as tc_prefill_attn, plus TC_ERR_CAPACITY.
+ */
+tc_status tc_prefill_attn_noalloc(tc_ctx *ctx, int32_t layer, const void *q, const void *k_new,
+                                  const void *v_new, void *out, const int32_t *cu_seqlens,
+                                  const int32_t *block_table, int32_t max_blocks,
+                                  const int32_t *prefix_len, const int32_t *suffix_len, int32_t B,
+                                  float sm_scale, void *stream);
+
+/*
  * Grow sequences for decoding: make sure query i's row of block_table has a block for every
  * position below new_len[i] (its current blocks are the leading entries that are not -1; more
  * are taken lowest-free-first, queries in order).  A decode step is then tc_prefill_attn with

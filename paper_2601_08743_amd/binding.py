@@ -37,7 +37,7 @@ TC_SLOTS_ROWS, TC_SLOTS_BLOCKS = 0, 1
 
 EXPORTS = ["tc_block_bytes", "tc_pool_bytes", "tc_first_seq_block", "tc_create", "tc_destroy",
            "tc_register_table_kv", "tc_load_async", "tc_load_trace", "tc_is_resident",
-           "tc_stitch_kv", "tc_stitch_kv_rope", "tc_stitch_alias", "tc_prefill_attn", "tc_grow_seqs", "tc_release_seqs", "tc_read_seq_kv",
+           "tc_stitch_kv", "tc_stitch_kv_rope", "tc_stitch_alias", "tc_prefill_attn", "tc_prefill_attn_noalloc", "tc_grow_seqs", "tc_release_seqs", "tc_read_seq_kv",
            "tc_kv_splits", "tc_set_kv_splits", "tc_set_row_blocks", "tc_set_attn_kernel", "tc_attn_kernel", "tc_profile_enable", "tc_profile_read", "tc_last_error", "tc_version",
            "tc_trie_create", "tc_trie_destroy", "tc_trie_insert", "tc_trie_match", "tc_rerank",
            "tc_pin_tables", "tc_unpin_tables", "tc_plan_pipeline"]
@@ -69,6 +69,8 @@ _sig = {
     "tc_stitch_kv_rope": (_i32, [_vp, _vp, _vp, _i32, _vp, _vp, ctypes.c_double, _vp, _i32, _vp, _vp]),
     "tc_prefill_attn": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32,
                                ctypes.c_float, _vp]),
+    "tc_prefill_attn_noalloc": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32,
+                                       ctypes.c_float, _vp]),
     "tc_grow_seqs": (_i32, [_vp, _vp, _i32, _i32, _vp]),
     "tc_release_seqs": (_i32, [_vp, _vp, _i32, _i32]),
     "tc_read_seq_kv": (_i32, [_vp, _i32, _vp, _i32, _vp, _vp, _vp]),
@@ -241,6 +243,16 @@ class Context:
         self._check(_lib.tc_prefill_attn(self._h, layer, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
                                          cu.ctypes.data, bt.ctypes.data, max_blocks, pl.ctypes.data,
                                          sl.ctypes.data, B, sm_scale, _stream(stream)))
+
+    def tc_prefill_attn_noalloc(self, layer: int, q, k_new, v_new, out, cu_seqlens, block_table,
+                                prefix_len, suffix_len, sm_scale: float, stream=None):
+        cu, bt = _i32arr(cu_seqlens), _i32arr(block_table)
+        pl, sl = _i32arr(prefix_len), _i32arr(suffix_len)
+        B = pl.size
+        max_blocks = bt.shape[1] if bt.ndim == 2 else (bt.size // B if B else 0)
+        self._check(_lib.tc_prefill_attn_noalloc(self._h, layer, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                                 cu.ctypes.data, bt.ctypes.data, max_blocks, pl.ctypes.data,
+                                                 sl.ctypes.data, B, sm_scale, _stream(stream)))
 
     def tc_grow_seqs(self, block_table: np.ndarray, new_len) -> np.ndarray:
         """Returns the grown block table (a copy; the argument is left alone)."""

@@ -45,12 +45,22 @@ struct Slot {
 
 inline size_t align8(size_t n) { return (n + 7) & ~size_t(7); }
 
-// Capacity of a fixed workspace for plans and split-KV partials (callers that cannot allocate).
+// ------------------------------------------------------------------ workspace of tc_prefill_attn_noalloc
+// The entry point that allocates nothing keeps what tc_prefill_attn keeps in hipMalloc'ed buffers -
+// the batch's integer plan and the split-KV partials - in this array, which the code object brings
+// with it: 4 MiB for the plan, 60 MiB for partials.  Every GPU the library runs on holds its own
+// copy at its own address until the process ends; host code reaches it only through the address
+// hipGetSymbolAddress returns for the current device (tc_create resolves it once per device).
 constexpr size_t kScratchPlanInts = size_t(1) << 20;
 constexpr size_t kScratchPartFloats = size_t(15) << 20;
+constexpr size_t kScratchBytes = (kScratchPlanInts + kScratchPartFloats) * 4;
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+char *g_scratch_ptr[kMaxDevices];                   // device address of `scratch` on each device, once resolved
 
 }  // namespace
 
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 struct tc_ctx {
     tc_config cfg{};
@@ -353,7 +363,18 @@ tc_status tc_create(const tc_config *cfg, void *kv_pool_dev, size_t pool_bytes, 
 
     std::unique_ptr<tc_ctx> ctx(new tc_ctx);
     ctx->cfg = *cfg;
-    if (hipGetDevice(&ctx->device) != hipSuccess) return TC_ERR_HIP;
+    // this device's copy of the static workspace: its address comes from the runtime, once per device,
+    // with that device current (the array's name means nothing to host code)
+    if (hipGetDevice(&ctx->device) != hipSuccess || ctx->device < 0 || ctx->device >= kMaxDevices) return TC_ERR_HIP;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[ctx->device]) {
+            void *ptr = nullptr;
+            if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TC_ERR_HIP;
+            g_scratch_ptr[ctx->device] = (char *)ptr;
+        }
+        ctx->scratch_dev = g_scratch_ptr[ctx->device];
+    }
     // pinned staging for plan uploads, sized so that a plan bound for the static workspace always fits
     if (hipHostMalloc((void **)&ctx->h_stage, kScratchPlanInts * sizeof(int32_t), hipHostMallocDefault) != hipSuccess)
         return TC_ERR_HIP;
@@ -943,6 +964,16 @@ tc_status tc_prefill_attn(tc_ctx *ctx, int32_t layer, const void *q, const void 
 {
     return prefill_common(ctx, layer, q, k_new, v_new, out, cu_seqlens, block_table, max_blocks, prefix_len,
                           suffix_len, B, sm_scale, stream, false);
+}
+
+tc_status tc_prefill_attn_noalloc(tc_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,
+                                  void *out, const int32_t *cu_seqlens, const int32_t *block_table,
+                                  int32_t max_blocks, const int32_t *prefix_len, const int32_t *suffix_len,
+                                  int32_t B, float sm_scale, void *stream)
+{
+    if (ctx && !ctx->scratch_dev) return fail(ctx, TC_ERR_HIP, "attn (no allocation): the static workspace was not resolved");
+    return prefill_common(ctx, layer, q, k_new, v_new, out, cu_seqlens, block_table, max_blocks, prefix_len,
+                          suffix_len, B, sm_scale, stream, true);
 }
 
 tc_status tc_grow_seqs(tc_ctx *ctx, int32_t *block_table, int32_t max_blocks, int32_t B, const int32_t *new_len)
