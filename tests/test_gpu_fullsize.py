@@ -167,6 +167,8 @@ def test_c4_long_prefix(H, row_blocks):
             sl = slice(int(wl.cu_seqlens[i]), int(wl.cu_seqlens[i + 1]))
             np.testing.assert_array_equal(kk.view(np.uint8), np.concatenate([ks, qkv[1][sl]]).view(np.uint8))
             np.testing.assert_array_equal(vv.view(np.uint8), np.concatenate([vs, qkv[2][sl]]).view(np.uint8))
+    elif row_blocks == 1:                         # the pipelined kernel has a 1024-tile block-id table of its own: unsplit
+        assert dw.ctx.tc_attn_kernel() == 2 and dw.ctx.tc_kv_splits() == 1
     else:
         assert dw.ctx.tc_kv_splits() >= 2        # the block ids of a work item's key range must fit LDS
     assert e <= 1e-2 and rel <= 0.06
