@@ -43,6 +43,19 @@ constexpr int kPpLds = kPpBid + kPpMaxTiles * 4 * 4 + 256;   // + slack to align
 constexpr int kPpRing = 5;                           // operand fragments in flight: reads run kPpRing - 1 matrix instructions ahead
 constexpr float kPpRescale = 8.f;                    // log2 units: rescale O only when the maximum grew by more
 
+// lanes l and l ^ 32 hold the two halves of one row: the larger of their two values, in both
+// (v_permlane32_swap exchanges the upper 32 lanes of its first operand with the lower 32 of its
+// second: with the same value in both it yields (low half twice, high half twice); no LDS round trip)
+__device__ __forceinline__ float max_with_other_half(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// kPads: the batch has sequences that alias table slots, whose block-table entries carry unused
+// tail positions to mask; without them a tile's entries are not looked at in the softmax phase.
+template <bool kPads>
 __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b, AttnArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
@@ -92,9 +105,12 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
     const char *pool_l = g.pool + (int64_t)a.layer * g.layer_stride + (int64_t)it.kvh * 4096;
     const int64_t bb = g.block_bytes;
     const uint32_t v_half = (uint32_t)(g.block_bytes >> 1);
-    auto issue_tile = [&](int t) {                     // 4 load instructions
+    // (the block id of the tile after the one being requested is read from LDS right behind the
+    // loads and used by the next call, so that no call waits for an LDS round trip)
+    int bid_next = s_bid[w >> 1];                      // tile 0 (never used when the range is empty)
+    auto issue_tile = [&](int t) {                     // 4 load instructions; t = 0, 1, 2, .. in order
         const int j = w >> 1, i0 = 2 * (w & 1);
-        const char *src = pool_l + (int64_t)entry_bid(__builtin_amdgcn_readfirstlane(s_bid[t * 4 + j])) * bb;
+        const char *src = pool_l + (int64_t)entry_bid(__builtin_amdgcn_readfirstlane(bid_next)) * bb;
         const uint32_t kd = lds0 + (t % kPpKBufs) * kPpTile + j * 4096;
         const uint32_t vd = lds0 + kPpV + (t % kPpVBufs) * kPpTile + j * 4096;
 #pragma unroll
@@ -105,6 +121,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
 #pragma unroll
         for (int i = i0; i < i0 + 2; ++i)               // V chunks in operand order (see v_off)
             load_to_lds(vd + i * 1024, src + v_half + i * 1024, (2 * (lane & 31) + (lane >> 5)) * 16);
+        bid_next = s_bid[min(t + 1, n - 1) * 4 + j];
     };
     if (0 < n) issue_tile(0);
     if (1 < n) issue_tile(1);
@@ -169,8 +186,11 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
     // V(t): scores of tile t -> weights
     auto v_phase = [&](int t) {
         const int key0 = (it.tile_begin + t) * kAttnKeys;
-        const int4 e4 = *(const int4 *)&s_bid[t * 4];
-        const int pad4 = entry_pad(e4.x) | (entry_pad(e4.y) << 8) | (entry_pad(e4.z) << 16) | (entry_pad(e4.w) << 24);
+        int pad4 = 0;
+        if (kPads) {
+            const int4 e4 = *(const int4 *)&s_bid[t * 4];
+            pad4 = entry_pad(e4.x) | (entry_pad(e4.y) << 8) | (entry_pad(e4.z) << 16) | (entry_pad(e4.w) << 24);
+        }
         if (pad4 != 0 || key0 + kAttnKeys - 1 > wave_lim_min) {      // causal edge or unused block tails in this tile
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
@@ -188,7 +208,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
         for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sacc[0][e]);
 #pragma unroll
         for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[1][e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = max_with_other_half(mx);
         const float mxs = mx * c;
         if (__builtin_expect(__any(mxs > m_run + kPpRescale), 0)) {   // rare; also taken while m_run is still -inf
             const float m_new = fmaxf(m_run, mxs);
@@ -302,12 +322,18 @@ hipError_t launch_attn_pp_bf16(const Geom &g, const BatchDev &b, const AttnArgs 
     if (g.D != 128 || g.esize != 2 || a.n_append != 0) return hipErrorInvalidValue;
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)attn_bf16_pp_kernel,
+        hipError_t e = hipFuncSetAttribute((const void *)attn_bf16_pp_kernel<false>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kPpLds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)attn_bf16_pp_kernel<true>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kPpLds);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipExtLaunchKernelGGL(attn_bf16_pp_kernel, dim3(a.n_items), dim3(512), kPpLds, L.stream, L.start, L.stop, 0, g, b, a);
+    if (a.has_pads)
+        hipExtLaunchKernelGGL(attn_bf16_pp_kernel<true>, dim3(a.n_items), dim3(512), kPpLds, L.stream, L.start, L.stop, 0, g, b, a);
+    else
+        hipExtLaunchKernelGGL(attn_bf16_pp_kernel<false>, dim3(a.n_items), dim3(512), kPpLds, L.stream, L.start, L.stop, 0, g, b, a);
     return hipGetLastError();
 }
 

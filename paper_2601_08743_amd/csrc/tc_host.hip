@@ -938,6 +938,7 @@ static tc_status prefill_common(tc_ctx *ctx, int32_t layer, const void *q, const
     a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
     a.n_append = bf16 && !p.pingpong ? p.total_S + p.B : 0; a.items = p.items_dev; a.n_items = p.n_items; a.layer = layer;
     a.scale_log2 = sm_scale * 1.4426950408889634f;
+    a.has_pads = p.block_pad.empty() ? 0 : 1;
     a.part_o = p.part;
     a.part_ml = !p.part ? nullptr
               : bf16 ? p.part + (size_t)p.max_splits * p.n_groups * p.row_blocks * kAttnRows * 64

@@ -105,6 +105,7 @@ struct AttnArgs {
     int32_t layer;
     int32_t n_items;
     int32_t n_append;    // append units run by the bf16 attention launch (total_S + B), 0 = none
+    int32_t has_pads;    // some block-table entry of the batch carries unused tail positions (aliased table blocks)
 };
 
 }  // namespace tc
