@@ -149,6 +149,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
     auto m_phase = [&](int t, bool do_qk, bool do_pv) {
         const uint32_t kb = lds0 + (t % kPpKBufs) * kPpTile + k_off;
         const uint32_t vb = lds0 + ((t + kPpVBufs - 1) % kPpVBufs) * kPpTile + v_off;
+        bf16x8 kf[kPpRing];
+#define TC_KF(j) (*(lds_frag)(uintptr_t)((kb ^ (((j) >> 1) << 5)) + ((j) & 1) * 32 * 256))
         if (do_pv) {
             bf16x8 vf[kPpRing];
 #define TC_VF(j) (*(lds_frag)(uintptr_t)(vb + ((j) >> 2) * 4096 + ((j) & 3) * 1024))
@@ -160,6 +162,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 if (j + kPpRing - 1 < 16) vf[(j + kPpRing - 1) % kPpRing] = TC_VF(j + kPpRing - 1);
+                else if (do_qk) kf[j + kPpRing - 1 - 16] = TC_KF(j + kPpRing - 1 - 16);   // the first K fragments ride behind the last V ones
                 o[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j % kPpRing], pf[j >> 2], o[j & 3], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);     // keep the reads where they are: ahead (the scheduler pulls them back to their use)
             }
@@ -169,10 +172,10 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
             f32x16 zero;                               // the first product of each half starts from the constant 0
 #pragma unroll
             for (int e = 0; e < 16; ++e) zero[e] = 0.f;
-            bf16x8 kf[kPpRing];
-#define TC_KF(j) (*(lds_frag)(uintptr_t)((kb ^ (((j) >> 1) << 5)) + ((j) & 1) * 32 * 256))
+            if (!do_pv) {
 #pragma unroll
-            for (int j = 0; j < kPpRing - 1; ++j) kf[j] = TC_KF(j);
+                for (int j = 0; j < kPpRing - 1; ++j) kf[j] = TC_KF(j);
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
@@ -180,8 +183,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
                 sacc[j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j % kPpRing], qf[j >> 1], j < 2 ? zero : sacc[j & 1], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
-#undef TC_KF
         }
+#undef TC_KF
     };
     // V(t): scores of tile t -> weights
     auto v_phase = [&](int t) {
@@ -225,14 +228,29 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][e], c, neg_m));
-                sacc[mb][e] = p;
-                l_lane += p;
+                sacc[mb][e] = __builtin_amdgcn_exp2f(fmaf(sacc[mb][e], c, neg_m));
             }
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
             for (int e = 0; e < 8; ++e) pf[kk][e] = (__bf16)sacc[kk >> 1][8 * (kk & 1) + e];
+        // the row sum is taken over the weights as PV will use them (rounded to bf16), two per
+        // instruction: v_dot2_f32_bf16 with (1, 1) as the other operand
+        {
+            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+            bf16x2 ones;
+            ones[0] = (__bf16)1.f;
+            ones[1] = (__bf16)1.f;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    bf16x2 pr;
+                    pr[0] = pf[kk][e];
+                    pr[1] = pf[kk][e + 1];
+                    l_lane = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_lane, false);
+                }
+        }
         // the next matrix phase starts with PV of this tile: its first two V fragments are fetched now,
         // so that its first matrix instruction does not wait for an LDS round trip
         const uint32_t vb = lds0 + (t % kPpVBufs) * kPpTile + v_off;
