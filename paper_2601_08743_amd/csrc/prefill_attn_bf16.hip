@@ -528,9 +528,17 @@ static_assert(kLdsBytesPipe <= 160 * 1024 && 2 * kStage <= kFastBid, "LDS layout
 // Shorter runs take the general loop.  Runs of exactly three tiles are excluded on evidence, not
 // on a found cause: on some machines their first launches in a process returned wrong rows
 // (launch-dependent results for identical inputs, gone when the run went through the general loop),
-// while runs of four and more have never differed between launches.  Little is lost: runs this
-// short are mostly the pipeline's fill and drain (a two-tile run was measured slower than the
-// general loop).
+// while runs of four and more have never differed between launches.  What has been ruled out on the
+// CPU: the load schedule (a host model of the issue order, the vmcnt waits and the buffer reuse holds
+// for every run length from 3 up: tests/test_pipe_schedule_model.py; a run of three reuses no LDS
+// buffer at all and waits at least as long as longer runs do); reads of score registers this launch
+// never wrote (same test: every register the unconditional vector work touches was written by the
+// prime step or an earlier QK, also in the two steps without a QK); compiler-made copies next to
+// the hand-placed matrix instructions on any path of the control flow, the zero-iteration steady
+// loop of a three-tile run included, and a compiler value living in M0 across the LDS loads
+// (tests/test_kernel_schedule.py, on the emitted assembly).  The cause is open; the path stays off
+// for three tiles.  Little is lost: runs this short are mostly the pipeline's fill and drain (a
+// two-tile run was measured slower than the general loop).
 constexpr int kFastMinTiles = 4;
 
 #define TC_SB() __builtin_amdgcn_sched_barrier(0)

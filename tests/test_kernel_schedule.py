@@ -130,3 +130,28 @@ def test_pipelined_steps_keep_their_slot_structure(instructions):
     one = sum(1 for g in gaps if g == 1)
     print("gaps between matrix instructions holding exactly one hand-placed exp: %d" % one)
     assert one >= 2 * 31
+
+
+@pytest.mark.parametrize("src", ["prefill_attn_bf16.hip", "prefill_attn_pp_bf16.hip", "decode_attn_bf16.hip"])
+def test_compiler_keeps_nothing_in_m0(src):
+    """The direct-to-LDS loads (csrc/lds_dma.h) set M0 in inline assembly and cannot declare it as
+    clobbered (the compiler reserves the register).  That is sound only while the compiler itself
+    never keeps a value in M0 in these kernels: every mention of m0 in the emitted code must be one
+    of the hand-written `s_mov_b32 m0, ...` that directly precede a global_load_lds."""
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not available")
+    path = os.path.join(ROOT, "paper_2601_08743_amd", "csrc", src)
+    with tempfile.TemporaryDirectory() as d:
+        out = os.path.join(d, "k.s")
+        subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                               "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", os.path.dirname(path),
+                               "-S", "--cuda-device-only", path, "-o", out], stderr=subprocess.DEVNULL)
+        lines = [l.split(";")[0].strip() for l in open(out)]
+    lines = [l for l in lines if l and not l.startswith(".")]
+    uses = [i for i, l in enumerate(lines) if re.search(r"\bm0\b", l)]
+    assert uses, "no direct-to-LDS loads found in %s" % src
+    for i in uses:
+        assert re.match(r"^s_mov_b32 m0, ", lines[i]), lines[i]
+        nxt = [l for l in lines[i + 1:i + 4] if not l.startswith("s_nop")]
+        assert nxt and nxt[0].startswith("global_load_lds_dwordx4"), (lines[i], nxt[:1])
+    print("%s: %d uses of m0, all hand-written" % (src, len(uses)))
