@@ -97,7 +97,12 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
     {
         const int last_blk = max(((P + S + kBlockTokens - 1) >> 4) - 1, 0);
         const int32_t *bt = b.block_table + (int64_t)it.q * b.max_blocks;
-        for (int idx = tid; idx < n * 4; idx += 512) s_bid[idx] = bt[min(it.tile_begin * 4 + idx, last_blk)];
+        // (whole tiles below the sequence's last block go four entries per access where the table row
+        // is 16-byte aligned; the rest entry by entry, clamped)
+        const int32_t *src = bt + it.tile_begin * 4;
+        const int n_wide = (((uintptr_t)src) & 15) == 0 ? max(min(n, (last_blk + 1 - it.tile_begin * 4) >> 2), 0) : 0;
+        for (int idx = tid; idx < n_wide; idx += 512) ((int4 *)s_bid)[idx] = ((const int4 *)src)[idx];
+        for (int idx = n_wide * 4 + tid; idx < n * 4; idx += 512) s_bid[idx] = bt[min(it.tile_begin * 4 + idx, last_blk)];
     }
     __syncthreads();
 
@@ -129,7 +134,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
     // ---- state
     f32x16 o[4], sacc[2];         // sacc: scores of the tile between its M and V phase
     bf16x8 pf[4];                 // weights of the tile between its V phase and the next M phase (always written first)
-    bf16x8 vpre[2];               // first V fragments of that M phase
+    bf16x8 vpre[kPpRing - 1];     // first V fragments of that M phase
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -149,15 +154,16 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
     auto m_phase = [&](int t, bool do_qk, bool do_pv) {
         const uint32_t kb = lds0 + (t % kPpKBufs) * kPpTile + k_off;
         const uint32_t vb = lds0 + ((t + kPpVBufs - 1) % kPpVBufs) * kPpTile + v_off;
+        // the wave in its matrix phase goes first when both waves of a SIMD have an instruction to
+        // issue (measured on one machine against the same build without it: -1.1 %)
+        __builtin_amdgcn_s_setprio(2);
         bf16x8 kf[kPpRing];
 #define TC_KF(j) (*(lds_frag)(uintptr_t)((kb ^ (((j) >> 1) << 5)) + ((j) & 1) * 32 * 256))
         if (do_pv) {
             bf16x8 vf[kPpRing];
 #define TC_VF(j) (*(lds_frag)(uintptr_t)(vb + ((j) >> 2) * 4096 + ((j) & 3) * 1024))
-            vf[0] = vpre[0];                           // read at the end of the softmax phase before
-            vf[1] = vpre[1];
 #pragma unroll
-            for (int j = 2; j < kPpRing - 1; ++j) vf[j] = TC_VF(j);
+            for (int j = 0; j < kPpRing - 1; ++j) vf[j] = vpre[j];      // read at the end of the softmax phase before
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
@@ -184,6 +190,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        __builtin_amdgcn_s_setprio(0);
 #undef TC_KF
     };
     // V(t): scores of tile t -> weights
@@ -251,11 +258,11 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
                     l_lane = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_lane, false);
                 }
         }
-        // the next matrix phase starts with PV of this tile: its first two V fragments are fetched now,
-        // so that its first matrix instruction does not wait for an LDS round trip
+        // the next matrix phase starts with PV of this tile: its first V fragments (as many as its
+        // reads run ahead) are fetched now, so that it starts without waiting for an LDS round trip
         const uint32_t vb = lds0 + (t % kPpVBufs) * kPpTile + v_off;
-        vpre[0] = *(lds_frag)(uintptr_t)(vb);
-        vpre[1] = *(lds_frag)(uintptr_t)(vb + 1024);
+#pragma unroll
+        for (int j = 0; j < kPpRing - 1; ++j) vpre[j] = *(lds_frag)(uintptr_t)(vb + j * 1024);
     };
     // the wave's own part of tile t must have landed before the barrier that lets the first wave
     // read it; the tile issued after it may still be in flight
