@@ -277,6 +277,33 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
     // their part at the end of their V(t-1), B's at the end of their M(t-1).  Tile t+2 is requested at
     // the start of a wave's V(t) (A: interval 2t+1, B: 2t+2); the buffers it goes to were last read in
     // interval 2t-1.
+    // A wave none of whose 32 rows exists (the row space of a (query, KV head) rarely fills its last
+    // 256-row tile) brings its share of every tile and passes every barrier, but runs neither matrix
+    // nor softmax phase: on a chip whose clock is set by its power budget, work not done is time
+    // gained by the others.  (Kept apart from the loop below, which compiles to worse code with a
+    // test around its phases.)
+    if (__builtin_amdgcn_readfirstlane((int)(it.m0 + w * 32 >= m_rows))) {
+        if (n > 0) {
+            wait_tile(0);
+            __syncthreads();
+            if (grp) __syncthreads();
+            if (grp) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (2 < n) issue_tile(2);
+            if (!grp) wait_tile(1);
+            __syncthreads();
+            for (int t = 1; t < n; ++t) {
+                if (grp) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                if (t + 2 < n) issue_tile(t + 2);
+                if (!grp) wait_tile(t + 1);
+                __syncthreads();
+            }
+            __syncthreads();
+            if (!grp) __syncthreads();
+        }
+        return;
+    }
     if (n > 0) {
         wait_tile(0);
         __syncthreads();                               // tile 0 visible
