@@ -83,6 +83,7 @@ def bench_pipeline(args):
         k, v = wl.table_kv(t)
         host_kv.append((torch.from_numpy(k).pin_memory(), torch.from_numpy(v).pin_memory()))
     s_main, s_load = torch.cuda.Stream(), torch.cuda.Stream()
+    load_streams = [s_load] + [torch.cuda.Stream() for _ in range(max(args.load_streams, 1) - 1)]
     # suffix activations: two layers' worth of random q/k/v, reused cyclically by the layers
     # (their values do not change what is timed)
     qkv = []
@@ -165,11 +166,11 @@ def bench_pipeline(args):
         res_p, res_l, res_c, misses, nbytes = [], [], [], 0, 0
         for rep in range(reps + warmup):
             fresh()
-            tp = timed(lambda: PL.run(ctx, queries, steps, 0, L, s_load, stitch, layers,
+            tp = timed(lambda: PL.run(ctx, queries, steps, 0, L, load_streams, stitch, layers,
                                       torch.cuda.synchronize if serial else None))
             tr = ctx.tc_load_trace()
             fresh()
-            tl = timed(lambda: PL.run(ctx, queries, steps, 0, L, s_load, lambda a, b: None, lambda a, b, h: None))
+            tl = timed(lambda: PL.run(ctx, queries, steps, 0, L, load_streams, lambda a, b: None, lambda a, b, h: None))
             fresh()
             t_compute[0] = 0.0
             PL.run(ctx, queries, steps_serial, 0, L, s_load, stitch_clocked, layers_clocked)
@@ -653,6 +654,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="skip the extra timing of the layer loop replayed as a HIP graph")
     ap.add_argument("--micro-batch", type=int, default=8, help="b_c: requests computed per micro-batch (c5 pipeline)")
     ap.add_argument("--prefetch", type=int, default=-1, help="b_m: requests loaded ahead (c5 pipeline; default b_c, 0 = no overlap)")
+    ap.add_argument("--load-streams", type=int, default=2,
+                    help="c5 pipeline: side streams the load calls take in turn (2: one copy's start-up gap is covered by the other queue)")
     ap.add_argument("--policy", default="lru", choices=["lru", "fifo", "lfu"], help="replacement rule (c5 pipeline)")
     ap.add_argument("--rerank", action="store_true", help="visit the batch in reranked order (c5 pipeline)")
     ap.add_argument("--no-taper", action="store_true", help="c5 pipeline: micro-batches of b_c to the end (no shrinking tail)")

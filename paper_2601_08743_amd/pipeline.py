@@ -36,7 +36,13 @@ def run(ctx: "B.Context", queries: Sequence[np.ndarray], steps: np.ndarray, l0: 
     `before_demand()` is called ahead of each step's demand loads: a baseline without any overlap
     waits there for the device to go idle (the host otherwise runs ahead, and even demand loads
     overlap the previous step's layers).  `keep_pinned` (schedules planned with it; aliasing
-    stitch): a micro-batch's tables are unpinned after its layers are enqueued, not after its stitch."""
+    stitch): a micro-batch's tables are unpinned after its layers are enqueued, not after its stitch.
+    `load_stream` may be a list of streams: the load calls then take them in turn, so that the copies
+    of consecutive requests are handed to the copy engines from two queues and the start-up gap
+    between one copy and the next (tens of microseconds on one queue) is covered by the other queue's
+    copy; the library orders slots across streams with its own events."""
+    streams = list(load_stream) if isinstance(load_stream, (list, tuple)) else [load_stream]
+    turn = [0]
 
     def ask(a: int, b: int) -> None:
         ids = flat_tables(queries, a, b)
@@ -46,7 +52,8 @@ def run(ctx: "B.Context", queries: Sequence[np.ndarray], steps: np.ndarray, l0: 
             # tables, so a micro-batch at the head of a prefetched range need not wait for the rest
             for i in range(a, b):
                 if len(queries[i]):
-                    ctx.tc_load_async(np.asarray(queries[i], dtype=np.int32), l0, l1, load_stream)
+                    ctx.tc_load_async(np.asarray(queries[i], dtype=np.int32), l0, l1, streams[turn[0] % len(streams)])
+                    turn[0] += 1
 
     for c0, c1, d0, d1, p0, p1 in np.asarray(steps).tolist():
         if before_demand is not None:
