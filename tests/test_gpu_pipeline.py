@@ -34,7 +34,7 @@ POLICIES = [("lru", 0, oracle.LRUModel), ("fifo", 1, oracle.FIFOModel), ("lfu", 
 @pytest.mark.parametrize("name,policy,Model", POLICIES)
 @pytest.mark.parametrize("b_c,b_m", [(2, 2), (2, 0), (1, 4), (3, 1)])
 @pytest.mark.parametrize("rerank", [False, True])
-def test_pipeline_trace_and_stitches(H, name, policy, Model, b_c, b_m, rerank):
+def test_pipeline_trace_and_stitches(H, name, policy, Model, b_c, b_m, rerank, n_load_streams=1):
     from paper_2601_08743_amd import binding as B
     from paper_2601_08743_amd import pipeline as PL
     wl = W.make_workload(_cfg())
@@ -50,7 +50,7 @@ def test_pipeline_trace_and_stitches(H, name, policy, Model, b_c, b_m, rerank):
     assert [tuple(r) for r in steps.tolist()] == want_steps
 
     dw = H.DeviceWorkload(wl, load_all=False, capacity=c.capacity, policy=policy)
-    s_load = torch.cuda.Stream()
+    s_load = torch.cuda.Stream() if n_load_streams == 1 else [torch.cuda.Stream() for _ in range(n_load_streams)]
     q_l, k_l, v_l = wl.suffix_qkv(1)
     dq, dk, dv = (H.to_dev(x, c) for x in (q_l, k_l, v_l))
     cu = wl.cu_seqlens
