@@ -193,12 +193,15 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
         __builtin_amdgcn_s_setprio(0);
 #undef TC_KF
     };
-    // V(t): scores of tile t -> weights
+    // V(t): scores of tile t -> weights.  (With unused block tails to mask, the tile's four
+    // block-table entries are read from LDS at the end of the phase before, like the first V fragments.)
+    int4 e4_next = make_int4(0, 0, 0, 0);
+    if (kPads && n > 0) e4_next = *(const int4 *)&s_bid[0];
     auto v_phase = [&](int t) {
         const int key0 = (it.tile_begin + t) * kAttnKeys;
         int pad4 = 0;
         if (kPads) {
-            const int4 e4 = *(const int4 *)&s_bid[t * 4];
+            const int4 e4 = e4_next;
             pad4 = entry_pad(e4.x) | (entry_pad(e4.y) << 8) | (entry_pad(e4.z) << 16) | (entry_pad(e4.w) << 24);
         }
         if (pad4 != 0 || key0 + kAttnKeys - 1 > wave_lim_min) {      // causal edge or unused block tails in this tile
@@ -263,6 +266,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(Geom g, BatchDev b
         const uint32_t vb = lds0 + (t % kPpVBufs) * kPpTile + v_off;
 #pragma unroll
         for (int j = 0; j < kPpRing - 1; ++j) vpre[j] = *(lds_frag)(uintptr_t)(vb + j * 1024);
+        if (kPads) e4_next = *(const int4 *)&s_bid[min(t + 1, n - 1) * 4];
     };
     // the wave's own part of tile t must have landed before the barrier that lets the first wave
     // read it; the tile issued after it may still be in flight
