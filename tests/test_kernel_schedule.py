@@ -132,6 +132,60 @@ def test_pipelined_steps_keep_their_slot_structure(instructions):
     assert one >= 2 * 31
 
 
+def _sregs(text):
+    out = set()
+    for m in re.finditer(r"\bs\[(\d+):(\d+)\]|\bs(\d+)\b", text):
+        if m.group(1):
+            out.update(range(int(m.group(1)), int(m.group(2)) + 1))
+        else:
+            out.add(int(m.group(3)))
+    return out
+
+
+def _device_asm(src):
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not available")
+    path = os.path.join(ROOT, "paper_2601_08743_amd", "csrc", src)
+    with tempfile.TemporaryDirectory() as d:
+        out = os.path.join(d, "k.s")
+        subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                               "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", os.path.dirname(path),
+                               "-S", "--cuda-device-only", path, "-o", out], stderr=subprocess.DEVNULL)
+        lines = [l.split(";")[0].strip() for l in open(out)]
+    return [l for l in lines if l and not l.startswith(".")]
+
+
+@pytest.mark.parametrize("src", ["prefill_attn_bf16.hip", "prefill_attn_pp_bf16.hip", "decode_attn_bf16.hip"])
+def test_lds_loads_read_no_freshly_vector_written_scalar(src):
+    """A vector-memory instruction must not read a scalar register that a vector instruction wrote
+    less than 5 wait states earlier (no interlock), and the compiler cannot keep that rule for a load
+    hidden in inline assembly (csrc/lds_dma.h): it puts the v_readfirstlane of a per-lane base right in
+    front of the statement.  The statement copies the base with a scalar move of its own, so the
+    nearest writer of every such load's base pair must be a scalar instruction (a scalar-written
+    register may be used at once).  Checked on the emitted code."""
+    lines = _device_asm(src)
+    loads = [i for i, l in enumerate(lines) if l.startswith("global_load_lds")]
+    assert loads, "no direct-to-LDS loads found in %s" % src
+    for i in loads:
+        base = _sregs(lines[i].split(None, 1)[1])
+        assert len(base) == 2, lines[i]
+        gap, writer = 0, None
+        for j in range(i - 1, max(i - 12, -1), -1):
+            if lines[j].endswith(":"):
+                break
+            op, _, rest = lines[j].partition(" ")
+            if op == "s_nop":
+                gap += int(rest) + 1
+                continue
+            if _sregs(rest.split(",")[0]) & base and not op.startswith(("s_cmp", "s_cbranch", "s_waitcnt")):
+                writer = (op, gap)
+                break
+            gap += 1
+        assert writer is not None, "base of '%s' has no writer in sight" % lines[i]
+        assert writer[0].startswith("s_") or writer[1] >= 5, (lines[i], writer)
+    print("%s: %d direct-to-LDS loads, every base written by a scalar instruction" % (src, len(loads)))
+
+
 @pytest.mark.parametrize("src", ["prefill_attn_bf16.hip", "prefill_attn_pp_bf16.hip", "decode_attn_bf16.hip"])
 def test_compiler_keeps_nothing_in_m0(src):
     """The direct-to-LDS loads (csrc/lds_dma.h) set M0 in inline assembly and cannot declare it as
