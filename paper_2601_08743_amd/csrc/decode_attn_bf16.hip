@@ -295,13 +295,11 @@ hipError_t launch_decode_bf16(const Geom &g, const BatchDev &b, const AttnArgs &
 {
     if (a.n_items + a.n_append == 0) return hipSuccess;
     if (g.D != 128 || g.esize != 2 || g.G > 32) return hipErrorInvalidValue;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)decode_attn_bf16_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kDecLds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static PerDeviceOnce configured;
+    const hipError_t e = configured.run([] {
+        return hipFuncSetAttribute((const void *)decode_attn_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kDecLds);
+    });
+    if (e != hipSuccess) return e;
     TC_LAUNCH(decode_attn_bf16_kernel, a.n_items + a.n_append, kDecLds, L, g, b, a);
     return hipGetLastError();
 }

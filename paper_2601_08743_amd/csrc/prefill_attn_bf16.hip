@@ -988,13 +988,11 @@ __global__ __launch_bounds__(256) void merge_bf16_kernel(Geom g, AttnArgs a, con
 template <int RB>
 static hipError_t launch_attn_rb(const Geom &g, const BatchDev &b, const AttnArgs &a, const Launch &L)
 {
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)attn_bf16_kernel<RB>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static PerDeviceOnce configured;
+    const hipError_t e = configured.run([] {
+        return hipFuncSetAttribute((const void *)attn_bf16_kernel<RB>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    });
+    if (e != hipSuccess) return e;
     TC_LAUNCH(attn_bf16_kernel<RB>, a.n_items + a.n_append, kLdsBytes, L, g, b, a);
     return hipGetLastError();
 }
@@ -1005,13 +1003,12 @@ hipError_t launch_attn_bf16(const Geom &g, const BatchDev &b, const AttnArgs &a,
     if (a.n_items + a.n_append == 0) return hipSuccess;
     if (g.D != 128 || g.esize != 2) return hipErrorInvalidValue;
     if (row_blocks == 1 && pipelined) {
-        static bool configured = false;
-        if (!configured) {
-            hipError_t e = hipFuncSetAttribute((const void *)attn_bf16_pipe_kernel,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesPipe);
-            if (e != hipSuccess) return e;
-            configured = true;
-        }
+        static PerDeviceOnce configured;
+        const hipError_t e = configured.run([] {
+            return hipFuncSetAttribute((const void *)attn_bf16_pipe_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kLdsBytesPipe);
+        });
+        if (e != hipSuccess) return e;
         TC_LAUNCH(attn_bf16_pipe_kernel, a.n_items + a.n_append, kLdsBytesPipe, L, g, b, a);
         return hipGetLastError();
     }

@@ -376,16 +376,16 @@ hipError_t launch_attn_pp_bf16(const Geom &g, const BatchDev &b, const AttnArgs 
 {
     if (a.n_items == 0) return hipSuccess;
     if (g.D != 128 || g.esize != 2 || a.n_append != 0) return hipErrorInvalidValue;
-    static bool configured = false;
-    if (!configured) {
+    static PerDeviceOnce configured;
+    const hipError_t ec = configured.run([] {
         hipError_t e = hipFuncSetAttribute((const void *)attn_bf16_pp_kernel<false>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kPpLds);
         if (e == hipSuccess)
             e = hipFuncSetAttribute((const void *)attn_bf16_pp_kernel<true>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kPpLds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+        return e;
+    });
+    if (ec != hipSuccess) return ec;
     if (a.has_pads)
         hipExtLaunchKernelGGL(attn_bf16_pp_kernel<true>, dim3(a.n_items), dim3(512), kPpLds, L.stream, L.start, L.stop, 0, g, b, a);
     else

@@ -2,6 +2,7 @@
 // Nothing here is part of the public ABI (see include/tablecache.h).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
@@ -17,6 +18,26 @@ struct Launch {
 };
 #define TC_LAUNCH(kernel, grid, lds_bytes, L, ...) \
     hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(256), (lds_bytes), (L).stream, (L).start, (L).stop, 0, __VA_ARGS__)
+
+// A kernel's dynamic-LDS limit (hipFuncSetAttribute) is a property of the kernel on one device: each
+// launcher keeps one of these per kernel and raises the limit the first time it launches on a device.
+// (Two threads that race on a device's first launch both set the same value.)
+struct PerDeviceOnce {
+    static constexpr int kDevices = 64;
+    std::atomic<unsigned char> done[kDevices];
+    template <typename F>
+    hipError_t run(F &&set_attributes)
+    {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= kDevices) return hipErrorInvalidDevice;
+        if (done[dev].load(std::memory_order_acquire)) return hipSuccess;
+        e = set_attributes();
+        if (e == hipSuccess) done[dev].store(1, std::memory_order_release);
+        return e;
+    }
+};
 
 // kv_stitch.hip
 hipError_t launch_stitch(const Geom &g, const BatchDev &b, int l0, int l1, bool rope, const Launch &L);
