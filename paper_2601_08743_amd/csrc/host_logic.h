@@ -194,15 +194,35 @@ inline bool plan_attention_pass(const tc_config &c, const PlanKnobs &knobs, Plan
     p.pingpong = false;
     // Decode step: every query brings at most one new token, so a KV head has only G rows and the
     // work is reading K and V once.  The decode kernels split the keys of a (query, KV head) over
-    // the four waves of a work-group and over `ns` work-groups: enough of them to cover the chip,
-    // but at least six key tiles each.  Unused block tails of sequences that alias table slots ride
-    // in the device block table and are masked by the kernel.
+    // the four waves of a work-group and over `ns` work-groups.  A work-group holds a CU (its ring of
+    // tiles fills the LDS), and what a launch of this kind costs is how its loads get going and
+    // drain, once per round of work-groups: so the ranges are cut for ONE round of equally long
+    // work-groups - the smallest range length L (in key tiles, at least six) for which
+    // sum over (query, KV head) of ceil(tiles / L) fits the 256 CUs; a long sequence is cut into
+    // more ranges than a short one.  Batches that do not fit one round even at the longest range a
+    // work item may have run in several, longest items first.  Unused block tails of sequences that
+    // alias table slots ride in the device block table and are masked by the kernel.
     if (bf16 && G <= 32 && p.total_S > 0 && ctx->forced_row_blocks == 0 &&
         (ctx->forced_attn_kernel == 0 || ctx->forced_attn_kernel == 3) &&
         std::all_of(p.suffix_len.begin(), p.suffix_len.end(), [](int32_t s) { return s <= 1; })) {
-        int n_q = 0;
-        for (int i = 0; i < p.B; ++i) n_q += p.suffix_len[i] > 0 ? 1 : 0;
-        const int cap = std::max(1, (512 + n_q * c.n_kv_heads - 1) / (n_q * c.n_kv_heads));
+        constexpr int kCus = 256, kMinRange = 6;
+        auto tiles_of_q = [&](int i) { return (p.prefix_len[i] + KT - 1) / KT; };
+        auto items_at = [&](int L) {
+            int64_t n = 0;
+            for (int i = 0; i < p.B; ++i)
+                if (p.suffix_len[i] > 0) n += (int64_t)c.n_kv_heads * std::max(1, (tiles_of_q(i) + L - 1) / L);
+            return n;
+        };
+        int L = kAttnMaxTiles;
+        if (items_at(L) <= kCus) {                      // one round is possible: the shortest ranges that still fit it
+            int lo = kMinRange, hi = kAttnMaxTiles;     // items_at is non-increasing in L
+            while (lo < hi) {
+                const int mid = (lo + hi) / 2;
+                if (items_at(mid) <= kCus) hi = mid;
+                else lo = mid + 1;
+            }
+            L = lo;
+        }
         splits_of_q.assign(p.B, 1);
         p.max_splits = 1;
         items.clear();
@@ -210,8 +230,8 @@ inline bool plan_attention_pass(const tc_config &c, const PlanKnobs &knobs, Plan
         for (int i = 0; i < p.B; ++i) {
             if (p.suffix_len[i] <= 0) continue;
             const int P = p.prefix_len[i];
-            const int n_tiles = (P + KT - 1) / KT;
-            int ns = ctx->forced_splits > 0 ? ctx->forced_splits : std::min(cap, std::max(1, n_tiles / 6));
+            const int n_tiles = tiles_of_q(i);
+            int ns = ctx->forced_splits > 0 ? ctx->forced_splits : (n_tiles + L - 1) / L;
             ns = std::max(ns, (n_tiles + kAttnMaxTiles - 1) / kAttnMaxTiles);
             ns = std::max(1, std::min(ns, std::max(n_tiles, 1)));
             splits_of_q[i] = ns;
@@ -227,6 +247,9 @@ inline bool plan_attention_pass(const tc_config &c, const PlanKnobs &knobs, Plan
                     items.push_back(it);
                 }
         }
+        std::stable_sort(items.begin(), items.end(), [](const AttnItem &x, const AttnItem &y) {
+            return x.tile_end - x.tile_begin > y.tile_end - y.tile_begin;
+        });
         p.n_groups = 0;
         p.row_blocks = 1;
         p.n_items = (int32_t)items.size();

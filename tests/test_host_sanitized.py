@@ -170,6 +170,47 @@ def test_planner_paper_shapes(exe):
     _check_plan(info, items, 28, 4, dec)
 
 
+def test_decode_ranges_make_one_round_of_even_work_groups(exe):
+    """A decode step is planned for one round of work-groups on the 256 CUs, all about equally long:
+    the paper-shaped batches come out as at most 256 items, none longer than the shortest common
+    range length that fits, and a long sequence is cut into more ranges than a short one."""
+    import sys
+    sys.path.insert(0, ROOT)
+    from paper_2601_08743_amd import workloads as W
+    for name, Hq, Hkv in (("c3", 28, 4), ("c4", 32, 8), ("c2", 28, 4)):
+        wl = W.get(name)
+        PS = [(int(wl.table_len[q].sum()) + int(s), 1) for q, s in zip(wl.queries, wl.suffix_len)]
+        info, items = _plan(exe, Hq, Hkv, PS)
+        assert info["decode"] == 1
+        longest = _check_plan(info, items, Hq, Hkv, PS)
+        real = [it for it in items if it[0] >= 0]
+        tiles = [-(-P // 64) for P, _ in PS]
+        assert len(real) <= 256, (name, len(real))
+        # no shorter common range length would have fitted the 256 CUs (or the floor of six tiles was hit)
+        L = longest
+        fits = lambda L: sum(Hkv * max(1, -(-t // L)) for t in tiles) <= 256
+        assert fits(L) and (L <= 6 or not fits(L - 1)), (name, L)
+        per_q = {}
+        for q, kvh, m0, tb, te, split, ns in real:
+            per_q[q] = ns
+        order = sorted(range(len(tiles)), key=lambda i: tiles[i])
+        assert all(per_q[a] <= per_q[b] for a, b in zip(order, order[1:])), name
+        lens = [te - tb for _, _, _, tb, te, _, _ in real]
+        assert lens == sorted(lens, reverse=True), "longest items first"
+        print("%s decode: %d items, ranges of %d..%d key tiles, %d..%d ranges per sequence" % (
+            name, len(real), min(lens), max(lens), min(per_q.values()), max(per_q.values())))
+    # more (query, KV head) pairs than CUs: one range each, several rounds
+    PS = [(3000 + 17 * i, 1) for i in range(100)]
+    info, items = _plan(exe, 28, 4, PS)
+    assert info["decode"] == 1 and info["max_splits"] == 1 and sum(1 for it in items if it[0] >= 0) == 400
+    _check_plan(info, items, 28, 4, PS)
+    # a sequence longer than one item's block-id table is cut whatever the batch looks like
+    PS = [(64 * 700, 1)] + [(500, 1)] * 80
+    info, items = _plan(exe, 28, 4, PS)
+    _check_plan(info, items, 28, 4, PS)
+    assert info["max_splits"] == 3
+
+
 def test_planner_random_batches(exe):
     rng = np.random.default_rng(11)
     for _ in range(150):
