@@ -13,7 +13,8 @@
 //   f <k> b0 .. bk-1                release
 //   plan <dtype> <Hq> <Hkv> <D> <splits> <row_blocks> <kernel> <B> then B pairs "P S"
 //                                   -> "plan <n_items> <max_splits> <decode> <pingpong> <pipelined> <row_blocks> <ok>"
-//                                      and one line "i q kvh m0 tile_begin tile_end split n_splits" per item
+//                                      one line "i q kvh m0 tile_begin tile_end split n_splits group" per item,
+//                                      "groups <entries> <n_groups>" and one line "g kvh m0 n_splits cu S" per merge group
 //   trie <n> then n lines "<id> <len> tok..."; match <len> tok... -> "match <n> (id start)..."
 //   rerank <n_queries> <n_tables> <anchor> then per query "<k> ids..." -> "rerank order..."
 //   pipeline <n_queries> <capacity> <b_c> <b_m> <keep_pinned> <taper> then per query "<k> ids..."
@@ -111,7 +112,10 @@ int main()
             std::printf("plan %d %d %d %d %d %d %d\n", (int)items.size(), p.max_splits, p.decode ? 1 : 0,
                         p.pingpong ? 1 : 0, p.pipelined ? 1 : 0, p.row_blocks, ok ? 1 : 0);
             for (const AttnItem &it : items)
-                std::printf("i %d %d %d %d %d %d %d\n", it.q, it.kvh, it.m0, it.tile_begin, it.tile_end, it.split, it.n_splits);
+                std::printf("i %d %d %d %d %d %d %d %d\n", it.q, it.kvh, it.m0, it.tile_begin, it.tile_end, it.split, it.n_splits,
+                            it.q < 0 ? -1 : it.group);
+            std::printf("groups %d %d\n", (int)groups.size(), p.n_groups);
+            for (const MergeGroup &mg : groups) std::printf("g %d %d %d %d %d\n", mg.kvh, mg.m0, mg.n_splits, mg.cu, mg.S);
         } else if (cmd == "trie") {
             int n;
             std::cin >> n;

@@ -187,6 +187,8 @@ inline bool plan_attention_pass(const tc_config &c, const PlanKnobs &knobs, Plan
 {
     const PlanKnobs *ctx = &knobs;
     cap_bound = false;
+    items.clear();                                      // a second pass starts from nothing
+    groups.clear();
     const int G = c.n_q_heads / c.n_kv_heads;
     const bool bf16 = c.dtype == TC_BF16;
     const int KT = bf16 ? kAttnKeys : kF32Keys;

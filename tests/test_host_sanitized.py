@@ -93,9 +93,15 @@ def _plan(exe, Hq, Hkv, PS, splits=0, rb=0, kernel=0, dtype=1, D=128):
     lines = run(exe, "plan %d %d %d %d %d %d %d %d %s\n" % (dtype, Hq, Hkv, D, splits, rb, kernel, len(PS),
                                                           " ".join("%d %d" % ps for ps in PS)))
     head = list(map(int, lines[0].split()[1:]))
-    items = [tuple(map(int, l.split()[1:])) for l in lines[1:]]
+    rows = [tuple(map(int, l.split()[1:])) for l in lines[1:] if l.startswith("i ")]
+    items = [r[:7] for r in rows]
     assert head[0] == len(items)
-    return dict(max_splits=head[1], decode=head[2], pingpong=head[3], pipelined=head[4], row_blocks=head[5], ok=head[6]), items
+    ghead = [l for l in lines if l.startswith("groups ")][0].split()
+    groups = [tuple(map(int, l.split()[1:])) for l in lines if l.startswith("g ")]
+    info = dict(max_splits=head[1], decode=head[2], pingpong=head[3], pipelined=head[4], row_blocks=head[5], ok=head[6],
+                n_groups=int(ghead[2]), groups=groups, item_group=[r[7] for r in rows])
+    assert int(ghead[1]) == len(groups)
+    return info, items
 
 
 def _check_plan(info, items, Hq, Hkv, PS, dtype=1):
@@ -111,6 +117,16 @@ def _check_plan(info, items, Hq, Hkv, PS, dtype=1):
         rt = 4 if dtype == 0 else 128 * info["row_blocks"]
         unified = dtype == 0 or bool(info["pingpong"])
     cover = {}
+    if not info["decode"] and dtype == 1:
+        # the merge launch goes by the group table: one entry per (query, KV head, row tile), in the
+        # order of the items' group numbers, each with the partition count its items carry
+        assert len(info["groups"]) == info["n_groups"]
+        for (q, kvh, m0, tb, te, split, ns), grp in zip(items, info["item_group"]):
+            if q < 0:
+                continue
+            assert 0 <= grp < info["n_groups"]
+            g_kvh, g_m0, g_ns, g_cu, g_S = info["groups"][grp]
+            assert (g_kvh, g_m0, g_ns, g_S) == (kvh, m0, ns, PS[q][1]), (q, kvh, m0, ns, info["groups"][grp])
     for q, kvh, m0, tb, te, split, ns in items:
         if q < 0:
             continue
@@ -147,6 +163,15 @@ def test_planner_partition_limit_with_forced_splits(exe):
                   (splits, kernel, info["max_splits"], longest))
     info, items = _plan(exe, 28, 4, PS, splits=2, kernel=1)
     assert info["max_splits"] >= 3 and not info["pipelined"]
+    # longer than every kernel's table (1095 key tiles): the pipelined kernel is planned twice (for
+    # the general kernel's 256 tiles first, then for its own 1024), and the merge groups must be
+    # those of the second pass - they once were the first pass's, with five partitions each
+    PS = [(70001, 37), (100, 5)]
+    for kernel, splits, want in ((2, 1, 2), (2, 4, 4), (4, 1, 2), (1, 2, 5), (0, 0, None)):
+        info, items = _plan(exe, 4, 1, PS, splits=splits, kernel=kernel)
+        _check_plan(info, items, 4, 1, PS)
+        if want is not None:
+            assert info["max_splits"] == want, (kernel, splits, info["max_splits"])
 
 
 def test_planner_paper_shapes(exe):
