@@ -56,6 +56,41 @@ def test_noalloc_matches_allocating_entry_point():
             assert all(s > 1 for s, _, _ in res), "the case is meant to use split-KV partials"
 
 
+def test_noalloc_other_kernels():
+    """The same through the long-launch kernel (split, so with partials in the workspace) and for a
+    decode step (the decode kernels keep one partial per key range there)."""
+    import harness as H
+    base = W.CONFIGS["c2"]
+    big = W.scaled(base, n_layers=1, n_tables=8, tables_per_query=(6, 6), capacity=8)
+    res, err = _case(H, big, 4)
+    print("no-alloc long-launch kernel: (splits, identical, max diff) %s; vs checker %.3e" % (res, err), flush=True)
+    assert all(same for _, same, _ in res) and err <= 1e-2
+    # decode: prefill first, then one token per query through both entry points
+    cfg = W.scaled(base, n_layers=1, n_tables=8, tables_per_query=(3, 3), capacity=8, batch=3, suffix_len=(5, 40))
+    wl = W.make_workload(cfg)
+    P = np.array([int(wl.table_len[q].sum()) for q in wl.queries])
+    S = wl.suffix_len.astype(int)
+    dw = H.DeviceWorkload(wl, seq_blocks=int(sum(-(-(p + s + 1) // 16) for p, s in zip(P, S))) + 4)
+    bt, pl = dw.stitch(max_blocks=int(max(-(-(p + s + 1) // 16) for p, s in zip(P, S))) + 1)
+    dw.attn_layer(0, bt, pl)
+    cur = (P + S).astype(np.int32)
+    bt = dw.ctx.tc_grow_seqs(bt, cur + 1)
+    rng = np.random.default_rng(3)
+    q, k, v = (H.to_dev(W.f32_to_bf16_bits(rng.standard_normal(size=(cfg.batch, h, cfg.head_dim), dtype=np.float32)), cfg)
+               for h in (cfg.n_q_heads, cfg.n_kv_heads, cfg.n_kv_heads))
+    cu1, one = np.arange(cfg.batch + 1, dtype=np.int32), np.ones(cfg.batch, dtype=np.int32)
+    ref, got = torch.full_like(q, float("nan")), torch.full_like(q, float("nan"))
+    dw.ctx.tc_prefill_attn(0, q, k, v, ref, cu1, bt, cur, one, wl.sm_scale)
+    assert dw.ctx.tc_attn_kernel() == 3 and dw.ctx.tc_kv_splits() > 1
+    dw.ctx.tc_prefill_attn_noalloc(0, q, k, v, got, cu1, bt, cur, one, wl.sm_scale)
+    torch.cuda.synchronize()
+    assert dw.ctx.tc_attn_kernel() == 3
+    assert torch.isfinite(ref.float()).all()
+    assert torch.equal(ref.view(torch.int16), got.view(torch.int16))
+    dw.ctx.tc_release_seqs(bt)
+    dw.close()
+
+
 def test_noalloc_refuses_what_does_not_fit():
     """A batch whose partials exceed the fixed workspace is refused with TC_ERR_CAPACITY and
     enqueues nothing; the allocating entry point still serves it."""
