@@ -236,6 +236,33 @@ def test_random_batches_through_both_kernels(H, seed):
         float(np.abs(outs[1] - outs[2]).max())))
 
 
+@pytest.mark.parametrize("seed", [0, 3, 7])
+@pytest.mark.parametrize("splits", [0, 3])
+def test_random_batches_two_row_blocks_per_wave(H, seed, splits):
+    """The general kernel's optional work-group shape (tc_set_row_blocks(2): 256 rows, two row
+    blocks per wave) on ragged batches drawn like the ones above, unsplit and in three partitions."""
+    rng = np.random.default_rng(9000 + seed)
+    n_tables = 6
+    B = int(rng.integers(1, 6))
+    cfg = W.scaled(W.CONFIGS["c2"], name="rb2_%d" % seed, n_layers=1, n_tables=n_tables, batch=B, capacity=n_tables,
+                   seed=9000 + seed)
+    table_len = rng.integers(1, 401, size=n_tables).astype(np.int32)
+    queries = [rng.choice(n_tables, size=int(rng.integers(1, 5)), replace=False).astype(np.int32) for _ in range(B)]
+    suffix = rng.integers(1, 201, size=B).astype(np.int32)
+    wl = W.Workload(cfg, table_len, queries, suffix)
+    dw = H.DeviceWorkload(wl)
+    dw.ctx.tc_set_row_blocks(2)
+    dw.ctx.tc_set_kv_splits(splits)
+    bt, pl = dw.stitch()
+    res, out, qkv = _errs(H, dw, bt, pl, 0)
+    assert dw.ctx.tc_attn_kernel() == 0                 # neither of the one-row-block kernels: the 256-row shape
+    for i, (e, _) in res.items():
+        tol = TOL if int(pl[i]) >= 64 else max(TOL, 2.0 ** -7 * 4.7)
+        assert e <= tol, (seed, i, int(pl[i]), int(suffix[i]), e)
+    print("seed %d, %d partitions asked (%d made): worst %.2e" % (seed, splits, dw.ctx.tc_kv_splits(), max(e for e, _ in res.values())))
+    dw.close()
+
+
 @pytest.mark.parametrize("heads", [(8, 8), (32, 8), (8, 2), (28, 4)])
 def test_repeated_launches_are_bit_identical(H, heads):
     """The same launch on the same inputs must return the same bits every time, from the first
