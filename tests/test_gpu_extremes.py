@@ -197,3 +197,35 @@ def test_many_short_queries(H, kind):
     print("decode step of 400 queries in %d ranges at most: max-abs err %.2e" % (dw.ctx.tc_kv_splits(), worst))
     dw.ctx.tc_release_seqs(bt)
     dw.close()
+
+
+@pytest.mark.parametrize("kind,forced", [(0, 0), (4, 1), (2, 1), (1, 2)])
+def test_long_prefix_read_in_place(H, kind, forced):
+    """The long query again, its tables read in place (block-format slots, tc_stitch_alias): three
+    tables of 30 011, 39 989 and 7 tokens, so the sequence has unused block tails in the middle of
+    a partition, at a partition's end, and a table shorter than a block at the end of the prefix."""
+    cfg = W.scaled(W.CONFIGS["c2"], name="longa", n_layers=1, n_q_heads=4, n_kv_heads=1, n_tables=3, batch=2,
+                   tables_per_query=(1, 1), capacity=3, seed=31338)
+    wl = W.Workload(cfg, np.asarray([30011, 39989, 7], dtype=np.int32),
+                    [np.asarray([0, 1, 2], dtype=np.int32), np.asarray([2], dtype=np.int32)],
+                    np.asarray([37, 5], dtype=np.int32))
+    dw = H.DeviceWorkload(wl, slot_layout=1)
+    dw.ctx.tc_set_attn_kernel(kind)
+    dw.ctx.tc_set_kv_splits(forced)
+    bt, pl = dw.alias()
+    assert int(pl[0]) == 16 * (-(-30011 // 16) + -(-39989 // 16) + 1) and int(pl[1]) == 16
+    out, qkv = dw.attn_layer(0, bt, pl)
+    got = H.out_to_f64(out, wl.cfg)
+    ref = H.oracle_attn_layer(wl, dw.tables_np, 0, qkv)
+    worst = 0.0
+    for i, r in ref.items():
+        sl = slice(int(wl.cu_seqlens[i]), int(wl.cu_seqlens[i + 1]))
+        assert np.isfinite(got[sl]).all()
+        e = float(np.abs(got[sl] - r).max())
+        # the second query sees 7 + a few keys: outputs as large as single values
+        assert e <= (TOL if i == 0 else max(TOL, 2.0 ** -8 * 4.7)), (i, e)
+        worst = max(worst, e)
+    print("in place, kernel %d (chosen %d), %d partitions asked, %d made: max-abs err %.2e" % (
+        kind, dw.ctx.tc_attn_kernel(), forced, dw.ctx.tc_kv_splits(), worst))
+    dw.ctx.tc_release_seqs(bt)
+    dw.close()
