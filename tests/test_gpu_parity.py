@@ -266,21 +266,28 @@ def test_replacement_trace_matches_app_a_models(H):
         dw.close()
 
 
-def test_layer_loop_replayed_as_a_graph_matches_eager(H):
+@pytest.mark.parametrize("kind,entry", [(0, "tc_prefill_attn"), (4, "tc_prefill_attn"), (1, "tc_prefill_attn"),
+                                        (0, "tc_prefill_attn_noalloc"), (4, "tc_prefill_attn_noalloc")])
+def test_layer_loop_replayed_as_a_graph_matches_eager(H, kind, entry):
     """The per-layer calls captured into a HIP graph (kernel launches only: no memset nodes) and
     replayed several times, with eager stitches, releases and synchronisations in between, give
-    bit-identical outputs to the eager calls every time."""
+    bit-identical outputs to the eager calls every time - through the pipelined kernel with its
+    merge launch (the automatic choice here), the long-launch kernel with its append launch, the
+    general kernel, and through the entry point that allocates nothing, which exists for callers
+    like this one (the batch's plan is uploaded by the eager call before the capture)."""
     cfg = W.scaled(W.CONFIGS["c2"], n_layers=3, n_tables=8, tables_per_query=(6, 6), capacity=8)
     wl = W.make_workload(cfg)
     dw = H.DeviceWorkload(wl)
+    dw.ctx.tc_set_attn_kernel(kind)
     stream = torch.cuda.Stream()
     qkv = [tuple(H.to_dev(x, cfg) for x in wl.suffix_qkv(l)) for l in range(3)]
     outs = [torch.zeros_like(qkv[l][0]) for l in range(3)]
+    call = getattr(dw.ctx, entry)
 
     def layers(bt, pl):
         for l in range(3):
             q, k, v = qkv[l]
-            dw.ctx.tc_prefill_attn(l, q, k, v, outs[l], wl.cu_seqlens, bt, pl, wl.suffix_len, wl.sm_scale, stream)
+            call(l, q, k, v, outs[l], wl.cu_seqlens, bt, pl, wl.suffix_len, wl.sm_scale, stream)
 
     bt, pl = dw.stitch(stream=stream)
     layers(bt, pl)
@@ -301,4 +308,8 @@ def test_layer_loop_replayed_as_a_graph_matches_eager(H):
         torch.cuda.synchronize()
         for l in range(3):
             assert torch.equal(outs[l], eager[l]), (rep, l)
+    assert dw.ctx.tc_attn_kernel() == (kind or 2) and dw.ctx.tc_kv_splits() > 1
+    ref = H.oracle_attn_layer(wl, dw.tables_np, 2, wl.suffix_qkv(2))
+    got = H.out_to_f64(outs[2], cfg)
+    assert max(float(np.abs(got[int(wl.cu_seqlens[i]):int(wl.cu_seqlens[i + 1])] - r).max()) for i, r in ref.items()) <= 1e-2
     dw.close()
