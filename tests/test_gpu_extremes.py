@@ -59,6 +59,14 @@ def test_prefill_over_a_prefix_longer_than_the_block_id_tables(H, setup, kind, f
     print("kernel %d (chosen %d), %d partitions asked, %d made: max-abs err %.2e" % (
         kind, dw.ctx.tc_attn_kernel(), forced, splits, worst))
     assert worst <= TOL
+    if kind == 0:                                       # the gather and the append, bit for bit
+        for i in range(2):
+            n = int(pl[i]) + int(wl.suffix_len[i])
+            kk, vv = dw.ctx.tc_read_seq_kv(0, bt[i, :-(-n // 16)], n, np.uint16)
+            ks, vs = H.oracle_sequences(wl, dw.tables_np, 0, i)
+            sl = slice(int(wl.cu_seqlens[i]), int(wl.cu_seqlens[i + 1]))
+            np.testing.assert_array_equal(kk.view(np.uint8), np.concatenate([ks, qkv[1][sl]]).view(np.uint8))
+            np.testing.assert_array_equal(vv.view(np.uint8), np.concatenate([vs, qkv[2][sl]]).view(np.uint8))
     dw.ctx.tc_release_seqs(bt)
     dw.close()
 
