@@ -136,7 +136,7 @@ def test_fixed_reference_extremes(H, profile):
     wl = _SteeredScores(cfg, np.asarray([n_tok], dtype=np.int32), [np.asarray([0], dtype=np.int32)],
                         np.asarray([48], dtype=np.int32), {0: level.astype(np.float32)})
     bad = []
-    for kind, splits in ((2, 1), (2, 2), (1, 1)):
+    for kind, splits in ((2, 1), (2, 2), (1, 1), (4, 1), (4, 3)):
         dw = H.DeviceWorkload(wl)
         dw.ctx.tc_set_attn_kernel(kind)
         dw.ctx.tc_set_kv_splits(splits)
@@ -151,6 +151,56 @@ def test_fixed_reference_extremes(H, profile):
             bad.append((profile, kind, splits, e))
         dw.close()
     assert not bad, bad
+
+
+@pytest.mark.parametrize("profile", ["rising_overflow", "falling", "spike_late"])
+def test_decode_step_over_extreme_scores(H, profile):
+    """The decode kernels under the same profiles (their running maximum is raised lazily, by
+    steps of at least 2^8): one new token over 640 steered keys cut into key ranges, so the ranges'
+    references differ by hundreds of log2 units when they are combined."""
+    import oracle
+    n_tok = 640
+    t = np.arange(n_tok, dtype=np.float64)
+    if profile == "rising_overflow":
+        level = 0.05 + 40.0 * t / n_tok
+    elif profile == "falling":
+        level = 40.0 * (1.0 - t / n_tok) + 0.01
+    else:
+        level = np.full(n_tok, 0.05)
+        level[500] = 45.0
+    cfg = W.scaled(W.CONFIGS["c2"], name="steerd", n_layers=1, n_tables=1, batch=1, tables_per_query=(1, 1),
+                   capacity=1, seed=778)
+    wl = _SteeredScores(cfg, np.asarray([n_tok], dtype=np.int32), [np.asarray([0], dtype=np.int32)],
+                        np.asarray([3], dtype=np.int32), {0: level.astype(np.float32)})
+    c = wl.cfg
+    for splits in (0, 1, 5):
+        dw = H.DeviceWorkload(wl, seq_blocks=-(-(n_tok + 4) // 16) + 4)
+        dw.ctx.tc_set_kv_splits(splits)
+        bt, pl = dw.stitch(max_blocks=-(-(n_tok + 4) // 16) + 1)
+        _, qkv = dw.attn_layer(0, bt, pl)
+        cur = np.asarray([n_tok + 3], dtype=np.int32)
+        bt = dw.ctx.tc_grow_seqs(bt, cur + 1)
+        rng = np.random.default_rng(12)
+        q = W.f32_to_bf16_bits((np.abs(rng.standard_normal(size=(1, c.n_q_heads, c.head_dim))) + 0.5).astype(np.float32))
+        k, v = (W.f32_to_bf16_bits(rng.standard_normal(size=(1, c.n_kv_heads, c.head_dim), dtype=np.float32)) for _ in range(2))
+        dq, dk, dv = H.to_dev(q, c), H.to_dev(k, c), H.to_dev(v, c)
+        out = torch.full_like(dq, float("nan"))
+        dw.ctx.tc_prefill_attn(0, dq, dk, dv, out, np.asarray([0, 1], dtype=np.int32), bt, cur, np.asarray([1], dtype=np.int32),
+                               wl.sm_scale, None)
+        torch.cuda.synchronize()
+        assert dw.ctx.tc_attn_kernel() == 3
+        ks, vs = H.oracle_sequences(wl, dw.tables_np, 0, 0)
+        K, V = np.concatenate([ks, qkv[1]]), np.concatenate([vs, qkv[2]])
+        ref = oracle.prefill_attn(W.storage_to_f64(q, "bf16"), W.storage_to_f64(K, "bf16"), W.storage_to_f64(V, "bf16"),
+                                  W.storage_to_f64(k, "bf16"), W.storage_to_f64(v, "bf16"), wl.sm_scale)
+        got = H.out_to_f64(out, c)
+        assert np.isfinite(got).all(), (profile, splits)
+        vmax = max(float(np.abs(W.bf16_bits_to_f32(V)).max()), float(np.abs(W.bf16_bits_to_f32(v)).max()))
+        e = float(np.abs(got - ref).max())
+        print("%s, decode, %d ranges asked (%d made): max-abs %.3e (max |v| %.2f)" % (profile, splits, dw.ctx.tc_kv_splits(), e, vmax))
+        assert e <= max(TOL, 3.0 * 2.0 ** -9 * vmax), (profile, splits, e)
+        dw.ctx.tc_release_seqs(bt)
+        dw.close()
 
 
 class _CountingValues(W.Workload):
