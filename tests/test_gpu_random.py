@@ -24,10 +24,15 @@ def H():
     return harness
 
 
-def _case(H, seed):
+def _case(H, seed, long_tokens=0):
+    """long_tokens > 0: table 0 gets that many tokens and the first query reads it (few heads, so the
+    checker stays fast): key ranges of hundreds of tiles, where the kernels' block-id tables decide
+    the number of partitions."""
     from paper_2601_08743_amd import binding as B
     rng = np.random.default_rng(seed)
     hkv, G = int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 4, 5, 7, 8]))
+    if long_tokens:
+        hkv, G = int(rng.choice([1, 2])), int(rng.choice([1, 4, 7]))
     hq = hkv * G
     nt, batch = int(rng.integers(2, 9)), int(rng.integers(1, 6))
     lo, hi = sorted((int(rng.choice([1, 20, 150])), int(rng.choice([40, 300, 700]))))
@@ -36,6 +41,13 @@ def _case(H, seed):
                            choice="uniform", suffix_len=(0, int(rng.choice([1, 17, 90, 200]))), capacity=nt,
                            seed=1000 + seed)
     wl = W.make_workload(cfg)
+    if long_tokens:
+        tl = wl.table_len.copy()
+        tl[0] = long_tokens
+        queries = [np.asarray(q, dtype=np.int32) for q in wl.queries]
+        if 0 not in queries[0].tolist():
+            queries[0] = np.concatenate([queries[0][:2], np.asarray([0], dtype=np.int32)])
+        wl = W.Workload(cfg, tl, queries, wl.suffix_len)
     alias, kind = bool(rng.integers(0, 2)), int(rng.choice([0, 1, 2, 4]))
     splits = int(rng.choice([0, 0, 1, 2, 3, 5]))
     S = wl.suffix_len.astype(int)
@@ -89,6 +101,15 @@ def _case(H, seed):
         assert np.isfinite(god[i]).all() and e <= 1e-2, ("decode step, kernel %d, query %d: %g; " % (dkind, i, e)) + tag
     dw.ctx.tc_release_seqs(bt)
     dw.close()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_batches_with_a_long_table(H, seed):
+    """The same draws with one table of 17 000 .. 45 000 tokens in the first query: more key tiles
+    than the general kernel's block-id table holds (256), so forced partition counts are raised, the
+    pipelined kernel's batch is planned twice, and the merge runs over the replanned groups."""
+    rng = np.random.default_rng(31 + seed)
+    _case(H, 9000 + seed, long_tokens=int(rng.integers(17000, 45001)))
 
 
 @pytest.mark.parametrize("block", range(4))
