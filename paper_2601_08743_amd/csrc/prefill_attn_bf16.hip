@@ -525,20 +525,22 @@ constexpr int kFastV = kFastBufs * kFastKTile;            // V buffers follow th
 constexpr int kFastBid = kFastV + kFastBufs * kVTile;     // block ids of the item's key range (up to kPipeMaxTiles tiles)
 constexpr int kLdsBytesPipe = kFastBid + kPipeMaxTiles * 4 * 4;
 static_assert(kLdsBytesPipe <= 160 * 1024 && 2 * kStage <= kFastBid, "LDS layout");
-// Shorter runs take the general loop.  Runs of exactly three tiles are excluded on evidence, not
-// on a found cause: on some machines their first launches in a process returned wrong rows
-// (launch-dependent results for identical inputs, gone when the run went through the general loop),
-// while runs of four and more have never differed between launches.  What has been ruled out on the
-// CPU: the load schedule (a host model of the issue order, the vmcnt waits and the buffer reuse holds
-// for every run length from 3 up: tests/test_pipe_schedule_model.py; a run of three reuses no LDS
-// buffer at all and waits at least as long as longer runs do); reads of score registers this launch
-// never wrote (same test: every register the unconditional vector work touches was written by the
-// prime step or an earlier QK, also in the two steps without a QK); compiler-made copies next to
-// the hand-placed matrix instructions on any path of the control flow, the zero-iteration steady
-// loop of a three-tile run included, and a compiler value living in M0 across the LDS loads
-// (tests/test_kernel_schedule.py, on the emitted assembly).  The cause is open; the path stays off
-// for three tiles.  Little is lost: runs this short are mostly the pipeline's fill and drain (a
-// two-tile run was measured slower than the general loop).
+// Shorter runs take the general loop: they are mostly the pipeline's fill and drain (two tiles were
+// measured slower than the general loop, three within a few percent of it either way).
+// History of this limit.  An earlier build returned launch-dependent rows for runs of exactly three
+// tiles and the limit was raised to four before the cause was known.  The cause, found since by
+// building that source again with the limit at three (wrong in 117 of 120 fresh contexts): under
+// register pressure the compiler kept a Q fragment in accumulation registers and reloaded it
+// (v_accvgpr_read) directly in front of a hand-placed QK matrix instruction.  A matrix instruction
+// must not read a register a vector instruction wrote less than two wait states earlier; the
+// compiler keeps that rule for its own matrix instructions and cannot for inline assembly.  Five
+// idle slots in front of every hand-placed matrix instruction made that build right (0 of 120); so
+// did naming the score registers in the step's closing fence (which this source does), because it
+// changed the allocation and the reload went away.  That the rule holds in the emitted code -
+// no vector write to a source of a hand-placed matrix instruction in the two wait states before
+// it - is now checked by tests/test_kernel_schedule.py, which fails on that earlier source; with
+// it, this source runs three-tile runs correctly when the limit is lowered (160 + 200 fresh
+// contexts, bits equal across launches).
 constexpr int kFastMinTiles = 4;
 
 #define TC_SB() __builtin_amdgcn_sched_barrier(0)

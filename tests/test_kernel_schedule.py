@@ -132,6 +132,60 @@ def test_pipelined_steps_keep_their_slot_structure(instructions):
     assert one >= 2 * 31
 
 
+def test_no_vector_write_right_in_front_of_a_hand_placed_matrix_instruction():
+    """A matrix instruction must not read a register that a vector instruction wrote less than 2
+    wait states earlier; the compiler keeps that rule for its own matrix instructions and cannot
+    for those inside inline assembly.  The hand-written steps keep every such pair far apart, but
+    the compiler's own moves can land there: a build of this kernel once reloaded a Q fragment from
+    accumulation registers (v_accvgpr_read, a spill under register pressure) directly in front of
+    the first QK instruction of a key-tile half, and short pipelined runs returned launch-dependent
+    rows; two idle slots in front of the matrix instructions made them right again.  Checked on the
+    emitted code of all kernels in the file: every matrix instruction inside an assembly statement,
+    its three source operands, the two wait states in front of it."""
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not available")
+    with tempfile.TemporaryDirectory() as d:
+        out = os.path.join(d, "k.s")
+        subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                               "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", os.path.dirname(SRC),
+                               "-S", "--cuda-device-only", SRC, "-o", out], stderr=subprocess.DEVNULL)
+        raw = open(out).read().splitlines()
+    ins, in_asm = [], False                     # (text, inside an assembly statement)
+    for l in raw:
+        t = l.strip()
+        if t.startswith(";;#ASMSTART"):
+            in_asm = True
+            continue
+        if t.startswith(";;#ASMEND"):
+            in_asm = False
+            continue
+        t = t.split(";")[0].strip()
+        if not t or t.startswith(".") or t.endswith(":"):
+            continue
+        ins.append((t, in_asm))
+    n = 0
+    for i, (t, in_asm) in enumerate(ins):
+        if not (in_asm and t.startswith("v_mfma")):
+            continue
+        n += 1
+        src = set()
+        for part in t.split(None, 1)[1].split(",")[1:]:
+            src |= _regs(part)
+        gap, j = 0, i - 1
+        while j >= 0 and gap < 2:
+            op, _, rest = ins[j][0].partition(" ")
+            if op == "s_nop":
+                gap += int(rest) + 1
+            else:
+                if op.startswith("v_") and not op.startswith("v_mfma") and not op.startswith("v_cmp"):
+                    assert not (_regs(rest.split(",")[0]) & src), "'%s' writes a source of '%s' %d wait states ahead of it" % (
+                        ins[j][0], t, gap)
+                gap += 1
+            j -= 1
+    assert n >= 32 * 5
+    print("hand-placed matrix instructions checked: %d" % n)
+
+
 def _sregs(text):
     out = set()
     for m in re.finditer(r"\bs\[(\d+):(\d+)\]|\bs(\d+)\b", text):
